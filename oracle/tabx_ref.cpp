@@ -1,0 +1,457 @@
+/*
+ * tabx_ref.cpp -- CPU checker for the TABX batched environment step.
+ *
+ * TEST INFRASTRUCTURE ONLY (see tabx_ref.h).  One env at a time, one unit at a
+ * time, one pair at a time; nothing is blocked, fused or reordered.  Build with
+ *   g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC
+ * so that every float expression below is evaluated exactly as written.
+ *
+ * Stage order follows App. A "Interaction Dynamics": (1) physics update,
+ * (2) action application (movement / rotation / combat), (3) post-processing
+ * (zone effects, alive flags, reward, termination).
+ */
+#include "tabx_ref.h"
+
+#include <cmath>
+#include <vector>
+
+namespace {
+
+enum { ACT_NOOP = 0, ACT_XP = 1, ACT_YP = 2, ACT_XM = 3, ACT_YM = 4,
+       ACT_ATTACK = 5, ACT_ROT_L = 6, ACT_ROT_R = 7 };
+enum { ZONE_OPEN = 0, ZONE_LAVA = 1, ZONE_BUSH = 2, ZONE_SWAMP = 3 };
+
+const float TWO_PI_F = 6.28318530717958647692f;
+
+/* ---- sine / cosine of a heading in [0, 2*pi] -------------------------------
+ * Quadrant reduction n = trunc(theta * 2/pi + 1/2), remainder by a two-term
+ * split of pi/2, then Taylor polynomials of degree 9 (sin) and 8 (cos) in
+ * Horner form with explicit fused multiply-adds.  |r| <= pi/4 so the series
+ * remainders are below 3e-8.  No libm transcendental is involved, so the
+ * value is a fixed function of the float input on any IEEE machine. */
+void sincos_spec(float theta, float *s_out, float *c_out)
+{
+    const float TWO_OVER_PI = 0.63661977236758134308f;
+    const float PIO2_HI = 1.57079637050628662109375f;      /* float(pi/2)      */
+    const float PIO2_LO = -4.37113882867379435e-8f;        /* pi/2 - PIO2_HI   */
+    const float S1 = -1.0f / 6.0f, S2 = 1.0f / 120.0f, S3 = -1.0f / 5040.0f,
+                S4 = 1.0f / 362880.0f;
+    const float C1 = -0.5f, C2 = 1.0f / 24.0f, C3 = -1.0f / 720.0f,
+                C4 = 1.0f / 40320.0f;
+
+    float q = theta * TWO_OVER_PI;
+    q = q + 0.5f;
+    int   n  = (int)q;
+    float fn = (float)n;
+    float r  = std::fmaf(-fn, PIO2_HI, theta);
+    r        = std::fmaf(-fn, PIO2_LO, r);
+    float r2 = r * r;
+
+    float ps = std::fmaf(r2, S4, S3);
+    ps       = std::fmaf(r2, ps, S2);
+    ps       = std::fmaf(r2, ps, S1);
+    float r3 = r * r2;
+    float sr = std::fmaf(r3, ps, r);
+
+    float pc = std::fmaf(r2, C4, C3);
+    pc       = std::fmaf(r2, pc, C2);
+    pc       = std::fmaf(r2, pc, C1);
+    float cr = std::fmaf(r2, pc, 1.0f);
+
+    switch (n & 3) {
+    case 0:  *s_out = sr;  *c_out = cr;  break;
+    case 1:  *s_out = cr;  *c_out = -sr; break;
+    case 2:  *s_out = -sr; *c_out = -cr; break;
+    default: *s_out = -cr; *c_out = sr;  break;
+    }
+}
+
+inline float clampf(float v, float lo, float hi)
+{
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+
+/* Terrain cell code under a position (0 when there is no terrain). */
+int cell_code(const RefParams &P, const RefScenario &S, int e, float x, float y)
+{
+    if (!S.terrain || P.grid_w <= 0 || P.grid_h <= 0) return 0;
+    int cx = (int)(x / P.cell_size);
+    int cy = (int)(y / P.cell_size);
+    if (cx > P.grid_w - 1) cx = P.grid_w - 1;
+    if (cy > P.grid_h - 1) cy = P.grid_h - 1;
+    if (cx < 0) cx = 0;
+    if (cy < 0) cy = 0;
+    return (int)S.terrain[((long)e * P.grid_h + cy) * P.grid_w + cx];
+}
+
+/* Mean health ratio of one team over its enabled units, ascending index
+ * (the bracketed means of Eq. 1).  A team with no enabled unit has ratio 0. */
+float team_ratio(const RefParams &P, const RefScenario &S, const RefState &st,
+                 int e, int team)
+{
+    const int N = P.num_units, b = e * N;
+    float sum = 0.0f;
+    int   cnt = 0;
+    for (int u = 0; u < N; ++u) {
+        if (!S.enabled[b + u] || S.team[b + u] != team) continue;
+        sum = sum + st.hp[b + u] / S.hmax[b + u];
+        cnt += 1;
+    }
+    return cnt > 0 ? sum / (float)cnt : 0.0f;
+}
+
+void reset_env(const RefParams &P, const RefScenario &S, RefState &st, int e)
+{
+    const int N = P.num_units, b = e * N;
+    for (int u = 0; u < N; ++u) {
+        const int k = b + u;
+        st.x[k] = S.init_x[k];
+        st.y[k] = S.init_y[k];
+        st.theta[k] = S.init_theta[k];
+        st.vx[k] = 0.0f;
+        st.vy[k] = 0.0f;
+        st.hp[k] = S.enabled[k] ? S.hmax[k] : 0.0f;
+        st.cd[k] = 0.0f;
+        st.reveal[k] = 0.0f;
+        st.alive[k] = S.enabled[k] ? 1 : 0;
+        const int zone = cell_code(P, S, e, st.x[k], st.y[k]) & 3;
+        st.cur_speed[k] = (zone == ZONE_SWAMP) ? S.speed[k] * P.swamp_mult : S.speed[k];
+    }
+    st.t[e] = 0;
+    st.phi_prev[e] = team_ratio(P, S, st, e, 0) - team_ratio(P, S, st, e, 1);
+}
+
+/* Hurtbox test (App. A "Attack range geometry"): the attacker's forward
+ * rectangle x in [0, L], y in [-hw, hw] (attacker frame) against the target's
+ * body circle; closed boundary.  Returns the overlap flag, the squared
+ * centre distance in *d2 and, if margin is given, |gap - r_j| in doubles. */
+bool hurtbox_hit(float xi, float yi, float ci, float si, float L, float hw,
+                 float xj, float yj, float rj, float *d2, double *margin)
+{
+    float dx = xj - xi;
+    float dy = yj - yi;
+    float lx = (dx * ci) + (dy * si);
+    float ly = (dy * ci) - (dx * si);
+    float ex = lx - clampf(lx, 0.0f, L);
+    float ey = ly - clampf(ly, -hw, hw);
+    float g2 = (ex * ex) + (ey * ey);
+    *d2 = (dx * dx) + (dy * dy);
+    if (margin) *margin = std::fabs(std::sqrt((double)g2) - (double)rj);
+    return g2 <= rj * rj;
+}
+
+/* Role filter: damage dealers reach enemies only, healers (negative damage)
+ * allies only. */
+inline bool role_allows(float dmg_i, int team_i, int team_j)
+{
+    return dmg_i < 0.0f ? (team_i == team_j) : (team_i != team_j);
+}
+
+void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
+              const unsigned char *act, float *rewards, unsigned char *dones,
+              double *min_margin)
+{
+    const int N = P.num_units, b = e * N;
+    std::vector<unsigned char> alive0(N);
+    std::vector<float> bdmg(N, 0.0f), c(N), s(N);
+    std::vector<int> target(N, -1);
+    std::vector<unsigned char> landed(N, 0);
+
+    for (int u = 0; u < N; ++u) alive0[u] = st.alive[b + u];
+
+    /* ---- stage 1: physics --------------------------------------------------- */
+    for (int u = 0; u < N; ++u) {
+        const int k = b + u;
+        if (!S.enabled[k]) continue;
+        float v = st.cd[k] - P.dt;
+        st.cd[k] = v > 0.0f ? v : 0.0f;
+        v = st.reveal[k] - P.dt;
+        st.reveal[k] = v > 0.0f ? v : 0.0f;
+        if (!alive0[u]) continue;
+        float x = st.x[k] + st.vx[k] * P.dt;
+        float y = st.y[k] + st.vy[k] * P.dt;
+        bool oob = (x < 0.0f) || (x > P.map_w) || (y < 0.0f) || (y > P.map_h);
+        if (oob) bdmg[u] = (P.boundary_frac * S.hmax[k]) * P.dt;
+        st.x[k] = clampf(x, 0.0f, P.map_w);
+        st.y[k] = clampf(y, 0.0f, P.map_h);
+    }
+
+    /* ---- stage 2: actions ---------------------------------------------------- */
+    const float dtheta = P.turn_rate * P.dt;
+    for (int u = 0; u < N; ++u) {
+        const int k = b + u;
+        st.vx[k] = 0.0f;
+        st.vy[k] = 0.0f;
+        if (alive0[u]) {
+            const int a = act[k];
+            const float sp = st.cur_speed[k];
+            if (a == ACT_XP) st.vx[k] = sp;
+            else if (a == ACT_YP) st.vy[k] = sp;
+            else if (a == ACT_XM) st.vx[k] = -sp;
+            else if (a == ACT_YM) st.vy[k] = -sp;
+            else if (a == ACT_ROT_L) {
+                float th = st.theta[k] + dtheta;
+                if (th >= TWO_PI_F) th = th - TWO_PI_F;
+                st.theta[k] = th;
+            } else if (a == ACT_ROT_R) {
+                float th = st.theta[k] - dtheta;
+                if (th < 0.0f) th = th + TWO_PI_F;
+                st.theta[k] = th;
+            }
+        }
+        sincos_spec(st.theta[k], &s[u], &c[u]);
+    }
+
+    /* attackable matrix row by row, closest valid target (ties: lowest index) */
+    for (int i = 0; i < N; ++i) {
+        if (!alive0[i]) continue;
+        const int ki = b + i;
+        float best = 0.0f;
+        for (int j = 0; j < N; ++j) {
+            if (j == i || !alive0[j]) continue;
+            const int kj = b + j;
+            if (!role_allows(S.dmg[ki], S.team[ki], S.team[kj])) continue;
+            float d2;
+            double m;
+            bool hit = hurtbox_hit(st.x[ki], st.y[ki], c[i], s[i], S.range[ki],
+                                   S.hurt_halfwidth[ki], st.x[kj], st.y[kj],
+                                   S.radius[kj], &d2, min_margin ? &m : nullptr);
+            if (min_margin && m < min_margin[e]) min_margin[e] = m;
+            if (hit && (target[i] < 0 || d2 < best)) {
+                target[i] = j;
+                best = d2;
+            }
+        }
+    }
+
+    /* eligibility: chose the combat action with the cooldown elapsed; the
+     * cooldown restarts whether or not a target is in the hurtbox */
+    for (int i = 0; i < N; ++i) {
+        const int ki = b + i;
+        bool elig = alive0[i] && act[ki] == ACT_ATTACK && st.cd[ki] <= 0.0f;
+        if (elig) st.cd[ki] = S.cooldown[ki];
+        landed[i] = (elig && target[i] >= 0) ? 1 : 0;
+    }
+
+    /* victim-side application: every victim sums the damage (heals negative)
+     * of the attackers that designated it, ascending attacker index, then
+     * subtracts once together with the boundary penalty and clamps */
+    for (int j = 0; j < N; ++j) {
+        if (!alive0[j]) continue;
+        const int kj = b + j;
+        float acc = 0.0f;
+        for (int i = 0; i < N; ++i)
+            if (landed[i] && target[i] == j) acc = acc + S.dmg[b + i];
+        float h = (st.hp[kj] - acc) - bdmg[j];
+        st.hp[kj] = clampf(h, 0.0f, S.hmax[kj]);
+    }
+    /* combat reveal (bush rule): a landed damaging attack exposes both ends */
+    for (int i = 0; i < N; ++i) {
+        if (landed[i] && S.dmg[b + i] > 0.0f) {
+            st.reveal[b + i] = P.reveal_time;
+            st.reveal[b + target[i]] = P.reveal_time;
+        }
+    }
+
+    /* ---- stage 3: zone effects, alive flags, reward, termination -------------- */
+    const float lava_step = P.lava_dps * P.dt;
+    for (int u = 0; u < N; ++u) {
+        const int k = b + u;
+        if (!S.enabled[k]) { st.alive[k] = 0; continue; }
+        const int zone = cell_code(P, S, e, st.x[k], st.y[k]) & 3;
+        if (alive0[u] && zone == ZONE_LAVA) {
+            float h = st.hp[k] - lava_step;
+            st.hp[k] = h > 0.0f ? h : 0.0f;
+        }
+        st.cur_speed[k] = (zone == ZONE_SWAMP) ? S.speed[k] * P.swamp_mult : S.speed[k];
+        st.alive[k] = st.hp[k] > 0.0f ? 1 : 0;
+    }
+    st.t[e] += 1;
+
+    const float ratio0 = team_ratio(P, S, st, e, 0);
+    const float ratio1 = team_ratio(P, S, st, e, 1);
+    const float phi = ratio0 - ratio1;
+    const float dense = phi - st.phi_prev[e];
+    float r0 = dense, r1 = -dense;
+
+    int alive_cnt[2] = {0, 0};
+    for (int u = 0; u < N; ++u)
+        if (st.alive[b + u]) alive_cnt[S.team[b + u] ? 1 : 0] += 1;
+    const bool done = alive_cnt[0] == 0 || alive_cnt[1] == 0 || st.t[e] >= P.max_steps;
+    if (done) {
+        /* one rule for wipe-out and truncation: the allies win only with a
+         * strictly larger mean health ratio (equal ratios: allies lose) */
+        const bool ally_win = ratio0 > ratio1;
+        r0 = r0 + (ally_win ? 1.0f : -1.0f);
+        r1 = r1 + (ally_win ? -1.0f : 1.0f);
+    }
+    for (int u = 0; u < N; ++u) {
+        const int k = b + u;
+        rewards[k] = S.enabled[k] ? (S.team[k] ? r1 : r0) : 0.0f;
+    }
+    dones[e] = done ? 1 : 0;
+    if (done) reset_env(P, S, st, e);
+    else st.phi_prev[e] = phi;
+}
+
+void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, int e,
+                 float *obs, unsigned long long *vis_mask, unsigned char *action_mask,
+                 double *min_margin)
+{
+    const int N = P.num_units, Z = P.max_zones, b = e * N;
+    const int D = tabx_ref_obs_dim(&P);
+    const int words = (N + 63) / 64;
+    std::vector<float> c(N), s(N);
+    std::vector<int> code(N);
+    for (int u = 0; u < N; ++u) {
+        sincos_spec(st.theta[b + u], &s[u], &c[u]);
+        code[u] = cell_code(P, S, e, st.x[b + u], st.y[b + u]);
+    }
+
+    for (int i = 0; i < N; ++i) {
+        const int ki = b + i;
+        float *row = obs + ((long)ki) * D;
+        for (int o = 0; o < D; ++o) row[o] = 0.0f;
+        if (vis_mask)
+            for (int w = 0; w < words; ++w) vis_mask[(long)ki * words + w] = 0ull;
+        if (action_mask)
+            action_mask[ki] = (st.alive[ki] && st.cd[ki] <= 0.0f) ? 1 : 0;
+        if (!S.enabled[ki]) continue;
+
+        /* own block */
+        row[0] = st.hp[ki];
+        row[1] = st.hp[ki] / S.hmax[ki];
+        row[2] = st.x[ki];
+        row[3] = st.y[ki];
+        row[4] = st.theta[ki];
+        row[5] = S.range[ki];
+        row[6] = S.dmg[ki];
+        row[7] = st.cd[ki];
+        row[8] = S.cooldown[ki] != 0.0f ? st.cd[ki] / S.cooldown[ki] : 0.0f;
+        row[9] = S.radius[ki];
+        row[10] = S.mass[ki];
+        row[11] = S.sight_angle[ki];
+        row[12] = st.alive[ki] ? 1.0f : 0.0f;
+        row[13] = st.cur_speed[ki];
+        row[14] = (float)(code[i] & 3);
+
+        /* other units, ascending index, self skipped */
+        int slot = 0;
+        for (int j = 0; j < N; ++j) {
+            if (j == i) continue;
+            const int kj = b + j;
+            float *o = row + 15 + 16 * slot;
+            slot += 1;
+            if (!st.alive[ki] || !st.alive[kj]) continue;
+
+            float dx = st.x[kj] - st.x[ki];
+            float dy = st.y[kj] - st.y[ki];
+            float d2 = (dx * dx) + (dy * dy);
+            float R = S.sight_range[ki];
+            bool in_range = d2 <= R * R;
+            float dot = (dx * c[i]) + (dy * s[i]);
+            float dist = std::sqrt(d2);
+            bool in_cone = (d2 == 0.0f) || (dot >= S.sight_cos_half[ki] * dist);
+            if (min_margin) {
+                double m = std::fabs((double)dist - (double)R);
+                if (m < min_margin[e]) min_margin[e] = m;
+                if (dist > 0.0f) {
+                    double cosang = (double)dot / (double)dist;
+                    if (cosang > 1.0) cosang = 1.0;
+                    if (cosang < -1.0) cosang = -1.0;
+                    double half = std::acos((double)S.sight_cos_half[ki]);
+                    m = std::fabs(std::acos(cosang) - half);
+                    if (in_range && m < min_margin[e]) min_margin[e] = m;
+                }
+            }
+            bool same_team = S.team[ki] == S.team[kj];
+            bool bush_j = (code[j] & 3) == ZONE_BUSH;
+            bool same_bush = bush_j && (code[i] & 3) == ZONE_BUSH && code[i] == code[j];
+            bool concealed = bush_j && !same_team && !same_bush && !(st.reveal[kj] > 0.0f);
+            bool visible = in_range && in_cone && !concealed;
+
+            float d2h;
+            double mh;
+            bool overlap = hurtbox_hit(st.x[ki], st.y[ki], c[i], s[i], S.range[ki],
+                                       S.hurt_halfwidth[ki], st.x[kj], st.y[kj],
+                                       S.radius[kj], &d2h, min_margin ? &mh : nullptr);
+            bool allowed = role_allows(S.dmg[ki], S.team[ki], S.team[kj]);
+            if (min_margin && allowed && mh < min_margin[e]) min_margin[e] = mh;
+            bool attackable = overlap && allowed;
+
+            if (!visible) continue;
+            if (vis_mask) vis_mask[(long)ki * words + (j >> 6)] |= 1ull << (j & 63);
+            o[0] = st.hp[kj];
+            o[1] = st.hp[kj] / S.hmax[kj];
+            o[2] = dx;
+            o[3] = dy;
+            o[4] = st.theta[kj];
+            o[5] = S.range[kj];
+            o[6] = S.dmg[kj];
+            o[7] = st.cd[kj];
+            o[8] = S.cooldown[kj] != 0.0f ? st.cd[kj] / S.cooldown[kj] : 0.0f;
+            o[9] = S.radius[kj];
+            o[10] = S.mass[kj];
+            o[11] = S.sight_angle[kj];
+            o[12] = 1.0f;
+            o[13] = same_team ? 1.0f : 0.0f;
+            o[14] = attackable ? 1.0f : 0.0f;
+            o[15] = st.cur_speed[kj];
+        }
+
+        /* zone descriptor slots; an inactive slot (type 0) stays zero */
+        for (int z = 0; z < Z; ++z) {
+            if (!S.zone_desc) break;
+            const float *d = S.zone_desc + ((long)e * Z + z) * 6;
+            float *o = row + 15 + 16 * (N - 1) + 6 * z;
+            if (d[0] == 0.0f) continue;
+            o[0] = d[0];
+            o[1] = d[1] - st.x[ki];
+            o[2] = d[2] - st.y[ki];
+            o[3] = d[3];
+            o[4] = d[4];
+            o[5] = d[5];
+        }
+    }
+}
+
+} /* namespace */
+
+extern "C" {
+
+int tabx_ref_obs_dim(const RefParams *p)
+{
+    return 15 + 16 * (p->num_units - 1) + 6 * p->max_zones;
+}
+
+void tabx_ref_sincos(float theta, float *s, float *c) { sincos_spec(theta, s, c); }
+
+void tabx_ref_sincos_n(const float *theta, int n, float *s, float *c)
+{
+    for (int k = 0; k < n; ++k) sincos_spec(theta[k], &s[k], &c[k]);
+}
+
+void tabx_ref_reset(const RefParams *p, const RefScenario *sc, RefState *st,
+                    const unsigned char *env_mask)
+{
+    for (int e = 0; e < p->num_envs; ++e)
+        if (!env_mask || env_mask[e]) reset_env(*p, *sc, *st, e);
+}
+
+void tabx_ref_step(const RefParams *p, const RefScenario *sc, RefState *st,
+                   const unsigned char *actions, float *rewards, unsigned char *dones,
+                   double *min_margin)
+{
+    for (int e = 0; e < p->num_envs; ++e)
+        step_env(*p, *sc, *st, e, actions, rewards, dones, min_margin);
+}
+
+void tabx_ref_observe(const RefParams *p, const RefScenario *sc, const RefState *st,
+                      float *obs, unsigned long long *vis_mask,
+                      unsigned char *action_mask, double *min_margin)
+{
+    for (int e = 0; e < p->num_envs; ++e)
+        observe_env(*p, *sc, *st, e, obs, vis_mask, action_mask, min_margin);
+}
+
+} /* extern "C" */

@@ -1,0 +1,84 @@
+/*
+ * tabx_ref.h -- CPU checker for the TABX batched environment step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  A plain, slow, single-threaded implementation of
+ * the environment rules of the paper's App. A (observation, action space,
+ * interaction dynamics, reward, zones), used by the tests, the smoke check and
+ * the benchmark's CPU-baseline leg to judge the GPU library.  It shares no code
+ * with the GPU library; the product never calls it.
+ *
+ * All pointers are host pointers owned by the caller.  Per-unit arrays are laid
+ * out [E][N] (env-major), float32 state as the workloads prescribe.
+ *
+ * Arithmetic: every float operation is a single correctly rounded IEEE float32
+ * operation (+ - * / sqrt, comparisons) or an explicit fmaf, evaluated in the
+ * order written in tabx_ref.cpp; sums over units run in ascending unit index.
+ *
+ * Parity pins (tests/test_oracle_*.py): hand-worked combat, heal, cooldown,
+ * boundary, terrain and reward cases derived from the paper's unit table and
+ * formulas; invariants; brute-force visibility/attackability with an
+ * independent double-precision atan2/hypot formulation; sincos against libm.
+ * The free parameters the paper does not print (time step, turn rate, sight
+ * cone, reveal duration, zone magnitudes) are inputs; their default values are
+ * "parity unpinned" with respect to the authors' own code, which is not
+ * available.
+ */
+#ifndef TABX_REF_H
+#define TABX_REF_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct RefParams {
+    int   num_envs, num_units;
+    int   grid_w, grid_h;       /* terrain cells; 0 = no terrain */
+    int   max_zones;            /* zone descriptor slots per env in the observation */
+    int   max_steps;            /* truncation horizon */
+    float map_w, map_h, cell_size;
+    float dt, turn_rate;
+    float lava_dps, swamp_mult, reveal_time, boundary_frac;
+} RefParams;
+
+typedef struct RefScenario {
+    const float *init_x, *init_y, *init_theta;
+    const float *hmax, *radius, *mass, *speed, *dmg, *range, *cooldown;
+    const float *sight_angle, *sight_cos_half, *sight_range, *hurt_halfwidth;
+    const unsigned char *team, *enabled;
+    const signed char   *terrain;    /* [E][grid_h][grid_w] or NULL */
+    const float         *zone_desc;  /* [E][max_zones][6] or NULL   */
+} RefScenario;
+
+typedef struct RefState {
+    float *x, *y, *vx, *vy, *theta, *hp, *cd, *reveal, *cur_speed;
+    unsigned char *alive;
+    int   *t;          /* [E] */
+    float *phi_prev;   /* [E] */
+} RefState;
+
+int  tabx_ref_obs_dim(const RefParams *p);
+void tabx_ref_sincos(float theta, float *s, float *c);
+void tabx_ref_sincos_n(const float *theta, int n, float *s, float *c);
+
+/* env_mask: [E] bytes, non-zero = reset that env; NULL = all. */
+void tabx_ref_reset(const RefParams *p, const RefScenario *sc, RefState *st,
+                    const unsigned char *env_mask);
+
+/* actions [E][N] u8; rewards [E][N] f32; dones [E] u8.
+ * min_margin: [E] doubles or NULL; each entry is lowered to the smallest
+ * distance (world units or radians) of any tested pair from a hurtbox boundary
+ * seen in this call (diagnostic, never feeds back into the results). */
+void tabx_ref_step(const RefParams *p, const RefScenario *sc, RefState *st,
+                   const unsigned char *actions, float *rewards,
+                   unsigned char *dones, double *min_margin);
+
+/* obs [E][N][D]; vis_mask [E][N][ceil(N/64)] u64 or NULL; action_mask [E][N] or NULL.
+ * min_margin as above, for the sight-range, sight-angle and hurtbox tests. */
+void tabx_ref_observe(const RefParams *p, const RefScenario *sc, const RefState *st,
+                      float *obs, unsigned long long *vis_mask,
+                      unsigned char *action_mask, double *min_margin);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

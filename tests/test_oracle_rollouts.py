@@ -1,0 +1,176 @@
+"""CPU checker on seeded rollouts: invariants and brute-force cross-checks (no GPU).
+
+Invariants come from the paper's rules: health clamped to [0, max] (App. A
+"Attack execution"), positions clipped to the arena (App. A "Movement and
+kinematic update"), dead and disabled units inert (App. A "Post-step
+bookkeeping"), team rewards opposite (Eq. 1 with the mirrored enemy reward),
+dense rewards telescoping to the potential.  The brute-force checks re-derive
+visibility, attackability and one tick's health change with independent float64
+formulations (tests/bruteforce.py).
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2602_01665_amd import inputs as I
+from tests import bruteforce as bf
+from tests.helpers import other_slot
+
+DENSE = I.Workload("dense_4v4", 24, 4, 24.0, 24, "iid", 0.7, "iid", steps=200, seed=991)
+SMALL = {
+    "c1": (I.WORKLOADS["c1_16env_3v3"], 16, 100),
+    "c2": (I.WORKLOADS["c2_4096env_5v5"], 12, 150),
+    "c3": (I.WORKLOADS["c3_16384env_10v10"], 8, 150),
+    "c5": (I.WORKLOADS["c5_1024env_64v64"], 2, 60),
+    "dense": (DENSE, 24, 200),
+}
+
+
+def _env(w, E, **override):
+    p = I.make_params(w, E, **override)
+    sc = I.make_scenario(w, E)
+    env = ref.RefEnv(p, sc)
+    env.reset()
+    return p, sc, env
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_invariants(name):
+    w, E, steps = SMALL[name]
+    p, sc, env = _env(w, E, max_steps=64)
+    N = w.num_units
+    team = sc["team"].astype(bool)
+    prev = env.snapshot()
+    ret = np.zeros(E, np.float64)
+    for s in range(steps):
+        a = I.actions_for_step(w.seed, s, E, N)
+        r, d = env.step(a)
+        st = env.st
+        assert np.all(st["hp"] >= 0) and np.all(st["hp"] <= sc["hmax"])
+        assert np.all(st["x"] >= 0) and np.all(st["x"] <= p["map_w"])
+        assert np.all(st["y"] >= 0) and np.all(st["y"] <= p["map_h"])
+        assert np.all((st["theta"] >= 0) & (st["theta"] <= np.float32(2 * math.pi)))
+        assert np.array_equal(st["alive"] == 1, st["hp"] > 0)
+        # team rewards are opposite and shared inside a team
+        r0 = r[:, 0]
+        assert np.array_equal(r[:, ~team[0]], np.repeat(r0[:, None], (~team[0]).sum(), 1))
+        assert np.array_equal(r[:, team[0]], np.repeat(-r0[:, None], team[0].sum(), 1))
+        live = d == 0
+        # units dead before the tick are inert during it
+        dead0 = (prev["alive"] == 0) & live[:, None]
+        for k in ("x", "y", "theta", "hp"):
+            assert np.array_equal(st[k][dead0], prev[k][dead0]), k
+        assert np.all(st["vx"][dead0] == 0) and np.all(st["vy"][dead0] == 0)
+        # alive counts never grow inside an episode
+        for tm in (0, 1):
+            m = team == bool(tm)
+            assert np.all((st["alive"] * m).sum(1)[live] <= (prev["alive"] * m).sum(1)[live])
+        # dense rewards telescope: running sum equals the potential of Eq. (1)
+        ret = np.where(live, ret + r0, 0.0)
+        ratio = st["hp"] / sc["hmax"]
+        phi = (ratio * ~team).sum(1) / (~team).sum(1) - (ratio * team).sum(1) / team.sum(1)
+        assert np.allclose(ret[live], phi[live], atol=2e-5)
+        assert np.allclose(st["phi_prev"][live], phi[live], atol=2e-6)
+        # finished episodes are back at their initial state
+        fin = d == 1
+        assert np.array_equal(st["x"][fin], sc["init_x"][fin])
+        assert np.all(st["t"][fin] == 0) and np.all(st["hp"][fin] == sc["hmax"][fin])
+        assert np.all(st["t"][live] == prev["t"][live] + 1)
+
+        obs, vis, am = env.observe()
+        for i in range(N):
+            assert not np.any(vis[:, i, i >> 6] >> np.uint64(i & 63) & np.uint64(1))
+        dead = st["alive"] == 0
+        assert not np.any(vis[dead]) and not np.any(am[dead])
+        assert not np.any(obs[dead][:, 15:15 + 16 * (N - 1)])
+        prev = env.snapshot()
+
+
+def test_snapshot_restore_and_determinism():
+    w, E, _ = SMALL["dense"]
+    p, sc, env = _env(w, E, max_steps=40)
+    N = w.num_units
+    for s in range(30):
+        env.step(I.actions_for_step(w.seed, s, E, N))
+    snap = env.snapshot()
+    trace = []
+    for s in range(30, 80):
+        r, d = env.step(I.actions_for_step(w.seed, s, E, N))
+        trace.append((r.copy(), d.copy(), env.observe()[0].copy()))
+    end = env.snapshot()
+    env.restore(snap)
+    for k, s in enumerate(range(30, 80)):
+        r, d = env.step(I.actions_for_step(w.seed, s, E, N))
+        assert np.array_equal(r, trace[k][0]) and np.array_equal(d, trace[k][1])
+        assert np.array_equal(env.observe()[0], trace[k][2])
+    for k, v in env.snapshot().items():
+        assert np.array_equal(v, end[k]), k
+
+
+@pytest.mark.parametrize("name", ["dense", "c1", "c3"])
+def test_visibility_and_attackable_vs_bruteforce(name):
+    w, E, steps = SMALL[name]
+    E = min(E, 8)
+    p, sc, env = _env(w, E, max_steps=64)
+    N = w.num_units
+    checked = flagged = 0
+    for s in range(min(steps, 90)):
+        env.step(I.actions_for_step(w.seed, s, E, N))
+        if s % 6:
+            continue
+        obs, vis, _ = env.observe()
+        st = env.st
+        for e in range(E):
+            ter = None if sc["terrain"] is None else sc["terrain"][e]
+            bvis, bm = bf.visibility_matrix(p, ter, st["x"][e], st["y"][e], st["theta"][e],
+                                            st["alive"][e], sc["team"][e], st["reveal"][e],
+                                            sc["sight_angle"][e], sc["sight_range"][e])
+            hit, hm = bf.hurtbox_matrix(st["x"][e], st["y"][e], st["theta"][e],
+                                        sc["range"][e], sc["hurt_halfwidth"][e],
+                                        sc["radius"][e])
+            for i in range(N):
+                for j in range(N):
+                    if i == j:
+                        continue
+                    got = int(vis[e, i, j >> 6]) >> (j & 63) & 1
+                    if bm[i, j] > 1e-4:
+                        assert got == int(bvis[i, j]), (s, e, i, j)
+                        checked += 1
+                    if got and hm[i, j] > 1e-4:
+                        heal = sc["dmg"][e, i] < 0
+                        ok = hit[i, j] and (heal == (sc["team"][e, i] == sc["team"][e, j]))
+                        assert other_slot(obs[e, i], i, j)[14] == float(ok), (s, e, i, j)
+                        flagged += 1
+    assert checked > 500 and flagged > 50
+
+
+@pytest.mark.parametrize("name", ["dense", "c1"])
+def test_one_tick_health_vs_bruteforce(name):
+    w, E, steps = SMALL[name]
+    p, sc, env = _env(w, E, max_steps=10_000)
+    N = w.num_units
+    compared = changed = 0
+    for s in range(steps):
+        a = I.actions_for_step(w.seed, s, E, N)
+        before = env.snapshot()
+        r, d = env.step(a)
+        for e in range(E):
+            if d[e]:
+                continue
+            ter = None if sc["terrain"] is None else sc["terrain"][e]
+            sc_e = {k: v[e] for k, v in sc.items() if v is not None and k not in
+                    ("terrain", "zone_desc")}
+            st_e = {k: v[e] for k, v in before.items() if v.ndim == 2}
+            x, y, th, hp, margin = bf.step_health(p, ter, sc_e, st_e, a[e])
+            if margin < 1e-4:
+                continue
+            compared += 1
+            assert np.allclose(env.st["x"][e], x, atol=1e-5)
+            assert np.allclose(env.st["y"][e], y, atol=1e-5)
+            dth = (env.st["theta"][e] - th + math.pi) % (2 * math.pi) - math.pi
+            assert np.all(np.abs(dth) < 1e-5)
+            assert np.allclose(env.st["hp"][e], hp, atol=1e-4), (s, e)
+            changed += int(np.any(env.st["hp"][e] != before["hp"][e]))
+    assert compared > 0.8 * E * steps * 0.5 and changed > 20
