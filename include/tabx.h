@@ -1,0 +1,145 @@
+/*
+ * tabx.h -- C ABI of the MI355X (gfx950) TABX batched battle-environment library.
+ *
+ * The library advances thousands of independent battle instances per call:
+ * unit movement and facing, hurtbox combat (attack / heal), terrain zones,
+ * health and alive flags, team rewards, termination with auto-reset, and the
+ * per-agent partial observations, as the paper defines them in App. A
+ * ("Observation and Global State", "Action Space", "Interaction Dynamics",
+ * "Reward", "Zones") and Sec. 4.
+ *
+ * Conventions
+ *  - E = num_envs, N = num_units per env (allies first or in any order; `team`
+ *    says which), D = tabx_obs_dim().
+ *  - Every pointer inside TabxScenario / TabxState and every array argument is a
+ *    DEVICE pointer into memory owned by the caller.  The library allocates and
+ *    frees nothing and keeps no global state; it borrows the pointers until the
+ *    enqueued work has finished on `stream`.
+ *  - Per-unit arrays are struct-of-arrays, one array per field, indexed
+ *    [e * N + u].  float arrays must be 4-byte aligned, `obs` and `vis_mask`
+ *    16-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls validate their arguments on the host, enqueue kernels and return
+ *    without synchronising.
+ *  - Every entry point returns TABX_OK (0) or a negative TabxError; on error
+ *    nothing has been enqueued.  num_envs == 0 is a valid no-op.
+ *  - An action id >= TABX_NUM_ACTIONS acts as TABX_ACT_NOOP.
+ */
+#ifndef TABX_H
+#define TABX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TABX_N_MAX 128        /* largest supported num_units            */
+#define TABX_Z_MAX 16         /* largest supported max_zones            */
+#define TABX_NUM_ACTIONS 8
+
+/* Discrete actions (Sec. 4; App. A "Action Space"): idle, four world-frame
+ * moves, the combat action (attack, or heal for units with negative damage),
+ * rotate left (counter-clockwise) and right. */
+enum TabxAction {
+    TABX_ACT_NOOP = 0, TABX_ACT_MOVE_XP = 1, TABX_ACT_MOVE_YP = 2, TABX_ACT_MOVE_XM = 3,
+    TABX_ACT_MOVE_YM = 4, TABX_ACT_ATTACK = 5, TABX_ACT_ROT_LEFT = 6, TABX_ACT_ROT_RIGHT = 7
+};
+
+/* Terrain cell code (App. A "Zones"): low two bits = zone type, upper bits =
+ * zone id (two bush cells belong to the same bush iff their codes are equal). */
+enum TabxZone { TABX_ZONE_OPEN = 0, TABX_ZONE_LAVA = 1, TABX_ZONE_BUSH = 2, TABX_ZONE_SWAMP = 3 };
+
+enum TabxError {
+    TABX_OK = 0,
+    TABX_ERR_NULL = -1,      /* a required pointer is NULL                          */
+    TABX_ERR_SHAPE = -2,     /* sizes out of range (N, zones, grid, negative E ...) */
+    TABX_ERR_ALIGN = -3,     /* a pointer is not aligned as required                */
+    TABX_ERR_LAUNCH = -4,    /* the HIP runtime refused the launch                  */
+    TABX_ERR_PARAM = -5      /* a physics constant is not finite / not positive     */
+};
+
+/* Physics and shape constants (App. A "Environment Parameters": the physics
+ * axis of the configuration).  Plain values, passed by pointer from the host. */
+typedef struct TabxParams {
+    int32_t num_envs, num_units;
+    int32_t grid_w, grid_h;       /* terrain cells; both 0 = no terrain              */
+    int32_t max_zones;            /* zone-descriptor slots per env in the obs (>= 0) */
+    int32_t max_steps;            /* truncation horizon (> 0)                        */
+    float   map_w, map_h;         /* arena is [0, map_w] x [0, map_h]                */
+    float   cell_size;            /* world units per terrain cell (> 0)              */
+    float   dt;                   /* time step                                       */
+    float   turn_rate;            /* heading change per time unit for a rotation     */
+    float   lava_dps;             /* lava health loss per time unit                  */
+    float   swamp_mult;           /* speed multiplier inside a swamp                 */
+    float   reveal_time;          /* how long combat exposes a unit hidden in a bush */
+    float   boundary_frac;        /* out-of-arena damage = boundary_frac*hmax*dt     */
+} TabxParams;
+
+/* The scenario: unit specifications and zones (the unit and zone axes of the
+ * configuration).  Read-only for the library.  All [E * N] unless noted. */
+typedef struct TabxScenario {
+    const float *init_x, *init_y, *init_theta;     /* spawn pose; theta in [0, 2*pi) */
+    const float *hmax, *radius, *mass, *speed;     /* hmax > 0 for enabled units     */
+    const float *dmg, *range, *cooldown;           /* dmg < 0 heals allies           */
+    const float *sight_angle;                      /* full cone width, rad (obs only) */
+    const float *sight_cos_half;                   /* cos(sight_angle / 2)           */
+    const float *sight_range;                      /* cone radius                    */
+    const float *hurt_halfwidth;                   /* lateral half-width of hurtbox  */
+    const uint8_t *team;                           /* 0 = allies, 1 = adversaries    */
+    const uint8_t *enabled;                        /* 0 = padding placeholder        */
+    const int8_t  *terrain;    /* [E][grid_h][grid_w] cell codes, NULL iff no grid   */
+    const float   *zone_desc;  /* [E][max_zones][6] = type, cx, cy, hx, hy, effect;
+                                  NULL iff max_zones == 0                            */
+} TabxScenario;
+
+/* Mutable environment state.  [E * N] unless noted.  A snapshot is a copy of
+ * these arrays. */
+typedef struct TabxState {
+    float *x, *y, *vx, *vy, *theta, *hp, *cd, *reveal, *cur_speed;
+    uint8_t *alive;
+    int32_t *t;          /* [E] ticks since the episode began                 */
+    float   *phi_prev;   /* [E] health-ratio potential after the previous tick */
+} TabxState;
+
+/* Floats per agent observation: 15 + 16 * (N - 1) + 6 * max_zones.
+ * Negative TabxError if the shape is unsupported. */
+int tabx_obs_dim(const TabxParams *params);
+int tabx_num_actions(void);
+
+/* Starts episodes (App. A "Environment Parameters": configuration applied at
+ * reset).  env_mask: device [E] bytes, non-zero = reset that env; NULL = all. */
+int tabx_reset(const TabxParams *params, const TabxScenario *scenario,
+               const TabxState *state, const uint8_t *env_mask, void *stream);
+
+/* One tick for every env (App. A "Interaction Dynamics", "Reward"):
+ * physics -> actions (move / rotate / combat) -> zone effects, alive flags,
+ * rewards, termination; a finished env is reset in place and reports done = 1.
+ *   actions [E][N] u8 (in), rewards [E][N] f32 (out), dones [E] u8 (out). */
+int tabx_step(const TabxParams *params, const TabxScenario *scenario,
+              const TabxState *state, const uint8_t *actions,
+              float *rewards, uint8_t *dones, void *stream);
+
+/* Per-agent observations of the current state (App. A "Observation and Global
+ * State", "Action Space" for the mask).
+ *   obs [E][N][D] f32 (out): own block (15), other-unit blocks (16 each,
+ *     ascending unit index without self, zero unless visible), zone slots (6 each);
+ *   vis_mask [E][N][ceil(N/64)] u64 (out, NULL to skip): bit j of row i = i sees j;
+ *   action_mask [E][N] u8 (out, NULL to skip): 1 = the combat action is available. */
+int tabx_observe(const TabxParams *params, const TabxScenario *scenario,
+                 const TabxState *state, float *obs, uint64_t *vis_mask,
+                 uint8_t *action_mask, void *stream);
+
+/* tabx_step followed by tabx_observe in one launch; results identical to the
+ * two separate calls. */
+int tabx_step_observe(const TabxParams *params, const TabxScenario *scenario,
+                      const TabxState *state, const uint8_t *actions,
+                      float *rewards, uint8_t *dones, float *obs,
+                      uint64_t *vis_mask, uint8_t *action_mask, void *stream);
+
+const char *tabx_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TABX_H */

@@ -1,0 +1,212 @@
+"""Thin Python binding of libtabx.so (the C ABI declared in include/tabx.h).
+
+Argument marshalling only: every stage of the environment tick runs inside the
+HIP kernels.  PyTorch owns the device memory and the stream; this module turns
+tensors into the pointer structs the library takes.  There is no CPU fallback:
+if the library has not been built, importing fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtabx.so")
+
+_F = C.POINTER(C.c_float)
+_U8 = C.POINTER(C.c_uint8)
+
+SCENARIO_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",
+                  "range", "cooldown", "sight_angle", "sight_cos_half", "sight_range",
+                  "hurt_halfwidth")
+STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
+
+EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
+           "tabx_step_observe", "tabx_strerror")
+
+
+class TabxParams(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("num_envs", "num_units", "grid_w", "grid_h", "max_zones", "max_steps")] + \
+               [(n, C.c_float) for n in
+                ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
+                 "reveal_time", "boundary_frac")]
+
+
+class TabxScenario(C.Structure):
+    _fields_ = [(n, _F) for n in SCENARIO_FLOAT] + \
+               [("team", _U8), ("enabled", _U8), ("terrain", C.POINTER(C.c_int8)),
+                ("zone_desc", _F)]
+
+
+class TabxState(C.Structure):
+    _fields_ = [(n, _F) for n in STATE_FLOAT] + \
+               [("alive", _U8), ("t", C.POINTER(C.c_int32)), ("phi_prev", _F)]
+
+
+class TabxError(RuntimeError):
+    pass
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it with `python -m paper_2602_01665_amd.build` "
+            "(hipcc, gfx950).  There is no fallback path.")
+    lib = C.CDLL(path)
+    P, S, T, V = C.POINTER(TabxParams), C.POINTER(TabxScenario), C.POINTER(TabxState), C.c_void_p
+    lib.tabx_obs_dim.argtypes = [P]
+    lib.tabx_num_actions.argtypes = []
+    lib.tabx_reset.argtypes = [P, S, T, V, V]
+    lib.tabx_step.argtypes = [P, S, T, V, V, V, V]
+    lib.tabx_observe.argtypes = [P, S, T, V, V, V, V]
+    lib.tabx_step_observe.argtypes = [P, S, T, V, V, V, V, V, V, V]
+    lib.tabx_strerror.argtypes = [C.c_int]
+    lib.tabx_strerror.restype = C.c_char_p
+    for name in EXPORTS[:-1]:
+        getattr(lib, name).restype = C.c_int
+    return lib
+
+
+_lib = load_library()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise TabxError(f"{what}: {_lib.tabx_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _cast(t, typ):
+    return C.cast(C.c_void_p(t.data_ptr()), typ) if t is not None else C.cast(None, typ)
+
+
+def make_params(p: dict) -> TabxParams:
+    return TabxParams(**{k: p[k] for k, _ in TabxParams._fields_})
+
+
+def tabx_obs_dim(params: TabxParams) -> int:
+    d = _lib.tabx_obs_dim(C.byref(params))
+    if d < 0:
+        _check(d, "tabx_obs_dim")
+    return d
+
+
+def tabx_num_actions() -> int:
+    return _lib.tabx_num_actions()
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def tabx_reset(params, scenario, state, env_mask=None, stream=None):
+    _check(_lib.tabx_reset(C.byref(params), C.byref(scenario), C.byref(state), _ptr(env_mask),
+                           _stream_ptr(stream)), "tabx_reset")
+
+
+def tabx_step(params, scenario, state, actions, rewards, dones, stream=None):
+    _check(_lib.tabx_step(C.byref(params), C.byref(scenario), C.byref(state), _ptr(actions),
+                          _ptr(rewards), _ptr(dones), _stream_ptr(stream)), "tabx_step")
+
+
+def tabx_observe(params, scenario, state, obs, vis_mask=None, action_mask=None, stream=None):
+    _check(_lib.tabx_observe(C.byref(params), C.byref(scenario), C.byref(state), _ptr(obs),
+                             _ptr(vis_mask), _ptr(action_mask), _stream_ptr(stream)),
+           "tabx_observe")
+
+
+def tabx_step_observe(params, scenario, state, actions, rewards, dones, obs, vis_mask=None,
+                      action_mask=None, stream=None):
+    _check(_lib.tabx_step_observe(C.byref(params), C.byref(scenario), C.byref(state),
+                                  _ptr(actions), _ptr(rewards), _ptr(dones), _ptr(obs),
+                                  _ptr(vis_mask), _ptr(action_mask), _stream_ptr(stream)),
+           "tabx_step_observe")
+
+
+class TabxEnv:
+    """Device buffers of one batch of environments plus the calls on them."""
+
+    def __init__(self, params: dict, scenario: dict, device="cuda:0", want_vis=True,
+                 want_action_mask=True):
+        self.device = torch.device(device)
+        self.p = dict(params)
+        self.params = make_params(self.p)
+        E, N = self.p["num_envs"], self.p["num_units"]
+        self.E, self.N = E, N
+        self.D = tabx_obs_dim(self.params)
+        self.words = (N + 63) // 64
+        dev = self.device
+
+        def up(a, dtype):
+            return torch.as_tensor(a, dtype=dtype).contiguous().to(dev)
+
+        self.sc = {k: up(scenario[k], torch.float32).reshape(E * N) for k in SCENARIO_FLOAT}
+        self.sc["team"] = up(scenario["team"], torch.uint8).reshape(E * N)
+        self.sc["enabled"] = up(scenario["enabled"], torch.uint8).reshape(E * N)
+        ter = scenario.get("terrain")
+        self.sc["terrain"] = None if ter is None else up(ter, torch.int8)
+        zd = scenario.get("zone_desc") if self.p["max_zones"] > 0 else None
+        self.sc["zone_desc"] = None if zd is None else up(zd, torch.float32)
+        self.scenario = TabxScenario(
+            **{k: _cast(self.sc[k], _F) for k in SCENARIO_FLOAT},
+            team=_cast(self.sc["team"], _U8), enabled=_cast(self.sc["enabled"], _U8),
+            terrain=_cast(self.sc["terrain"], C.POINTER(C.c_int8)),
+            zone_desc=_cast(self.sc["zone_desc"], _F))
+
+        self.st = {k: torch.zeros(E * N, dtype=torch.float32, device=dev) for k in STATE_FLOAT}
+        self.st["alive"] = torch.zeros(E * N, dtype=torch.uint8, device=dev)
+        self.st["t"] = torch.zeros(E, dtype=torch.int32, device=dev)
+        self.st["phi_prev"] = torch.zeros(E, dtype=torch.float32, device=dev)
+        self.state = self._state_struct(self.st)
+
+        self.rewards = torch.zeros(E, N, dtype=torch.float32, device=dev)
+        self.dones = torch.zeros(E, dtype=torch.uint8, device=dev)
+        self.obs = torch.zeros(E, N, self.D, dtype=torch.float32, device=dev)
+        self.vis = (torch.zeros(E, N, self.words, dtype=torch.int64, device=dev)
+                    if want_vis else None)
+        self.amask = (torch.zeros(E, N, dtype=torch.uint8, device=dev)
+                      if want_action_mask else None)
+
+    @staticmethod
+    def _state_struct(st: dict) -> TabxState:
+        return TabxState(**{k: _cast(st[k], _F) for k in STATE_FLOAT},
+                         alive=_cast(st["alive"], _U8),
+                         t=_cast(st["t"], C.POINTER(C.c_int32)),
+                         phi_prev=_cast(st["phi_prev"], _F))
+
+    def reset(self, env_mask=None, stream=None):
+        tabx_reset(self.params, self.scenario, self.state, env_mask, stream)
+
+    def step(self, actions, stream=None):
+        tabx_step(self.params, self.scenario, self.state, actions, self.rewards, self.dones,
+                  stream)
+
+    def observe(self, stream=None):
+        tabx_observe(self.params, self.scenario, self.state, self.obs, self.vis, self.amask,
+                     stream)
+
+    def step_observe(self, actions, stream=None):
+        tabx_step_observe(self.params, self.scenario, self.state, actions, self.rewards,
+                          self.dones, self.obs, self.vis, self.amask, stream)
+
+    def snapshot(self) -> dict:
+        return {k: v.clone() for k, v in self.st.items()}
+
+    def restore(self, snap: dict):
+        for k, v in snap.items():
+            self.st[k].copy_(v)
+
+    def state_numpy(self) -> dict:
+        out = {}
+        for k, v in self.st.items():
+            a = v.cpu().numpy()
+            out[k] = a if k in ("t", "phi_prev") else a.reshape(self.E, self.N)
+        return out

@@ -1,0 +1,85 @@
+"""The C-ABI library loads and exports what include/tabx.h declares; host-side argument
+validation returns the documented error codes without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tabx.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_01665_amd import build
+    if build.is_stale():
+        build.build()
+    from paper_2602_01665_amd import binding
+    return binding
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tabx_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None, n
+
+
+def _params(B, **kw):
+    base = dict(num_envs=4, num_units=20, grid_w=0, grid_h=0, max_zones=8, max_steps=10,
+                map_w=8.0, map_h=8.0, cell_size=1.0, dt=0.25, turn_rate=1.0, lava_dps=1.0,
+                swamp_mult=0.5, reveal_time=1.0, boundary_frac=0.1)
+    base.update(kw)
+    return B.TabxParams(**base)
+
+
+def test_obs_dim_and_shape_errors(B):
+    lib = B._lib
+    assert lib.tabx_num_actions() == 8
+    assert lib.tabx_obs_dim(C.byref(_params(B))) == 15 + 16 * 19 + 6 * 8
+    assert lib.tabx_obs_dim(C.byref(_params(B, num_units=128, max_zones=0))) == 15 + 16 * 127
+    assert lib.tabx_obs_dim(None) == -1
+    for bad in (dict(num_units=0), dict(num_units=129), dict(max_zones=17), dict(max_zones=-1),
+                dict(num_envs=-1), dict(grid_w=4), dict(max_steps=0)):
+        assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -2, bad
+    for bad in (dict(dt=0.0), dict(cell_size=-1.0), dict(map_w=float("nan")),
+                dict(lava_dps=float("inf"))):
+        assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -5, bad
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert len(lib.tabx_strerror(code)) > 0
+
+
+def test_null_and_alignment_errors_come_back_before_any_launch(B):
+    lib = B._lib
+    p = _params(B, max_zones=0)
+    sc, st = B.TabxScenario(), B.TabxState()
+    assert lib.tabx_reset(C.byref(p), None, C.byref(st), None, None) == -1
+    assert lib.tabx_reset(C.byref(p), C.byref(sc), C.byref(st), None, None) == -1
+    # fake but non-null addresses: validation only inspects them, nothing is launched
+    fake = 0x1000
+    for k, _ in B.TabxScenario._fields_:
+        if k not in ("terrain", "zone_desc"):
+            setattr(sc, k, C.cast(C.c_void_p(fake), dict(B.TabxScenario._fields_)[k]))
+    assert lib.tabx_reset(C.byref(p), C.byref(sc), None, None, None) == -1
+    for k, typ in B.TabxState._fields_:
+        setattr(st, k, C.cast(C.c_void_p(fake), typ))
+    assert lib.tabx_step(C.byref(p), C.byref(sc), C.byref(st), None, None, None, None) == -1
+    st.hp = C.cast(C.c_void_p(fake + 2), B._F)
+    assert lib.tabx_reset(C.byref(p), C.byref(sc), C.byref(st), None, None) == -3
+    st.hp = C.cast(C.c_void_p(fake), B._F)
+    assert lib.tabx_observe(C.byref(p), C.byref(sc), C.byref(st), C.c_void_p(fake + 4), None,
+                            None, None) == -3
+    # terrain pointer must be present exactly when there is a grid
+    pg = _params(B, max_zones=0, grid_w=4, grid_h=4)
+    assert lib.tabx_reset(C.byref(pg), C.byref(sc), C.byref(st), None, None) == -1
+    # an empty batch is a no-op that needs no buffers
+    p0 = _params(B, num_envs=0)
+    assert lib.tabx_step(C.byref(p0), None, None, None, None, None, None) == 0

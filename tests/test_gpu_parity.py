@@ -1,0 +1,290 @@
+"""HIP library vs CPU checker, element by element, through the C ABI (needs an MI355X).
+
+Bar: integer / boolean fields (alive, t, dones, visibility masks, action masks,
+discrete observation features) bit-exact; float32 fields (positions, headings,
+health, timers, rewards, observations) within 1e-5 absolute, over full seeded
+rollouts with auto-reset.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2602_01665_amd import inputs as I
+from tests.parity import compare_outputs, compare_state
+
+pytestmark = pytest.mark.gpu
+
+DENSE = I.Workload("dense_4v4", 128, 4, 24.0, 24, "iid", 0.7, "iid", steps=300, seed=991)
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _pair(w, E, scenario=None, **override):
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    assert torch.cuda.is_available()
+    p = I.make_params(w, E, **override)
+    sc = I.make_scenario(w, E) if scenario is None else scenario
+    ref = RefEnv(p, sc)
+    gpu = TabxEnv(p, sc)
+    ref.reset()
+    gpu.reset()
+    torch.cuda.synchronize()
+    compare_state(gpu.state_numpy(), ref.st, "after reset: ")
+    return p, sc, ref, gpu
+
+
+def _rollout(w, E, steps, fused, scenario=None, obs_every=1, **override):
+    import torch
+    p, sc, ref, gpu = _pair(w, E, scenario, **override)
+    N = p["num_units"]
+    inexact = dones = 0
+    for s in range(steps):
+        a = I.actions_for_step(w.seed, s, E, N)
+        ad = torch.from_numpy(a).to(gpu.device)
+        ref.step(a)
+        look = (s % obs_every == 0) or s == steps - 1
+        if fused:
+            gpu.step_observe(ad)
+        else:
+            gpu.step(ad)
+            if look:
+                gpu.observe()
+        if look or fused:
+            ref.observe()
+        torch.cuda.synchronize()
+        where = f"{w.name} E={E} step {s}: "
+        inexact += compare_state(gpu.state_numpy(), ref.st, where)
+        inexact += compare_outputs(gpu, ref, where, check_obs=look or fused)
+        dones += int(ref.dones.sum())
+    return inexact, dones
+
+
+CASES = [
+    ("c1_16env_3v3", 16, 100, dict(max_steps=32)),   # the small config, full size
+    ("c2_4096env_5v5", 96, 200, dict(max_steps=64)),
+    ("c3_16384env_10v10", 64, 200, dict(max_steps=96)),
+    ("c4_65536env_5v5", 256, 200, dict(max_steps=50)),
+    ("c5_1024env_64v64", 3, 60, dict(max_steps=40)),
+]
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+@pytest.mark.parametrize("name,E,steps,over", CASES, ids=[c[0] for c in CASES])
+def test_rollout_matches_checker(name, E, steps, over, fused):
+    _say(f"[gpu] rollout {name} E={E} steps={steps} fused={fused}")
+    inexact, dones = _rollout(I.WORKLOADS[name], E, steps, fused, **over)
+    _say(f"[gpu]   floats within tolerance but not bit-identical: {inexact}; episodes ended: {dones}")
+    assert dones > 0              # auto-reset was exercised
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_combat_heavy_rollout(fused):
+    _say(f"[gpu] dense 4v4 combat rollout fused={fused}")
+    inexact, dones = _rollout(DENSE, 128, 300, fused, max_steps=48)
+    _say(f"[gpu]   inexact floats {inexact}; episodes ended {dones}")
+    assert dones > 128
+
+
+@pytest.mark.parametrize("team_size,disabled", [(1, 0), (3, 1), (7, 2), (16, 3), (17, 0),
+                                                (32, 5), (33, 4), (50, 9), (64, 0)])
+def test_ragged_unit_counts_and_padding(team_size, disabled):
+    """Unit counts around the 32 / 64 / 128 lane boundaries, with disabled placeholders."""
+    w = I.Workload(f"ragged_{team_size}", 5, team_size, 40.0, 20, "iid", 0.6, "iid",
+                   steps=60, seed=4242 + team_size)
+    sc = I.make_scenario(w, 5)
+    rng = np.random.default_rng(team_size)
+    for e in range(5):
+        off = rng.choice(w.num_units, size=min(disabled, w.num_units - 2), replace=False)
+        # keep at least one unit per team enabled
+        off = [u for u in off if u not in (0, w.num_units - 1)]
+        sc["enabled"][e, off] = 0
+    _say(f"[gpu] ragged N={w.num_units} disabled={disabled}")
+    inexact, dones = _rollout(w, 5, 60, True, scenario=sc, max_steps=25)
+    assert dones > 0
+
+
+def test_zone_descriptor_slots_and_full_cone():
+    """Zone slots up to the maximum, 360-degree and narrow cones, odd cell size."""
+    w = I.Workload("zones", 9, 6, 30.0, 20, "rects", 1.0, "iid", max_zones=16, steps=80,
+                   seed=77)
+    sc = I.make_scenario(w, 9)
+    sc["sight_angle"][:, ::3] = np.float32(2 * math.pi)
+    sc["sight_cos_half"][:, ::3] = np.float32(-1.0)
+    sc["sight_angle"][:, 1::3] = np.float32(0.5)
+    sc["sight_cos_half"][:, 1::3] = np.float32(math.cos(0.25))
+    _say("[gpu] zone descriptors Z=16, mixed cones")
+    _rollout(w, 9, 80, True, scenario=sc, max_steps=30)
+    _rollout(w, 9, 40, False, scenario=sc, max_steps=30)
+
+
+def test_other_roster_units():
+    """Every roster row (big bodies, wide hurtboxes, long cooldowns) in one battle."""
+    names = list(I.ROSTER)
+    units = []
+    rng = np.random.default_rng(5)
+    for t in (0, 1):
+        for n in names:
+            units.append(dict(unit=n, team=t, x=float(rng.uniform(8, 24)),
+                              y=float(rng.uniform(8, 24)), theta=float(rng.uniform(0, 6.28))))
+    one = I.custom_scenario(units, 32.0)
+    E = 33
+    sc = {k: (None if v is None else np.ascontiguousarray(np.repeat(v, E, axis=0)))
+          for k, v in one.items()}
+    sc["init_x"] = (sc["init_x"] + rng.uniform(-4, 4, sc["init_x"].shape)).astype(np.float32)
+    sc["init_theta"] = rng.uniform(0, 6.28, sc["init_theta"].shape).astype(np.float32)
+    w = I.Workload("roster", E, len(names), 32.0, 0, "none", 1.0, "iid", steps=150, seed=31)
+    _say("[gpu] full roster 9v9")
+    inexact, dones = _rollout(w, E, 150, True, scenario=sc, max_steps=60)
+    assert dones > 0
+
+
+def test_fused_equals_separate_and_is_deterministic():
+    import torch
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = I.WORKLOADS["c3_16384env_10v10"]
+    E = 512
+    p = I.make_params(w, E, max_steps=40)
+    sc = I.make_scenario(w, E)
+    envs = [TabxEnv(p, sc) for _ in range(3)]
+    for g in envs:
+        g.reset()
+    _say("[gpu] fused vs separate vs repeated run, E=512")
+    for s in range(120):
+        ad = torch.from_numpy(I.actions_for_step(w.seed, s, E, w.num_units)).to("cuda:0")
+        envs[0].step_observe(ad)
+        envs[1].step(ad)
+        envs[1].observe()
+        envs[2].step_observe(ad)
+        torch.cuda.synchronize()
+        for other in envs[1:]:
+            for k in envs[0].st:
+                assert torch.equal(envs[0].st[k], other.st[k]), (s, k)
+            for name in ("rewards", "dones", "obs", "vis", "amask"):
+                assert torch.equal(getattr(envs[0], name), getattr(other, name)), (s, name)
+
+
+def test_snapshot_restore_replays_bitwise():
+    import torch
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = DENSE
+    E = 64
+    p = I.make_params(w, E, max_steps=48)
+    g = TabxEnv(p, I.make_scenario(w, E))
+    g.reset()
+    acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, w.num_units)).to("cuda:0")
+            for s in range(90)]
+    for s in range(30):
+        g.step_observe(acts[s])
+    snap = g.snapshot()
+    trace = []
+    for s in range(30, 90):
+        g.step_observe(acts[s])
+        trace.append((g.obs.clone(), g.rewards.clone(), g.dones.clone()))
+    g.restore(snap)
+    for n, s in enumerate(range(30, 90)):
+        g.step_observe(acts[s])
+        assert torch.equal(g.obs, trace[n][0]) and torch.equal(g.rewards, trace[n][1])
+        assert torch.equal(g.dones, trace[n][2])
+
+
+def test_reset_mask_and_empty_batch():
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = I.WORKLOADS["c2_4096env_5v5"]
+    E = 40
+    p, sc, ref, gpu = _pair(w, E)
+    for s in range(12):
+        a = I.actions_for_step(w.seed, s, E, w.num_units)
+        ref.step(a)
+        gpu.step(torch.from_numpy(a).to("cuda:0"))
+    mask = np.zeros(E, np.uint8)
+    mask[[0, 3, 17, 39]] = 1
+    ref.reset(mask)
+    gpu.reset(torch.from_numpy(mask).to("cuda:0"))
+    torch.cuda.synchronize()
+    compare_state(gpu.state_numpy(), ref.st, "masked reset: ")
+    # an empty batch is a valid no-op
+    p0 = I.make_params(w, 0)
+    sc0 = I.take_envs(sc, slice(0, 0))
+    g0 = TabxEnv(p0, sc0)
+    g0.reset()
+    g0.step_observe(torch.zeros(0, dtype=torch.uint8, device="cuda:0"))
+    torch.cuda.synchronize()
+
+
+def test_out_of_range_action_is_noop():
+    import torch
+    w = I.WORKLOADS["c1_16env_3v3"]
+    p, sc, ref, gpu = _pair(w, 16)
+    rng = np.random.default_rng(3)
+    for s in range(30):
+        a = rng.integers(0, 256, size=(16, 6), dtype=np.uint8)
+        ref.step(np.where(a >= 8, 0, a).astype(np.uint8))
+        gpu.step(torch.from_numpy(a).to("cuda:0"))
+        torch.cuda.synchronize()
+        compare_state(gpu.state_numpy(), ref.st, f"wild actions step {s}: ")
+
+
+# ---------------------------------------------------------------- full-size launches
+FULL = [
+    ("c2_4096env_5v5", 500, 48),
+    ("c3_16384env_10v10", 1000, 40),
+    ("c4_65536env_5v5", 1000, 64),
+    ("c5_1024env_64v64", 500, 3),
+]
+
+
+@pytest.mark.parametrize("name,steps,n_sample", FULL, ids=[c[0] for c in FULL])
+def test_full_size_sampled_envs(name, steps, n_sample):
+    """The benchmark's launch (fused tick, full env count, full step count); the checker
+    replays a sample of the envs (first, last, random) and every tick of them is compared."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = I.WORKLOADS[name]
+    E, N = w.num_envs, w.num_units
+    _say(f"[gpu] full size {name}: E={E} N={N} steps={steps} sample={n_sample}")
+    p = I.make_params(w)
+    sc = I.make_scenario(w)
+    rng = np.random.default_rng(11)
+    rows = np.unique(np.concatenate([[0, 1, E - 1], rng.choice(E, n_sample - 3, replace=False)]))
+    ref = RefEnv(I.make_params(w, len(rows)), I.take_envs(sc, rows))
+    ref.track_margin = True
+    gpu = TabxEnv(p, sc)
+    ref.reset()
+    gpu.reset()
+    rows_t = torch.from_numpy(rows).to("cuda:0")
+    inexact = dones = 0
+    for s in range(steps):
+        a = I.actions_for_step(w.seed, s, E, N)
+        gpu.step_observe(torch.from_numpy(a).to("cuda:0"))
+        ref.step(a[rows])
+        ref.observe()
+        st = {k: (v.reshape(E, N)[rows_t] if v.numel() == E * N else v[rows_t]).cpu().numpy()
+              for k, v in gpu.st.items()}
+        where = f"{name} full size step {s}: "
+        inexact += compare_state(st, ref.st, where)
+        inexact += compare_outputs(gpu, ref, where, rows=rows_t)
+        dones += int(ref.dones.sum())
+        if s % 100 == 0:
+            _say(f"[gpu]   step {s} ok")
+    _say(f"[gpu]   inexact floats {inexact}; sampled episodes ended {dones}; smallest "
+         f"boundary margin seen by the checker {ref.margin.min():.3e}")
+    # properties that hold for every env at any size
+    obs = gpu.obs
+    assert torch.isfinite(obs).all()
+    hp = gpu.st["hp"].reshape(E, N)
+    assert (hp >= 0).all() and (hp <= gpu.sc["hmax"].reshape(E, N)).all()
+    assert torch.equal(gpu.st["alive"].reshape(E, N) == 1, hp > 0)
+    r = gpu.rewards
+    team = gpu.sc["team"].reshape(E, N).bool()
+    assert torch.equal(r[:, :1].expand(E, N)[~team], r[~team])
+    assert torch.equal((-r[:, :1]).expand(E, N)[team], r[team])
