@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Throughput of the TABX batched tick (fused step + observe) on one MI355X.
+
+A "step" is one tick of the whole hot path for every env of the workload: physics,
+actions, hurtbox combat, zones, rewards, termination with auto-reset, and the per-agent
+observations.  Inputs (scenario, pre-generated seeded actions) are resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+# copy kernel of known size); see profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes_per_env(N: int, D: int, Z: int) -> int:
+    """Bytes one env-tick must move (fused step + observe): obs write, state read+write,
+    specs, action, reward, action mask, terrain cell, visibility mask per unit; zone
+    descriptors, tick counter / potential / done per env."""
+    words = (N + 63) // 64
+    per_unit = 4 * D + 2 * 37 + 46 + 1 + 4 + 1 + 1 + 8 * words
+    return N * per_unit + 24 * Z + 17
+
+
+def cpu_baseline(w, I, scenario: dict, sample_envs: int, ticks: int) -> dict:
+    from oracle.ref import RefEnv
+    E = min(sample_envs, w.num_envs)
+    p = I.make_params(w, E)
+    env = RefEnv(p, I.take_envs(scenario, slice(0, E)))
+    env.reset()
+    acts = [I.actions_for_step(w.seed, s, E, w.num_units) for s in range(min(ticks, 64))]
+    t0 = time.perf_counter()
+    for s in range(ticks):
+        env.step(acts[s % len(acts)])
+        env.observe()
+    dt = time.perf_counter() - t0
+    return {"value": E * w.num_units * ticks / dt, "unit": "agent-steps/s", "cores": 1,
+            "kind": "oracle",
+            "sample": f"first {E} envs of the workload, {ticks} ticks of step+observe, "
+                      f"single thread, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also time a plain device fill and copy of the obs-sized buffer "
+                         "(reference points for the HBM roofline and for rocprofv3 byte counters)")
+    ap.add_argument("--separate", action="store_true",
+                    help="time tabx_step + tabx_observe as two launches instead of the fused one")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (environments are independent; more GPUs "
+              "would each take a slice of the env index range, no collectives). "
+              "--gpus must be 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2602_01665_amd import build as hip_build
+    if hip_build.is_stale():
+        hip_build.build()
+    from paper_2602_01665_amd import inputs as I
+    from paper_2602_01665_amd.binding import TabxEnv
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    name = args.workload or I.HEADLINE
+    w = I.WORKLOADS[name]
+    E, N = w.num_envs, w.num_units
+    p = I.make_params(w)
+    scenario = I.make_scenario(w)
+    env = TabxEnv(p, scenario)
+    env.reset()
+    n_act = min(args.steps + args.warmup, 64)
+    acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, N)).to("cuda:0")
+            for s in range(n_act)]
+    stream = torch.cuda.current_stream()
+
+    def tick(s):
+        a = acts[s % n_act]
+        if args.separate:
+            env.step(a, stream)
+            env.observe(stream)
+        else:
+            env.step_observe(a, stream)
+
+    for s in range(args.warmup):
+        tick(s)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for s in range(args.steps):
+        tick(args.warmup + s)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = ev0.elapsed_time(ev1) / args.steps     # average per tick on the launch stream
+
+    assert torch.isfinite(env.obs).all()
+    B_env = algorithmic_bytes_per_env(N, env.D, p["max_zones"])
+    achieved = B_env * E / (kernel_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(name)
+    out = {
+        "metric": "agent-steps/sec (step+observe) at 16384 envs 10v10; HBM GB/s vs peak",
+        "value": E * N * args.steps / wall,
+        "unit": "agent-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "num_envs": E, "units_per_env": N, "obs_dim": env.D,
+                   "launch": "separate step+observe" if args.separate else "fused step_observe",
+                   "actions": f"{n_act} pre-generated seeded uniform action batches, cycled"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": B_env * E,
+                     "kernel_ms": kernel_ms},
+    }
+    if args.calibrate:
+        src = torch.empty_like(env.obs)
+        dst = torch.empty_like(env.obs)
+        nbytes = src.numel() * 4
+        cal = {"bytes": nbytes}
+        for label, fn, moved in (("fill", lambda: dst.fill_(1.0), nbytes),
+                                 ("copy", lambda: dst.copy_(src), 2 * nbytes)):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            ev0.record(stream)
+            for _ in range(20):
+                fn()
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / 20
+            cal[label + "_ms"] = ms
+            cal[label + "_GBs"] = moved / (ms * 1e-3) / 1e9
+        out["calibration"] = cal
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, I, scenario, 1024 if N <= 32 else 32,
+                                           1200 if N <= 32 else 300)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
