@@ -5,18 +5,16 @@
 // struct-of-arrays state of the G envs is one contiguous, coalesced run of G*N
 // elements per field.  For 64 < N <= 128 a workgroup of two wavefronts owns one
 // env.  The per-unit stages run in registers; what other lanes need is published
-// in LDS and read back as broadcasts inside the all-pairs loops (hurtbox,
-// visibility), which every lane runs over the units of its own env.
+// in LDS and read back as broadcasts inside the all-pairs loops.
 //
-// The observation tensor is almost all of the HBM traffic.  Its other-unit
-// blocks are written by a flat loop over (row, slot) pairs with four lanes per
-// 16-float block (one 16-byte store each, 1 KB contiguous per wave instruction);
-// the own blocks and zone slots are written by two smaller loops.
-//
-// Kernel time is bounded by VALU issue, not by HBM, unless the instruction count
-// per env is kept low; hence: boolean pair predicates are combined as scalar
-// lane masks, per-row visibility is pre-shifted into slot order so that the
-// writer needs one bit-field extract per block, and counts come from ballots.
+// The observation tensor is almost all of the HBM traffic, and HBM only takes it
+// at full rate when every cache line is completed by consecutive stores.  The
+// observe stage therefore loops over the observers i of an env; in pass i every
+// lane tests "does observer i see / reach my unit" and writes its unit's 16-float
+// block, taken from its own registers, into an LDS image of observer i's row;
+// the finished rows (one per packed env) are then streamed to HBM front to back,
+// 16 bytes per lane and 1 KB per store instruction.  Own blocks and zone slots
+// join the same stream.
 //
 // The rules follow the paper's App. A ("Interaction Dynamics", "Reward",
 // "Observation and Global State", "Zones").  All arithmetic is float32 with one
@@ -31,6 +29,8 @@
 
 namespace tabx {
 
+constexpr int kMaxPasses = 6;      // store passes that stream one set of staged rows
+
 struct KArgs {
     TabxParams   p;
     TabxScenario sc;
@@ -42,18 +42,16 @@ struct KArgs {
     float    *obs;
     uint64_t *vis_mask;
     uint8_t  *action_mask;
-    int       obs_dim;
+    int       obs_dim;             // D
     int       envs_per_block;      // G
-    int       rows_per_group;      // observation rows staged in LDS per pass
-    int       stage_floats;        // staging floats per wave (multiple of 4)
-    int       stage_offset;        // staging offset in dynamic LDS, floats (multiple of 4)
+    int       row_pitch;           // floats between staged rows: D + 1 rounded up to 4
+    int       copy_passes;         // ceil(G * row_pitch / 4 / lanes), <= kMaxPasses
 };
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte store, 4-byte aligned
 
 constexpr float kTwoPi = 6.28318530717958647692f;
 constexpr float kInf = __builtin_huge_valf();
-
 // Sine and cosine of a heading in [0, 2*pi]: quadrant index n = trunc(theta *
 // 2/pi + 1/2), remainder through a two-term split of pi/2, degree-9 / degree-8
 // Taylor polynomials in Horner form with explicit fused multiply-adds.
@@ -111,19 +109,41 @@ struct Place {
     size_t k;
 };
 
-template <int WAVES, int NW>
+template <int WAVES>
 struct Shared {
     static constexpr int L = 64 * WAVES;
-    float4   pj[L];           // pair-loop record of a unit: x, y, r^2, flags
-    int2     hitrec[L];       // {designated victim (local index) or -1, damage bits}
-    float2   share[L];        // this unit's term in the team-0 / team-1 ratio sums
-    float    tab[L][16];      // observation features of a unit
-    float4   row[L];          // observer record: x, y, info bits
-    uint32_t V[L][NW];        // visible, by slot (self bit dropped)
-    uint32_t A[L][NW];        // attackable, by slot
-    uint32_t T[L][NW];        // same team, by slot
+    union {
+        struct {                  // step stage
+            float4 pj[L];         // pair-loop record of a unit: x, y, r^2, flags
+            int2   hitrec[L];     // {designated victim (local index) or -1, damage bits}
+            float2 share[L];      // this unit's term in the team-0 / team-1 ratio sums
+        } st;
+        struct {                  // observe stage: what an observer's row needs
+            float4 pose[L];       // x, y, cos(theta), sin(theta)
+            float4 reach[L];      // attack range, hurtbox half-width, sight range^2, cos(cone / 2)
+        } ob;
+    };
+    int      seer[L];             // observer flags: alive | team<<1 | heals<<2 | enabled<<3 | bush key<<8
+    uint64_t rowbits[L][WAVES];   // ballot of "observer i sees lane" per observer index
     uint64_t ballots[WAVES][4];
 };
+
+// Orders LDS traffic between the lanes of a workgroup without waiting for global
+// stores in flight (a full __syncthreads would drain them).  One wavefront executes
+// its LDS operations in order, so a single-wave workgroup only pins the code order.
+template <int WAVES>
+__device__ __forceinline__ void lds_barrier()
+{
+    if (WAVES == 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    }
+}
 
 __device__ __forceinline__ int terrain_code(const KArgs &a, int e, float x, float y)
 {
@@ -221,8 +241,8 @@ __device__ __forceinline__ Place locate(const KArgs &a)
 }
 
 // How many lanes of the caller's env satisfy each of four predicates.
-template <int WAVES, int NW>
-__device__ __forceinline__ void env_counts(Shared<WAVES, NW> &sh, const Place &P, int N,
+template <int WAVES>
+__device__ __forceinline__ void env_counts(Shared<WAVES> &sh, const Place &P, int N,
                                            const bool (&pred)[4], int (&cnt)[4])
 {
     if (WAVES == 1) {
@@ -236,27 +256,27 @@ __device__ __forceinline__ void env_counts(Shared<WAVES, NW> &sh, const Place &P
             const uint64_t b = __ballot(pred[q]);
             if ((P.l & 63) == 0) sh.ballots[wv][q] = b;
         }
-        __syncthreads();
+        lds_barrier<WAVES>();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             cnt[q] = 0;
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) cnt[q] += __popcll(sh.ballots[w][q]);
         }
-        __syncthreads();
+        lds_barrier<WAVES>();
     }
 }
 
 // Mean health ratio of both teams over their enabled units (the bracketed means of
 // Eq. 1): the terms published in sh.share are added in ascending unit index; a term
 // of +0.0f (unit of the other team, or disabled) leaves a finite sum unchanged.
-template <int WAVES, int NW>
-__device__ __forceinline__ void team_means(const Shared<WAVES, NW> &sh, const Place &P, int N,
+template <int WAVES>
+__device__ __forceinline__ void team_means(const Shared<WAVES> &sh, const Place &P, int N,
                                            int c0, int c1, float &m0, float &m1)
 {
     float s0 = 0.0f, s1 = 0.0f;
     for (int jj = 0; jj < N; ++jj) {
-        const float2 q = sh.share[P.base + jj];
+        const float2 q = sh.st.share[P.base + jj];
         s0 = s0 + q.x;
         s1 = s1 + q.y;
     }
@@ -278,8 +298,8 @@ __device__ __forceinline__ float hurtbox_gap2(float dx, float dy, float ci, floa
     return (ex * ex) + (ey * ey);
 }
 
-template <int WAVES, int NW>
-__device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, const Place &P,
+template <int WAVES>
+__device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, const Place &P,
                                          Unit &U, int &code_u)
 {
     const int N = a.p.num_units;
@@ -329,9 +349,9 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
         heading_sincos(U.theta, su, cu);
     }
     // flags: team of a unit alive at entry, 2 for anything that cannot be a target
-    sh.pj[P.l] = make_float4(U.x, U.y, U.radius * U.radius,
+    sh.st.pj[P.l] = make_float4(U.x, U.y, U.radius * U.radius,
                              __int_as_float(alive0 ? U.team : 2));
-    __syncthreads();
+    lds_barrier<WAVES>();
 
     // stage 2b: attackable row of this unit over its env, closest valid target
     // (strict "<" keeps the lowest index on ties)
@@ -341,7 +361,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
         const float neg_hw = -U.hurt_hw;
         float best = kInf;
         for (int jj = 0; jj < N; ++jj) {
-            const float4 J = sh.pj[P.base + jj];
+            const float4 J = sh.st.pj[P.base + jj];
             const float dx = J.x - U.x;
             const float dy = J.y - U.y;
             float along;
@@ -356,8 +376,8 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
     const bool eligible = has && alive0 && act == TABX_ACT_ATTACK && U.cd <= 0.0f;
     if (eligible) U.cd = U.cooldown;
     const bool landed = eligible && target >= 0;
-    sh.hitrec[P.l] = make_int2(landed ? target : -1, __float_as_int(U.dmg));
-    __syncthreads();
+    sh.st.hitrec[P.l] = make_int2(landed ? target : -1, __float_as_int(U.dmg));
+    lds_barrier<WAVES>();
 
     // stage 2c: victim side.  Sum what the attackers that designated this unit
     // deal, ascending attacker index; subtract once with the arena penalty; clamp.
@@ -365,7 +385,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
         float acc = 0.0f;
         bool struck = landed && U.dmg > 0.0f;
         for (int ii = 0; ii < N; ++ii) {
-            const int2 h = sh.hitrec[P.base + ii];
+            const int2 h = sh.st.hitrec[P.base + ii];
             const bool mine = h.x == P.u;
             const float d = __int_as_float(h.y);
             acc = acc + (mine ? d : 0.0f);
@@ -396,13 +416,13 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
         }
     }
     const bool en = has && U.enabled;
-    sh.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
+    sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
                                 (en && U.team != 0) ? ratio : 0.0f);
     const bool pred[4] = {en && U.team == 0, en && U.team != 0,
                           has && U.alive && U.team == 0, has && U.alive && U.team != 0};
     int cnt[4];
     env_counts(sh, P, N, pred, cnt);
-    __syncthreads();
+    lds_barrier<WAVES>();
 
     // reward (Eq. 1), termination, terminal bonus
     float m0, m1;
@@ -413,6 +433,17 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
     const float dense = phi - phi_prev;
     float r0 = dense, r1 = -dense;
     const bool done = has && (cnt[2] == 0 || cnt[3] == 0 || t_new >= a.p.max_steps);
+    // does any env of this workgroup restart?  (one env per workgroup when WAVES == 2:
+    // the flag is already uniform there, up to the idle lanes)
+    bool any_done;
+    if (WAVES == 1) {
+        any_done = __ballot(done) != 0ull;
+    } else {
+        const uint64_t b = __ballot(done);
+        if ((P.l & 63) == 0) sh.ballots[P.l >> 6][0] = b;
+        lds_barrier<WAVES>();
+        any_done = (sh.ballots[0][0] | sh.ballots[WAVES - 1][0]) != 0ull;
+    }
     if (done) {
         const bool ally_win = m0 > m1;
         r0 = r0 + (ally_win ? 1.0f : -1.0f);
@@ -422,14 +453,15 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
 
     // auto-reset of finished envs; the potential of the fresh state seeds phi_prev
     float phi_next = phi;
-    if (__syncthreads_or(done ? 1 : 0)) {
+    lds_barrier<WAVES>();          // everyone has read the ratio terms of the finished tick
+    if (any_done) {
         if (done) {
             code_u = spawn_unit(a, P.e, P.k, U);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
         }
-        sh.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
+        sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
                                     (en && U.team != 0) ? ratio : 0.0f);
-        __syncthreads();
+        lds_barrier<WAVES>();
         float f0, f1;
         team_means(sh, P, N, cnt[0], cnt[1], f0, f1);
         if (done) phi_next = f0 - f1;
@@ -442,259 +474,213 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES, NW> &sh, 
     if (has) store_state(a, P.k, U);
 }
 
-// Removes bit i from a multi-word mask, moving the bits above it down by one.
-template <int NW>
-__device__ __forceinline__ void drop_bit(const uint32_t (&m)[NW], int i, uint32_t (&out)[NW])
-{
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        const int lo = i - 32 * w;          // bits of this word below `lo` keep their place
-        const uint32_t keep = lo >= 32 ? 0xffffffffu : (lo <= 0 ? 0u : ((1u << lo) - 1u));
-        const uint32_t next = (w + 1 < NW) ? m[w + 1] : 0u;
-        const uint32_t shifted = (m[w] >> 1) | (next << 31);
-        out[w] = (m[w] & keep) | (shifted & ~keep);
-    }
-}
-
-template <int WAVES, int NW>
-__device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES, NW> &sh,
-                                            float *zone_lds, const Place &P, const Unit &U,
-                                            int code_u)
+// Observation rows of every unit of the workgroup's envs, visibility masks, action masks.
+//
+// Staged row layout in LDS (floats): [pad][own block 15][other-unit blocks 16 * (N - 1)]
+// [zone slots 6 * Z][pad...], pitch = row_pitch.  The pad in front makes every 16-float
+// block and every 4-float zone chunk 16-byte aligned in LDS; a 16-byte chunk q of a staged
+// row holds row floats 4q - 1 .. 4q + 2 and goes to HBM with one 4-byte-aligned 16-byte
+// store.  The own blocks are kept for all units in `own` (same shifted layout) and are
+// picked up from there by the chunks q < 4.
+template <int WAVES>
+__device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *dyn,
+                                            const Place &P, const Unit &U, int code_u)
 {
     constexpr int LANES = 64 * WAVES;
     const int N = a.p.num_units;
     const int G = a.envs_per_block;
     const int D = a.obs_dim;
+    const int Dp = a.row_pitch;
+    const int CPR = Dp >> 2;                     // 16-byte chunks per staged row
     const int zlen = 6 * a.p.max_zones;
+    const int n1 = N - 1;
     const bool has = P.has;
-
-    __syncthreads();                 // LDS of the step stage is free to reuse
-    float cu = 1.0f, su = 0.0f;
-    {
-        const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
-        const int alive = has ? U.alive : 0;
-        const int hidden = (in_bush && !(U.reveal > 0.0f)) ? 1 : 0;
-        const int flags = alive | (U.team << 1) | (hidden << 2) | ((code_u & 0xff) << 8);
-        sh.pj[P.l] = make_float4(U.x, U.y, U.radius * U.radius, __int_as_float(flags));
-        const int info = P.u | (P.base << 8) | ((has && U.enabled) ? (1 << 16) : 0) | (P.g << 24);
-        sh.row[P.l] = make_float4(U.x, U.y, __int_as_float(info), 0.0f);
-        if (has) {
-            heading_sincos(U.theta, su, cu);
-            float4 *t = reinterpret_cast<float4 *>(sh.tab[P.l]);
-            t[0] = make_float4(U.hp, U.hp / U.hmax, U.x, U.y);
-            t[1] = make_float4(U.theta, U.range, U.dmg, U.cd);
-            t[2] = make_float4(U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f, U.radius, U.mass,
-                               U.sight_angle);
-            // own block ends with (alive, speed, zone); other-unit blocks read the
-            // speed from the last column and get columns 13, 14 from the masks
-            t[3] = make_float4(U.alive ? 1.0f : 0.0f, U.cur_speed, (float)(code_u & 3),
-                               U.cur_speed);
-            if (a.action_mask) a.action_mask[P.k] = (U.alive && U.cd <= 0.0f) ? 1 : 0;
-        }
-    }
-    // zone slots of each env slot: value (zero if the slot is inactive) and which
-    // own coordinate to subtract (centre x / y of an active slot)
-    float    *zv = zone_lds;
-    uint32_t *zmx = reinterpret_cast<uint32_t *>(zone_lds + G * zlen);
-    uint32_t *zmy = zmx + G * zlen;
-    for (int q = P.l; q < G * zlen; q += LANES) {
-        const int g = q / zlen;
-        const int e = blockIdx.x * G + g;
-        float v = 0.0f;
-        uint32_t mx = 0, my = 0;
-        if (e < a.p.num_envs) {
-            const int zz = q - g * zlen;
-            const int comp = zz % 6;
-            const float *d = a.sc.zone_desc + (size_t)e * zlen;
-            const bool active = d[zz - comp] != 0.0f;
-            v = active ? d[zz] : 0.0f;
-            mx = (active && comp == 1) ? 0xffffffffu : 0u;
-            my = (active && comp == 2) ? 0xffffffffu : 0u;
-        }
-        zv[q] = v;
-        zmx[q] = mx;
-        zmy[q] = my;
-    }
-    __syncthreads();
-
-    // visibility / attackable / same-team rows of this unit over its env
-    uint32_t vis[NW], att[NW], same[NW];
-    {
-        const bool heals = U.dmg < 0.0f;
-        const bool seer = has && U.alive;
-        const float R2 = U.sight_range * U.sight_range;
-        const float neg_hw = -U.hurt_hw;
-        const int bush_key = ((code_u & 3) == TABX_ZONE_BUSH) ? (code_u & 0xff) : -1;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            uint32_t v = 0, t = 0, s = 0;
-            const int jend = (N - 32 * w) < 32 ? (N - 32 * w) : 32;
-            for (int b = 0; b < jend; ++b) {
-                const int jj = 32 * w + b;
-                const float4 J = sh.pj[P.base + jj];
-                const int fj = __float_as_int(J.w);
-                const float dx = J.x - U.x;
-                const float dy = J.y - U.y;
-                float dot;
-                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, dot);
-                const float d2 = (dx * dx) + (dy * dy);
-                const bool in_range = d2 <= R2;
-                const bool in_cone = (d2 == 0.0f) || (dot >= U.cos_half * __builtin_sqrtf(d2));
-                const bool same_team = ((fj >> 1) & 1) == U.team;
-                const bool same_bush = (fj >> 8) == bush_key;
-                const bool concealed = (fj & 4) && !same_team && !same_bush;
-                const bool pair = seer && (fj & 1) && (jj != P.u);
-                const bool seen = pair && in_range && in_cone && !concealed;
-                const bool hit = pair && (heals == same_team) && (g2 <= J.z);
-                const uint32_t bit = 1u << b;
-                v |= seen ? bit : 0u;
-                t |= hit ? bit : 0u;
-                s |= same_team ? bit : 0u;
-            }
-            vis[w] = v;
-            att[w] = t;
-            same[w] = s;
-        }
-    }
-    if (has && a.vis_mask) {
-        const int words = (N + 63) >> 6;
-#pragma unroll
-        for (int w = 0; w < (NW + 1) / 2; ++w) {
-            const uint64_t lo = vis[2 * w];
-            const uint64_t hi = (2 * w + 1 < NW) ? vis[2 * w + 1] : 0u;
-            if (w < words) a.vis_mask[P.k * words + w] = lo | (hi << 32);
-        }
-    }
-    {
-        uint32_t sv[NW], sa[NW], st[NW];
-        drop_bit<NW>(vis, P.u, sv);
-        drop_bit<NW>(att, P.u, sa);
-        drop_bit<NW>(same, P.u, st);
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            sh.V[P.l][w] = sv[w];
-            sh.A[P.l][w] = sa[w];
-            sh.T[P.l][w] = st[w];
-        }
-    }
-    __syncthreads();
-
-    // ---- writer.  Rows are the units of this workgroup's envs in lane order.  Each wave
-    // builds a group of whole rows in its LDS staging area (other-unit blocks, own
-    // blocks, zone slots) and then streams the group to HBM front to back, 1 KB per
-    // store instruction, so that every cache line is completed by consecutive stores;
-    // rows written piecemeal leave partly written lines behind and cost twice the time.
-    const int envs_here = (a.p.num_envs - blockIdx.x * G) < G ? (a.p.num_envs - blockIdx.x * G) : G;
-    const int rows = envs_here * N;
-    float *out = a.obs + (size_t)blockIdx.x * G * N * D;
     const int lane = P.l & 63;
     const int wv = P.l >> 6;
-    const int RG = a.rows_per_group;
-    float *stg = zone_lds + a.stage_offset + wv * a.stage_floats;
-    const int n1 = N - 1;
-    const int zoff = 15 + 16 * n1;
-    const int grp = lane & 3;
-    const bool first = grp == 0, last = grp == 3;
-    // (row, slot) pair of this lane in the first pass over a group; a pass covers 16 pairs
-    const int sp0 = lane >> 2;
-    const int rl0 = n1 > 0 ? sp0 / n1 : 0;
-    const int s0 = sp0 - rl0 * n1;
-    const int wraps = n1 > 0 ? (16 + n1 - 1) / n1 : 0;
-    // (row, zone float) of this lane in the first pass over a group's zone slots
-    const int rlz0 = zlen > 0 ? lane / zlen : 0;
-    const int zz0 = lane - rlz0 * zlen;
-    const int wraps_z = zlen > 0 ? (64 + zlen - 1) / zlen : 0;
+    const int envs_here = (a.p.num_envs - blockIdx.x * G) < G ? (a.p.num_envs - blockIdx.x * G) : G;
 
-    for (int r0 = wv * RG; r0 < rows; r0 += WAVES * RG) {
-        const int nr = (rows - r0) < RG ? (rows - r0) : RG;
-        // other-unit blocks: four lanes per 16-float block
-        {
-            const int total = nr * n1;
-            int rl = rl0, s = s0;
-            for (int sp = sp0; sp < total; sp += 16) {
-                const int r = r0 + rl;
-                const float4 R = sh.row[r];
-                const int info = __float_as_int(R.z);
-                const int i = info & 0xff;
-                const int rbase = (info >> 8) & 0xff;
-                const int j = s + (s >= i ? 1 : 0);
-                float4 t = *reinterpret_cast<const float4 *>(&sh.tab[rbase + j][grp * 4]);
-                const int ws = (NW == 1) ? 0 : (s >> 5);
-                const int seen = __builtin_amdgcn_sbfe((int)sh.V[r][ws], s & 31, 1);   // 0 or -1
-                const int atk = __builtin_amdgcn_sbfe((int)sh.A[r][ws], s & 31, 1);
-                const int ally = __builtin_amdgcn_sbfe((int)sh.T[r][ws], s & 31, 1);
-                // relative position (first quarter), team / attackable flags (last quarter)
-                t.z = t.z - (first ? R.x : 0.0f);
-                t.w = t.w - (first ? R.y : 0.0f);
-                const float one = 1.0f;
-                t.y = last ? __int_as_float(ally & __float_as_int(one)) : t.y;
-                t.z = last ? __int_as_float(atk & __float_as_int(one)) : t.z;
-                float *d = stg + (rl * D + 15 + s * 16 + grp * 4);
-                d[0] = __int_as_float(__float_as_int(t.x) & seen);
-                d[1] = __int_as_float(__float_as_int(t.y) & seen);
-                d[2] = __int_as_float(__float_as_int(t.z) & seen);
-                d[3] = __int_as_float(__float_as_int(t.w) & seen);
-                s += 16;
-                for (int w = 0; w < wraps; ++w) {
-                    const bool wrap = s >= n1;
-                    s = wrap ? s - n1 : s;
-                    rl = wrap ? rl + 1 : rl;
+    float *own = dyn;                            // [LANES][16]
+    float *stg = dyn + LANES * 16;               // WAVES == 1: G rows; WAVES == 2: two buffers of one row
+
+    lds_barrier<WAVES>();                        // the step stage is done with the LDS union
+
+    // ---- publish this unit as an observer, and its own block
+    float cu = 1.0f, su = 0.0f;
+    const int alive = has ? U.alive : 0;
+    const bool enabled = has && U.enabled;
+    const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
+    const int my_code = code_u & 0xff;
+    const bool hidden = in_bush && !(U.reveal > 0.0f);
+    const float ratio = U.hp / U.hmax;
+    const float cd_ratio = U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f;
+    const float r2_me = U.radius * U.radius;
+    {
+        if (has) heading_sincos(U.theta, su, cu);
+        const int key = in_bush ? my_code : 0x100;         // 0x100 matches no cell code
+        sh.ob.pose[P.l] = make_float4(U.x, U.y, cu, su);
+        sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
+        sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | (key << 8);
+        float4 *t = reinterpret_cast<float4 *>(own + P.l * 16);
+        const float4 zero4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        t[0] = enabled ? make_float4(0.0f, U.hp, ratio, U.x) : zero4;
+        t[1] = enabled ? make_float4(U.y, U.theta, U.range, U.dmg) : zero4;
+        t[2] = enabled ? make_float4(U.cd, cd_ratio, U.radius, U.mass) : zero4;
+        t[3] = enabled ? make_float4(U.sight_angle, alive ? 1.0f : 0.0f, U.cur_speed, (float)(code_u & 3))
+                       : zero4;
+        if (has && a.action_mask) a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
+    }
+
+    // ---- zone chunks: lane (env slot zg, chunk zc) keeps its four zone floats in registers:
+    // value (zero if the slot is inactive) and which observer coordinate to subtract
+    const int ZC = (zlen + 3) >> 2;
+    const int zg = ZC > 0 ? P.l / ZC : 0;
+    const int zc = P.l - zg * ZC;
+    const bool zone_lane = ZC > 0 && zg < envs_here;
+    float zval[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    int zsx[4] = {0, 0, 0, 0}, zsy[4] = {0, 0, 0, 0};
+    if (zone_lane) {
+        const float *d = a.sc.zone_desc + (size_t)(blockIdx.x * G + zg) * zlen;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int zz = 4 * zc + k;
+            if (zz < zlen) {
+                const int comp = zz % 6;
+                const bool active = d[zz - comp] != 0.0f;
+                zval[k] = active ? d[zz] : 0.0f;
+                zsx[k] = (active && comp == 1) ? -1 : 0;
+                zsy[k] = (active && comp == 2) ? -1 : 0;
+            }
+        }
+    }
+    const int zone_seer0 = (WAVES == 1) ? zg * N : 0;     // lane of observer 0 of the zone lane's env
+    const int zone_dst0 = ((WAVES == 1) ? zg * Dp : 0) + 16 + 16 * n1 + 4 * zc;
+
+    // ---- store passes: chunk t = p * LANES + l of the staged rows -> (row slot, chunk in row)
+    unsigned dst_off[kMaxPasses];
+    int src_idx[kMaxPasses], src_step[kMaxPasses], valid[kMaxPasses];
+#pragma unroll
+    for (int p = 0; p < kMaxPasses; ++p) {
+        const int t = p * LANES + P.l;
+        const int tg = t / CPR;
+        const int q = t - tg * CPR;
+        int vm = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int o = 4 * q - 1 + k;
+            vm |= (o >= 0 && o < D) ? (1 << k) : 0;
+        }
+        valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
+        dst_off[p] = (unsigned)(tg * N * D + 4 * q);          // relative to (row base - 1)
+        const bool from_own = q < 4;
+        src_idx[p] = from_own ? ((WAVES == 1 ? tg * N : 0) * 16 + 4 * q) : (LANES * 16 + 4 * t);
+        src_step[p] = from_own ? 16 : 0;
+    }
+
+    lds_barrier<WAVES>();
+
+    // ---- one pass per observer index i: every lane's unit seen from observer i of its env
+    float *out = a.obs + (size_t)blockIdx.x * G * N * D;
+    const int blk_dst0 = ((WAVES == 1) ? P.g * Dp : 0) + 16 + 16 * P.u;
+    for (int i = 0; i < N; ++i) {
+        const int oi = P.base + i;
+        const float4 A = sh.ob.pose[oi];
+        const float4 B = sh.ob.reach[oi];
+        const int fi = sh.seer[oi];
+        const int buf = (WAVES == 1) ? 0 : (i & 1) * Dp;
+        // offset of this unit from the observer, in the observer's frame
+        const float dx = U.x - A.x;
+        const float dy = U.y - A.y;
+        float dot;
+        const float g2 = hurtbox_gap2(dx, dy, A.z, A.w, B.x, B.y, -B.y, dot);
+        const float d2 = (dx * dx) + (dy * dy);
+        const bool in_range = d2 <= B.z;
+        const bool in_cone = (d2 == 0.0f) || (dot >= B.w * __builtin_sqrtf(d2));
+        const bool same_team = ((fi >> 1) & 1) == U.team;
+        const bool same_bush = (fi >> 8) == my_code;
+        const bool concealed = hidden && !same_team && !same_bush;
+        const bool pair = alive && (fi & 1) && (i != P.u);
+        const bool seen = pair && in_range && in_cone && !concealed;
+        const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me);
+        if (a.vis_mask) {
+            const uint64_t b = __ballot(seen);
+            if (lane == 0) sh.rowbits[i][wv] = b;
+        }
+        if (has && i != P.u) {
+            const int m = seen ? -1 : 0;
+            float4 *d = reinterpret_cast<float4 *>(stg + buf + blk_dst0 - (P.u > i ? 16 : 0));
+            d[0] = make_float4(__int_as_float(__float_as_int(U.hp) & m),
+                               __int_as_float(__float_as_int(ratio) & m),
+                               __int_as_float(__float_as_int(dx) & m),
+                               __int_as_float(__float_as_int(dy) & m));
+            d[1] = make_float4(__int_as_float(__float_as_int(U.theta) & m),
+                               __int_as_float(__float_as_int(U.range) & m),
+                               __int_as_float(__float_as_int(U.dmg) & m),
+                               __int_as_float(__float_as_int(U.cd) & m));
+            d[2] = make_float4(__int_as_float(__float_as_int(cd_ratio) & m),
+                               __int_as_float(__float_as_int(U.radius) & m),
+                               __int_as_float(__float_as_int(U.mass) & m),
+                               __int_as_float(__float_as_int(U.sight_angle) & m));
+            d[3] = make_float4(seen ? 1.0f : 0.0f, (seen && same_team) ? 1.0f : 0.0f,
+                               (seen && hit) ? 1.0f : 0.0f,
+                               __int_as_float(__float_as_int(U.cur_speed) & m));
+        }
+        if (zone_lane) {
+            const float4 Z = sh.ob.pose[zone_seer0 + i];
+            const int en = (sh.seer[zone_seer0 + i] & 8) ? -1 : 0;
+            const int xb = __float_as_int(Z.x), yb = __float_as_int(Z.y);
+            float zo[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float shift = __int_as_float((xb & zsx[k]) | (yb & zsy[k]));
+                zo[k] = __int_as_float(__float_as_int(zval[k] - shift) & en);
+            }
+            *reinterpret_cast<float4 *>(stg + buf + zone_dst0) = make_float4(zo[0], zo[1], zo[2], zo[3]);
+        }
+        lds_barrier<WAVES>();
+
+        // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
+        float *row_m1 = out + (i * D - 1);
+#pragma unroll
+        for (int p = 0; p < kMaxPasses; ++p) {
+            if (p < a.copy_passes) {
+                const int from_own = src_step[p];
+                const int idx = src_idx[p] + (from_own ? 16 * i : buf);
+                const float4 v = *reinterpret_cast<const float4 *>(dyn + idx);
+                float *dp = row_m1 + dst_off[p];
+                const int vm = valid[p];
+                if (vm == 15) {
+                    f4u o = {v.x, v.y, v.z, v.w};
+                    *reinterpret_cast<f4u *>(dp) = o;
+                } else if (vm != 0) {
+                    if (vm & 1) dp[0] = v.x;
+                    if (vm & 2) dp[1] = v.y;
+                    if (vm & 4) dp[2] = v.z;
+                    if (vm & 8) dp[3] = v.w;
                 }
             }
         }
-        // own blocks: 16 lanes per row, 15 of them store
-        {
-            const int c = lane & 15;
-            for (int rl = lane >> 4; rl < nr; rl += 4) {
-                const int r = r0 + rl;
-                const int info = __float_as_int(sh.row[r].z);
-                const float v = sh.tab[r][c];
-                if (c < 15) stg[rl * D + c] = (info & (1 << 16)) ? v : 0.0f;
-            }
-        }
-        // zone slots: lane per float over the group's rows
-        if (zlen > 0) {
-            const int total = nr * zlen;
-            int rl = rlz0, zz = zz0;
-            for (int t = lane; t < total; t += 64) {
-                const float4 R = sh.row[r0 + rl];
-                const int info = __float_as_int(R.z);
-                const int q = ((info >> 24) & 0xff) * zlen + zz;
-                const uint32_t shift = (__float_as_int(R.x) & zmx[q]) | (__float_as_int(R.y) & zmy[q]);
-                const float v = zv[q] - __int_as_float((int)shift);
-                stg[rl * D + zoff + zz] = (info & (1 << 16)) ? v : 0.0f;
-                zz += 64;
-                for (int w = 0; w < wraps_z; ++w) {
-                    const bool wrap = zz >= zlen;
-                    zz = wrap ? zz - zlen : zz;
-                    rl = wrap ? rl + 1 : rl;
-                }
-            }
-        }
-        // LDS operations of one wave execute in order; the barrier only pins the code order
-        __builtin_amdgcn_wave_barrier();
-        const int nfl = nr * D;
-        float *dst = out + r0 * D;
-        for (int i = lane * 4; i < nfl; i += 256) {
-            const float4 v = *reinterpret_cast<const float4 *>(stg + i);
-            if (i + 3 < nfl) {
-                f4u o = {v.x, v.y, v.z, v.w};
-                *reinterpret_cast<f4u *>(dst + i) = o;
+        if (WAVES == 1) lds_barrier<WAVES>();    // two waves alternate between two staging buffers
+    }
+
+    if (a.vis_mask) {
+        lds_barrier<WAVES>();
+        if (has) {
+            if (WAVES == 1) {
+                const uint64_t range = N >= 64 ? ~0ull : ((1ull << N) - 1ull);
+                a.vis_mask[P.k] = (sh.rowbits[P.u][0] >> P.base) & range;
             } else {
-                dst[i] = v.x;
-                if (i + 1 < nfl) dst[i + 1] = v.y;
-                if (i + 2 < nfl) dst[i + 2] = v.z;
+                const int words = (N + 63) >> 6;
+                for (int w = 0; w < words; ++w) a.vis_mask[P.k * words + w] = sh.rowbits[P.u][w];
             }
         }
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
-template <int WAVES, int NW, bool DO_STEP, bool DO_OBS>
+template <int WAVES, bool DO_STEP, bool DO_OBS>
 __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
 {
-    __shared__ Shared<WAVES, NW> sh;
-    extern __shared__ __attribute__((aligned(16))) float zone_lds[];
+    __shared__ Shared<WAVES> sh;
+    extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
     const Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
@@ -702,15 +688,15 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         load_spec(a, P.k, U);
         load_state(a, P.k, U);
     }
-    if (DO_STEP) step_env<WAVES, NW>(a, sh, P, U, code_u);
+    if (DO_STEP) step_env<WAVES>(a, sh, P, U, code_u);
     else if (P.has) code_u = terrain_code(a, P.e, U.x, U.y);
-    if (DO_OBS) observe_env<WAVES, NW>(a, sh, zone_lds, P, U, code_u);
+    if (DO_OBS) observe_env<WAVES>(a, sh, dyn_lds, P, U, code_u);
 }
 
-template <int WAVES, int NW>
+template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
 {
-    __shared__ Shared<WAVES, NW> sh;
+    __shared__ Shared<WAVES> sh;
     const Place P = locate<WAVES>(a);
     const int N = a.p.num_units;
     const bool go = P.has && !(a.env_mask && a.env_mask[P.e] == 0);
@@ -723,12 +709,12 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
         store_state(a, P.k, U);
     }
     const bool en = go && U.enabled;
-    sh.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
-                                (en && U.team != 0) ? ratio : 0.0f);
+    sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
+                                   (en && U.team != 0) ? ratio : 0.0f);
     const bool pred[4] = {en && U.team == 0, en && U.team != 0, false, false};
     int cnt[4];
     env_counts(sh, P, N, pred, cnt);
-    __syncthreads();
+    lds_barrier<WAVES>();
     float m0, m1;
     team_means(sh, P, N, cnt[0], cnt[1], m0, m1);
     if (go && P.u == 0) {
@@ -793,25 +779,28 @@ static int check_state(const TabxState *s)
     return TABX_OK;
 }
 
-template <int WAVES, int NW>
+template <int WAVES>
 static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
 {
     const int G = a.envs_per_block;
     const dim3 grid((unsigned)((a.p.num_envs + G - 1) / G)), block(64 * WAVES);
-    const size_t zone_bytes = ((size_t)a.stage_offset + (size_t)WAVES * a.stage_floats) * sizeof(float);
+    // dynamic LDS: own blocks of all lanes, then the staged rows (G rows for a single
+    // wavefront, two alternating one-row buffers for a two-wave workgroup)
+    const size_t rows_staged = WAVES == 1 ? (size_t)G : 2;
+    const size_t dyn_bytes = ((size_t)64 * WAVES * 16 + rows_staged * a.row_pitch) * sizeof(float);
     switch (mode) {
     case MODE_RESET:
-        hipLaunchKernelGGL((tabx_reset_kernel<WAVES, NW>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
         break;
     case MODE_STEP:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, NW, true, false>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false>), grid, block, 0, stream, a);
         break;
     case MODE_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, NW, false, true>), grid, block, zone_bytes,
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true>), grid, block, dyn_bytes,
                            stream, a);
         break;
     case MODE_STEP_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, NW, true, true>), grid, block, zone_bytes,
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, true>), grid, block, dyn_bytes,
                            stream, a);
         break;
     }
@@ -852,16 +841,27 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
 
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
-    // N <= 64: one wavefront per workgroup, floor(64 / N) envs packed into it;
-    // 64 < N <= 128: two wavefronts per env
-    a.envs_per_block = p->num_units <= 64 ? 64 / p->num_units : 1;
-    // observation rows are staged in LDS in groups of about 6 KB per wave
-    a.rows_per_group = 1536 / a.obs_dim > 0 ? 1536 / a.obs_dim : 1;
-    a.stage_floats = (a.rows_per_group * a.obs_dim + 3) & ~3;
-    a.stage_offset = (3 * a.envs_per_block * 6 * p->max_zones + 3) & ~3;
-    if (p->num_units <= 32) launch_mode<1, 1>(mode, a, s);
-    else if (p->num_units <= 64) launch_mode<1, 2>(mode, a, s);
-    else launch_mode<2, 4>(mode, a, s);
+    // N <= 64: one wavefront per workgroup with G whole envs packed into it; G is floor(64 / N)
+    // unless the staged rows of G envs would need more than kMaxPasses store passes or more
+    // zone chunks than lanes.  64 < N <= 128: two wavefronts per env.
+    const int N = p->num_units;
+    const int waves = N <= 64 ? 1 : 2;
+    a.row_pitch = (a.obs_dim + 1 + 3) & ~3;
+    const int cpr = a.row_pitch / 4;
+    const int zc = (6 * p->max_zones + 3) / 4;
+    int G = 1;
+    if (waves == 1) {
+        G = 64 / N;
+        const int by_passes = kMaxPasses * 64 / cpr;
+        if (G > by_passes) G = by_passes;
+        if (zc > 0 && G > 64 / zc) G = 64 / zc;
+        if (G < 1) G = 1;
+    }
+    a.envs_per_block = G;
+    a.copy_passes = (G * cpr + 64 * waves - 1) / (64 * waves);
+    if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
+    if (waves == 1) launch_mode<1>(mode, a, s);
+    else launch_mode<2>(mode, a, s);
     return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
 }
 
