@@ -102,7 +102,7 @@ typedef struct TabxState {
     float   *phi_prev;   /* [E] health-ratio potential after the previous tick */
 } TabxState;
 
-/* Floats per agent observation: 15 + 16 * (N - 1) + 6 * max_zones.
+/* Floats per agent observation: 16 * N + 6 * max_zones.
  * Negative TabxError if the shape is unsupported. */
 int tabx_obs_dim(const TabxParams *params);
 int tabx_num_actions(void);
@@ -122,8 +122,17 @@ int tabx_step(const TabxParams *params, const TabxScenario *scenario,
 
 /* Per-agent observations of the current state (App. A "Observation and Global
  * State", "Action Space" for the mask).
- *   obs [E][N][D] f32 (out): own block (15), other-unit blocks (16 each,
- *     ascending unit index without self, zero unless visible), zone slots (6 each);
+ *   obs [E][N][D] f32 (out): own block (16 floats), other-unit blocks (16 each,
+ *     ascending unit index without self, all zero unless visible), zone slots (6 each);
+ *     own = health, health / max, x, y, heading, attack range, damage, cooldown left,
+ *           cooldown left / cooldown, body radius, mass, sight angle, alive, current
+ *           speed, zone type underfoot, team;
+ *     other = health, health / max, x - own x, y - own y, heading, attack range, damage,
+ *           cooldown left, cooldown ratio, body radius, mass, sight angle, alive (1),
+ *           same team, attackable by the observer, current speed;
+ *     zone = type, centre x - own x, centre y - own y, half extent x, half extent y,
+ *           effect magnitude (all zero for a slot of type 0);
+ *     a disabled unit's row is all zero;
  *   vis_mask [E][N][ceil(N/64)] u64 (out, NULL to skip): bit j of row i = i sees j;
  *   action_mask [E][N] u8 (out, NULL to skip): 1 = the combat action is available. */
 int tabx_observe(const TabxParams *params, const TabxScenario *scenario,

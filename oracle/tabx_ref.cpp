@@ -334,13 +334,14 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
         row[12] = st.alive[ki] ? 1.0f : 0.0f;
         row[13] = st.cur_speed[ki];
         row[14] = (float)(code[i] & 3);
+        row[15] = (float)S.team[ki];
 
         /* other units, ascending index, self skipped */
         int slot = 0;
         for (int j = 0; j < N; ++j) {
             if (j == i) continue;
             const int kj = b + j;
-            float *o = row + 15 + 16 * slot;
+            float *o = row + 16 + 16 * slot;
             slot += 1;
             if (!st.alive[ki] || !st.alive[kj]) continue;
 
@@ -403,7 +404,7 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
         for (int z = 0; z < Z; ++z) {
             if (!S.zone_desc) break;
             const float *d = S.zone_desc + ((long)e * Z + z) * 6;
-            float *o = row + 15 + 16 * (N - 1) + 6 * z;
+            float *o = row + 16 * N + 6 * z;
             if (d[0] == 0.0f) continue;
             o[0] = d[0];
             o[1] = d[1] - st.x[ki];
@@ -421,7 +422,7 @@ extern "C" {
 
 int tabx_ref_obs_dim(const RefParams *p)
 {
-    return 15 + 16 * (p->num_units - 1) + 6 * p->max_zones;
+    return 16 * p->num_units + 6 * p->max_zones;
 }
 
 void tabx_ref_sincos(float theta, float *s, float *c) { sincos_spec(theta, s, c); }

@@ -44,7 +44,7 @@ struct KArgs {
     uint8_t  *action_mask;
     int       obs_dim;             // D
     int       envs_per_block;      // G
-    int       row_pitch;           // floats between staged rows: D + 1 rounded up to 4
+    int       row_pitch;           // floats between staged rows: D rounded up to 4
     int       copy_passes;         // ceil(G * row_pitch / 4 / lanes), <= kMaxPasses
 };
 
@@ -476,14 +476,13 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
 
 // Observation rows of every unit of the workgroup's envs, visibility masks, action masks.
 //
-// Staged row layout in LDS (floats): [pad][own block 15][other-unit blocks 16 * (N - 1)]
-// [zone slots 6 * Z][pad...], pitch = row_pitch.  The pad in front makes every 16-float
-// block and every 4-float zone chunk 16-byte aligned in LDS; a 16-byte chunk q of a staged
-// row holds row floats 4q - 1 .. 4q + 2 and goes to HBM with one 4-byte-aligned 16-byte
-// store.  The own blocks are kept for all units in `own` (same shifted layout) and are
-// picked up from there by the chunks q < 4.
+// A row is N blocks of 16 floats (the observer's own block first, then the other units in
+// ascending index) followed by the zone slots.  The rows of pass i (observer i of every env
+// packed in the workgroup) are assembled in LDS as exact images of the HBM rows, pitch
+// row_pitch = D rounded up to 4 floats, and then go out in 16-byte chunks, chunk t of the
+// staged rows handled by lane t % lanes of store pass t / lanes.
 template <int WAVES>
-__device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *dyn,
+__device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *stg,
                                             const Place &P, const Unit &U, int code_u)
 {
     constexpr int LANES = 64 * WAVES;
@@ -493,18 +492,14 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int Dp = a.row_pitch;
     const int CPR = Dp >> 2;                     // 16-byte chunks per staged row
     const int zlen = 6 * a.p.max_zones;
-    const int n1 = N - 1;
     const bool has = P.has;
     const int lane = P.l & 63;
     const int wv = P.l >> 6;
     const int envs_here = (a.p.num_envs - blockIdx.x * G) < G ? (a.p.num_envs - blockIdx.x * G) : G;
 
-    float *own = dyn;                            // [LANES][16]
-    float *stg = dyn + LANES * 16;               // WAVES == 1: G rows; WAVES == 2: two buffers of one row
-
     lds_barrier<WAVES>();                        // the step stage is done with the LDS union
 
-    // ---- publish this unit as an observer, and its own block
+    // ---- publish this unit as an observer
     float cu = 1.0f, su = 0.0f;
     const int alive = has ? U.alive : 0;
     const bool enabled = has && U.enabled;
@@ -520,15 +515,13 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         sh.ob.pose[P.l] = make_float4(U.x, U.y, cu, su);
         sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
         sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | (key << 8);
-        float4 *t = reinterpret_cast<float4 *>(own + P.l * 16);
-        const float4 zero4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        t[0] = enabled ? make_float4(0.0f, U.hp, ratio, U.x) : zero4;
-        t[1] = enabled ? make_float4(U.y, U.theta, U.range, U.dmg) : zero4;
-        t[2] = enabled ? make_float4(U.cd, cd_ratio, U.radius, U.mass) : zero4;
-        t[3] = enabled ? make_float4(U.sight_angle, alive ? 1.0f : 0.0f, U.cur_speed, (float)(code_u & 3))
-                       : zero4;
         if (has && a.action_mask) a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
     }
+    // what differs between a unit's block in its own row and in another unit's row
+    const int own_mask = enabled ? -1 : 0;
+    const float own_alive = alive ? 1.0f : 0.0f;
+    const float own_zone = (float)(code_u & 3);
+    const float own_team = (float)U.team;
 
     // ---- zone chunks: lane (env slot zg, chunk zc) keeps its four zone floats in registers:
     // value (zero if the slot is inactive) and which observer coordinate to subtract
@@ -553,11 +546,11 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         }
     }
     const int zone_seer0 = (WAVES == 1) ? zg * N : 0;     // lane of observer 0 of the zone lane's env
-    const int zone_dst0 = ((WAVES == 1) ? zg * Dp : 0) + 16 + 16 * n1 + 4 * zc;
+    const int zone_dst0 = ((WAVES == 1) ? zg * Dp : 0) + 16 * N + 4 * zc;
 
     // ---- store passes: chunk t = p * LANES + l of the staged rows -> (row slot, chunk in row)
     unsigned dst_off[kMaxPasses];
-    int src_idx[kMaxPasses], src_step[kMaxPasses], valid[kMaxPasses];
+    int valid[kMaxPasses];
 #pragma unroll
     for (int p = 0; p < kMaxPasses; ++p) {
         const int t = p * LANES + P.l;
@@ -565,29 +558,23 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const int q = t - tg * CPR;
         int vm = 0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int o = 4 * q - 1 + k;
-            vm |= (o >= 0 && o < D) ? (1 << k) : 0;
-        }
+        for (int k = 0; k < 4; ++k) vm |= (4 * q + k < D) ? (1 << k) : 0;
         valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
-        dst_off[p] = (unsigned)(tg * N * D + 4 * q);          // relative to (row base - 1)
-        const bool from_own = q < 4;
-        src_idx[p] = from_own ? ((WAVES == 1 ? tg * N : 0) * 16 + 4 * q) : (LANES * 16 + 4 * t);
-        src_step[p] = from_own ? 16 : 0;
+        dst_off[p] = (unsigned)(tg * N * D + 4 * q);
     }
 
     lds_barrier<WAVES>();
 
     // ---- one pass per observer index i: every lane's unit seen from observer i of its env
     float *out = a.obs + (size_t)blockIdx.x * G * N * D;
-    const int blk_dst0 = ((WAVES == 1) ? P.g * Dp : 0) + 16 + 16 * P.u;
+    const int blk_row0 = (WAVES == 1) ? P.g * Dp : 0;
     for (int i = 0; i < N; ++i) {
         const int oi = P.base + i;
         const float4 A = sh.ob.pose[oi];
         const float4 B = sh.ob.reach[oi];
         const int fi = sh.seer[oi];
         const int buf = (WAVES == 1) ? 0 : (i & 1) * Dp;
-        // offset of this unit from the observer, in the observer's frame
+        // offset of this unit from the observer; `dot` is its component along the heading
         const float dx = U.x - A.x;
         const float dy = U.y - A.y;
         float dot;
@@ -598,20 +585,29 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const bool same_team = ((fi >> 1) & 1) == U.team;
         const bool same_bush = (fi >> 8) == my_code;
         const bool concealed = hidden && !same_team && !same_bush;
-        const bool pair = alive && (fi & 1) && (i != P.u);
+        const bool self = i == P.u;
+        const bool pair = alive && (fi & 1) && !self;
         const bool seen = pair && in_range && in_cone && !concealed;
         const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me);
         if (a.vis_mask) {
             const uint64_t b = __ballot(seen);
             if (lane == 0) sh.rowbits[i][wv] = b;
         }
-        if (has && i != P.u) {
-            const int m = seen ? -1 : 0;
-            float4 *d = reinterpret_cast<float4 *>(stg + buf + blk_dst0 - (P.u > i ? 16 : 0));
+        if (has) {
+            // block position in the row: own block first, then the others in index order
+            const int blk = self ? 0 : (P.u < i ? P.u + 1 : P.u);
+            const int m = self ? own_mask : (seen ? -1 : 0);
+            const float c2 = self ? U.x : dx;
+            const float c3 = self ? U.y : dy;
+            const float c12 = self ? own_alive : 1.0f;
+            const float c13 = self ? U.cur_speed : (same_team ? 1.0f : 0.0f);
+            const float c14 = self ? own_zone : (hit ? 1.0f : 0.0f);
+            const float c15 = self ? own_team : U.cur_speed;
+            float4 *d = reinterpret_cast<float4 *>(stg + buf + blk_row0 + 16 * blk);
             d[0] = make_float4(__int_as_float(__float_as_int(U.hp) & m),
                                __int_as_float(__float_as_int(ratio) & m),
-                               __int_as_float(__float_as_int(dx) & m),
-                               __int_as_float(__float_as_int(dy) & m));
+                               __int_as_float(__float_as_int(c2) & m),
+                               __int_as_float(__float_as_int(c3) & m));
             d[1] = make_float4(__int_as_float(__float_as_int(U.theta) & m),
                                __int_as_float(__float_as_int(U.range) & m),
                                __int_as_float(__float_as_int(U.dmg) & m),
@@ -620,9 +616,10 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                                __int_as_float(__float_as_int(U.radius) & m),
                                __int_as_float(__float_as_int(U.mass) & m),
                                __int_as_float(__float_as_int(U.sight_angle) & m));
-            d[3] = make_float4(seen ? 1.0f : 0.0f, (seen && same_team) ? 1.0f : 0.0f,
-                               (seen && hit) ? 1.0f : 0.0f,
-                               __int_as_float(__float_as_int(U.cur_speed) & m));
+            d[3] = make_float4(__int_as_float(__float_as_int(c12) & m),
+                               __int_as_float(__float_as_int(c13) & m),
+                               __int_as_float(__float_as_int(c14) & m),
+                               __int_as_float(__float_as_int(c15) & m));
         }
         if (zone_lane) {
             const float4 Z = sh.ob.pose[zone_seer0 + i];
@@ -639,14 +636,12 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         lds_barrier<WAVES>();
 
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
-        float *row_m1 = out + (i * D - 1);
+        float *row = out + i * D;
 #pragma unroll
         for (int p = 0; p < kMaxPasses; ++p) {
             if (p < a.copy_passes) {
-                const int from_own = src_step[p];
-                const int idx = src_idx[p] + (from_own ? 16 * i : buf);
-                const float4 v = *reinterpret_cast<const float4 *>(dyn + idx);
-                float *dp = row_m1 + dst_off[p];
+                const float4 v = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
+                float *dp = row + dst_off[p];
                 const int vm = valid[p];
                 if (vm == 15) {
                     f4u o = {v.x, v.y, v.z, v.w};
@@ -784,10 +779,13 @@ static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
 {
     const int G = a.envs_per_block;
     const dim3 grid((unsigned)((a.p.num_envs + G - 1) / G)), block(64 * WAVES);
-    // dynamic LDS: own blocks of all lanes, then the staged rows (G rows for a single
-    // wavefront, two alternating one-row buffers for a two-wave workgroup)
+    // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
+    // buffers for a two-wave workgroup), rounded up to whole store passes
     const size_t rows_staged = WAVES == 1 ? (size_t)G : 2;
-    const size_t dyn_bytes = ((size_t)64 * WAVES * 16 + rows_staged * a.row_pitch) * sizeof(float);
+    size_t dyn_floats = rows_staged * a.row_pitch;
+    const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
+    if (dyn_floats < pass_floats) dyn_floats = pass_floats;
+    const size_t dyn_bytes = dyn_floats * sizeof(float);
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
@@ -837,7 +835,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     a.obs = obs;
     a.vis_mask = vis_mask;
     a.action_mask = action_mask;
-    a.obs_dim = 15 + 16 * (p->num_units - 1) + 6 * p->max_zones;
+    a.obs_dim = 16 * p->num_units + 6 * p->max_zones;
 
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
@@ -846,7 +844,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     // zone chunks than lanes.  64 < N <= 128: two wavefronts per env.
     const int N = p->num_units;
     const int waves = N <= 64 ? 1 : 2;
-    a.row_pitch = (a.obs_dim + 1 + 3) & ~3;
+    a.row_pitch = (a.obs_dim + 3) & ~3;
     const int cpr = a.row_pitch / 4;
     const int zc = (6 * p->max_zones + 3) / 4;
     int G = 1;
@@ -873,7 +871,7 @@ int tabx_obs_dim(const TabxParams *p)
 {
     const int rc = tabx::check_params(p);
     if (rc) return rc;
-    return 15 + 16 * (p->num_units - 1) + 6 * p->max_zones;
+    return 16 * p->num_units + 6 * p->max_zones;
 }
 
 int tabx_num_actions(void) { return TABX_NUM_ACTIONS; }

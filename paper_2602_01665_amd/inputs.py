@@ -104,8 +104,8 @@ HEADLINE = "c3_16384env_10v10"
 
 
 def obs_dim(num_units: int, max_zones: int) -> int:
-    """Floats per agent observation: own block + (N-1) other blocks + zone slots."""
-    return 15 + 16 * (num_units - 1) + 6 * max_zones
+    """Floats per agent observation: N unit blocks of 16 (own first) + zone slots of 6."""
+    return 16 * num_units + 6 * max_zones
 
 
 def make_params(w: Workload, num_envs: int | None = None, **override) -> dict:

@@ -43,7 +43,7 @@ def acts(*a):
 def other_slot(D_row, i, j):
     """The 16-float block of unit j inside agent i's observation row."""
     k = j if j < i else j - 1
-    return D_row[15 + 16 * k: 15 + 16 * (k + 1)]
+    return D_row[16 + 16 * k: 16 + 16 * (k + 1)]
 
 
 def vis_bit(vis, e, i, j):

@@ -58,6 +58,6 @@ def compare_outputs(gpu, ref, where="", rows=None, check_obs=True):
         # discrete-valued observation features must agree exactly
         go, ro = g(gpu.obs), ref.obs
         N = ref.N
-        cols = [12, 14] + [15 + 16 * s + f for s in range(N - 1) for f in (12, 13, 14)]
+        cols = [12, 14, 15] + [16 + 16 * s + f for s in range(N - 1) for f in (12, 13, 14)]
         _cmp_int("obs discrete features", go[..., cols], ro[..., cols], where)
     return inexact

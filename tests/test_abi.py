@@ -44,8 +44,8 @@ def _params(B, **kw):
 def test_obs_dim_and_shape_errors(B):
     lib = B._lib
     assert lib.tabx_num_actions() == 8
-    assert lib.tabx_obs_dim(C.byref(_params(B))) == 15 + 16 * 19 + 6 * 8
-    assert lib.tabx_obs_dim(C.byref(_params(B, num_units=128, max_zones=0))) == 15 + 16 * 127
+    assert lib.tabx_obs_dim(C.byref(_params(B))) == 16 * 20 + 6 * 8
+    assert lib.tabx_obs_dim(C.byref(_params(B, num_units=128, max_zones=0))) == 16 * 128
     assert lib.tabx_obs_dim(None) == -1
     for bad in (dict(num_units=0), dict(num_units=129), dict(max_zones=17), dict(max_zones=-1),
                 dict(num_envs=-1), dict(grid_w=4), dict(max_steps=0)):

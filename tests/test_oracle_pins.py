@@ -333,20 +333,21 @@ def test_observation_layout():
     env.set_state(hp=np.array([[60.0, 20.0, 40.0]], np.float32),
                   cd=np.array([[0.75, 0.5, 0.0]], np.float32))
     obs, vis, m = env.observe()
-    D = 15 + 16 * 2 + 6 * 2
+    D = 16 * 3 + 6 * 2
     assert obs.shape == (1, 3, D) and env.D == D
     f32 = np.float32
-    own = obs[0, 0, :15]
+    own = obs[0, 0, :16]
     sight = f32(I.DEFAULTS["sight_angle"])
     assert list(own) == [60.0, f32(60.0) / f32(70.0), 10.0, 10.0, 0.0, 2.5, 22.0, 0.75, 0.5,
-                         1.0, 1.0, sight, 1.0, f32(1.4), 0.0]
+                         1.0, 1.0, sight, 1.0, f32(1.4), 0.0, 0.0]
+    assert obs[0, 1, 15] == 1.0                      # own team id of an adversary
     b1 = other_slot(obs[0, 0], 0, 1)
     assert list(b1) == [20.0, f32(0.8), 2.0, 0.5, 3.0, 10.0, -7.0, 0.5, 0.25, 1.0, 1.0,
                         sight, 1.0, 0.0, 1.0, 1.0]          # enemy, attackable
     b2 = other_slot(obs[0, 0], 0, 2)
     assert list(b2) == [40.0, 1.0, 4.0, -1.0, 1.0, 27.0, 28.0, 0.0, 0.0, 1.0, 1.0,
                         sight, 1.0, 1.0, 0.0, 1.0]          # ally, not attackable
-    z = obs[0, 0, 15 + 32:]
+    z = obs[0, 0, 16 + 32:]
     assert list(z) == [1.0, 2.0, 10.0, 4.0, 2.0, 4.0] + [0.0] * 6
     # unit 1 faces -x (theta 3.0): sees unit 0 (an enemy a healer cannot affect), not unit 2
     b0 = other_slot(obs[0, 1], 1, 0)

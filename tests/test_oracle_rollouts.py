@@ -84,7 +84,7 @@ def test_invariants(name):
             assert not np.any(vis[:, i, i >> 6] >> np.uint64(i & 63) & np.uint64(1))
         dead = st["alive"] == 0
         assert not np.any(vis[dead]) and not np.any(am[dead])
-        assert not np.any(obs[dead][:, 15:15 + 16 * (N - 1)])
+        assert not np.any(obs[dead][:, 16:16 + 16 * (N - 1)])
         prev = env.snapshot()
 
 
