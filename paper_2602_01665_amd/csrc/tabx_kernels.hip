@@ -124,7 +124,7 @@ struct Shared {
         } ob;
     };
     int      seer[L];             // observer flags: alive | team<<1 | heals<<2 | enabled<<3 | bush key<<8
-    uint64_t rowbits[L][WAVES];   // ballot of "observer i sees lane" per observer index
+    uint64_t rowbits[WAVES == 1 ? 1 : L][WAVES];   // two-wave workgroups: ballots of "observer i sees lane"
     uint64_t ballots[WAVES][4];
 };
 
@@ -567,6 +567,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
 
     // ---- one pass per observer index i: every lane's unit seen from observer i of its env
     float *out = a.obs + (size_t)blockIdx.x * G * N * D;
+    uint64_t my_row = 0;
     const int blk_row0 = (WAVES == 1) ? P.g * Dp : 0;
     for (int i = 0; i < N; ++i) {
         const int oi = P.base + i;
@@ -590,8 +591,10 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const bool seen = pair && in_range && in_cone && !concealed;
         const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me);
         if (a.vis_mask) {
+            // the ballot over the lanes is observer i's row; its own lane keeps it
             const uint64_t b = __ballot(seen);
-            if (lane == 0) sh.rowbits[i][wv] = b;
+            if (WAVES == 1) my_row = self ? b : my_row;
+            else if (lane == 0) sh.rowbits[i][wv] = b;
         }
         if (has) {
             // block position in the row: own block first, then the others in index order
@@ -639,14 +642,14 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         float *row = out + i * D;
 #pragma unroll
         for (int p = 0; p < kMaxPasses; ++p) {
-            if (p < a.copy_passes) {
+            const int vm = valid[p];
+            if (p < a.copy_passes && vm != 0) {
                 const float4 v = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
                 float *dp = row + dst_off[p];
-                const int vm = valid[p];
                 if (vm == 15) {
                     f4u o = {v.x, v.y, v.z, v.w};
                     *reinterpret_cast<f4u *>(dp) = o;
-                } else if (vm != 0) {
+                } else {
                     if (vm & 1) dp[0] = v.x;
                     if (vm & 2) dp[1] = v.y;
                     if (vm & 4) dp[2] = v.z;
@@ -662,7 +665,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         if (has) {
             if (WAVES == 1) {
                 const uint64_t range = N >= 64 ? ~0ull : ((1ull << N) - 1ull);
-                a.vis_mask[P.k] = (sh.rowbits[P.u][0] >> P.base) & range;
+                a.vis_mask[P.k] = (my_row >> P.base) & range;
             } else {
                 const int words = (N + 63) >> 6;
                 for (int w = 0; w < words; ++w) a.vis_mask[P.k * words + w] = sh.rowbits[P.u][w];
@@ -780,12 +783,9 @@ static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
     const int G = a.envs_per_block;
     const dim3 grid((unsigned)((a.p.num_envs + G - 1) / G)), block(64 * WAVES);
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
-    // buffers for a two-wave workgroup), rounded up to whole store passes
+    // buffers for a two-wave workgroup)
     const size_t rows_staged = WAVES == 1 ? (size_t)G : 2;
-    size_t dyn_floats = rows_staged * a.row_pitch;
-    const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
-    if (dyn_floats < pass_floats) dyn_floats = pass_floats;
-    const size_t dyn_bytes = dyn_floats * sizeof(float);
+    const size_t dyn_bytes = rows_staged * a.row_pitch * sizeof(float);
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
