@@ -29,7 +29,7 @@
 
 namespace tabx {
 
-constexpr int kMaxPasses = 6;      // store passes that stream one set of staged rows
+constexpr int kMaxPasses = 10;     // store passes that stream one set of staged rows
 
 struct KArgs {
     TabxParams   p;
@@ -45,7 +45,8 @@ struct KArgs {
     int       obs_dim;             // D
     int       envs_per_block;      // G
     int       row_pitch;           // floats between staged rows: D rounded up to 4
-    int       copy_passes;         // ceil(G * row_pitch / 4 / lanes), <= kMaxPasses
+    int       copy_passes;         // ceil(G * R * row_pitch / 4 / lanes), <= kMaxPasses
+    int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
 };
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte store, 4-byte aligned
@@ -546,7 +547,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         }
     }
     const int zone_seer0 = (WAVES == 1) ? zg * N : 0;     // lane of observer 0 of the zone lane's env
-    const int zone_dst0 = ((WAVES == 1) ? zg * Dp : 0) + 16 * N + 4 * zc;
+    const int R = a.rows_per_flush;
+    const int zone_dst0 = ((WAVES == 1) ? zg * R * Dp : 0) + 16 * N + 4 * zc;
 
     // ---- store passes: chunk t = p * LANES + l of the staged rows -> (row slot, chunk in row)
     unsigned dst_off[kMaxPasses];
@@ -554,11 +556,11 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
 #pragma unroll
     for (int p = 0; p < kMaxPasses; ++p) {
         const int t = p * LANES + P.l;
-        const int tg = t / CPR;
-        const int q = t - tg * CPR;
-        int vm = 0;
+        const int tg = t / (R * CPR);              // env slot
+        const int q = t - tg * (R * CPR);          // chunk within the env's R staged rows
+        int vm = 0;                                // R > 1 only when D is a multiple of 4
 #pragma unroll
-        for (int k = 0; k < 4; ++k) vm |= (4 * q + k < D) ? (1 << k) : 0;
+        for (int k = 0; k < 4; ++k) vm |= (R > 1 || 4 * q + k < D) ? (1 << k) : 0;
         valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
         dst_off[p] = (unsigned)(tg * N * D + 4 * q);
     }
@@ -568,13 +570,15 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     // ---- one pass per observer index i: every lane's unit seen from observer i of its env
     float *out = a.obs + (size_t)blockIdx.x * G * N * D;
     uint64_t my_row = 0;
-    const int blk_row0 = (WAVES == 1) ? P.g * Dp : 0;
-    for (int i = 0; i < N; ++i) {
+    const int blk_row0 = (WAVES == 1) ? P.g * R * Dp : 0;
+    for (int i0 = 0; i0 < N; i0 += R) {
+    for (int rr = 0; rr < R; ++rr) {
+        const int i = i0 + rr;
         const int oi = P.base + i;
         const float4 A = sh.ob.pose[oi];
         const float4 B = sh.ob.reach[oi];
         const int fi = sh.seer[oi];
-        const int buf = (WAVES == 1) ? 0 : (i & 1) * Dp;
+        const int buf = (WAVES == 1) ? rr * Dp : (i & 1) * Dp;
         // offset of this unit from the observer; `dot` is its component along the heading
         const float dx = U.x - A.x;
         const float dy = U.y - A.y;
@@ -636,10 +640,12 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             }
             *reinterpret_cast<float4 *>(stg + buf + zone_dst0) = make_float4(zo[0], zo[1], zo[2], zo[3]);
         }
+    }
         lds_barrier<WAVES>();
 
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
-        float *row = out + i * D;
+        const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
+        float *row = out + i0 * D;
 #pragma unroll
         for (int p = 0; p < kMaxPasses; ++p) {
             const int vm = valid[p];
@@ -784,7 +790,7 @@ static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)((a.p.num_envs + G - 1) / G)), block(64 * WAVES);
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
     // buffers for a two-wave workgroup)
-    const size_t rows_staged = WAVES == 1 ? (size_t)G : 2;
+    const size_t rows_staged = WAVES == 1 ? (size_t)G * a.rows_per_flush : 2;
     const size_t dyn_bytes = rows_staged * a.row_pitch * sizeof(float);
     switch (mode) {
     case MODE_RESET:
@@ -856,7 +862,13 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         if (G < 1) G = 1;
     }
     a.envs_per_block = G;
-    a.copy_passes = (G * cpr + 64 * waves - 1) / (64 * waves);
+    // two rows per flush when that turns half-line rows into whole 128-byte lines
+    int R = 1;
+    if (waves == 1 && a.obs_dim % 4 == 0 && N % 2 == 0 && (a.obs_dim * 4) % 128 != 0 &&
+        (a.obs_dim * 8) % 128 == 0 && (2 * G * cpr + 63) / 64 <= kMaxPasses)
+        R = 2;
+    a.rows_per_flush = R;
+    a.copy_passes = (G * R * cpr + 64 * waves - 1) / (64 * waves);
     if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
     if (waves == 1) launch_mode<1>(mode, a, s);
     else launch_mode<2>(mode, a, s);
