@@ -21,6 +21,7 @@
 // rounding per written operation: the file is compiled with -ffp-contract=off
 // and uses fmaf only where it is spelled out.
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "tabx.h"
@@ -47,6 +48,8 @@ struct KArgs {
     int       row_pitch;           // floats between staged rows: D rounded up to 4
     int       copy_passes;         // ceil(G * R * row_pitch / 4 / lanes), <= kMaxPasses
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
+    float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
+    int       cell_pow2;
 };
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte store, 4-byte aligned
@@ -92,6 +95,12 @@ __device__ __forceinline__ float median3(float v, float lo, float hi)
 {
     return __builtin_amdgcn_fmed3f(v, lo, hi);
 }
+
+// What the step stage already knows about a unit and the observe stage needs again.
+struct Carry {
+    float cu, su;      // cosine / sine of the heading
+    float ratio;       // hp / hmax
+};
 
 // Registers of one unit: mutable state, then read-only specification.
 struct Unit {
@@ -149,8 +158,9 @@ __device__ __forceinline__ void lds_barrier()
 __device__ __forceinline__ int terrain_code(const KArgs &a, int e, float x, float y)
 {
     if (a.sc.terrain == nullptr) return 0;
-    int cx = (int)(x / a.p.cell_size);
-    int cy = (int)(y / a.p.cell_size);
+    // dividing by a power of two and multiplying by its reciprocal round identically
+    int cx = a.cell_pow2 ? (int)(x * a.inv_cell) : (int)(x / a.p.cell_size);
+    int cy = a.cell_pow2 ? (int)(y * a.inv_cell) : (int)(y / a.p.cell_size);
     cx = cx > a.p.grid_w - 1 ? a.p.grid_w - 1 : cx;
     cy = cy > a.p.grid_h - 1 ? a.p.grid_h - 1 : cy;
     cx = cx < 0 ? 0 : cx;
@@ -301,13 +311,16 @@ __device__ __forceinline__ float hurtbox_gap2(float dx, float dy, float ci, floa
 
 template <int WAVES>
 __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, const Place &P,
-                                         Unit &U, int &code_u)
+                                         Unit &U, int &code_u, Carry &C)
 {
     const int N = a.p.num_units;
     const float dt = a.p.dt;
     const bool has = P.has;
     const int alive0 = has ? U.alive : 0;
     const int act = has ? (int)a.actions[P.k] : 0;
+    // per-env scalars, requested early: they are needed only after three LDS exchanges
+    const int t_new = has ? a.st.t[P.e] + 1 : 0;
+    const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
     float bdmg = 0.0f;
 
     // stage 1: cooldown / reveal timers, explicit Euler move, arena penalty + clip
@@ -325,6 +338,10 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
             U.y = clamp_between(ny, 0.0f, a.p.map_h);
         }
     }
+
+    // the position is final for this tick: fetch the terrain cell under it now, the zone
+    // effects of stage 3 use it after the combat exchange
+    if (has && U.enabled) code_u = terrain_code(a, P.e, U.x, U.y);
 
     // stage 2a: movement sets next tick's velocity, rotation turns the heading now
     float cu = 1.0f, su = 0.0f;
@@ -403,7 +420,6 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
     float ratio = 0.0f;
     if (has) {
         if (U.enabled) {
-            code_u = terrain_code(a, P.e, U.x, U.y);
             const int zone = code_u & 3;
             if (alive0 && zone == TABX_ZONE_LAVA) {
                 const float h = U.hp - (a.p.lava_dps * dt);
@@ -428,8 +444,6 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
     // reward (Eq. 1), termination, terminal bonus
     float m0, m1;
     team_means(sh, P, N, cnt[0], cnt[1], m0, m1);
-    const int t_new = has ? a.st.t[P.e] + 1 : 0;
-    const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
     const float phi = m0 - m1;
     const float dense = phi - phi_prev;
     float r0 = dense, r1 = -dense;
@@ -459,6 +473,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
         if (done) {
             code_u = spawn_unit(a, P.e, P.k, U);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
+            heading_sincos(U.theta, su, cu);
         }
         sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
                                     (en && U.team != 0) ? ratio : 0.0f);
@@ -473,6 +488,9 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
         a.dones[P.e] = done ? 1 : 0;
     }
     if (has) store_state(a, P.k, U);
+    C.cu = cu;
+    C.su = su;
+    C.ratio = ratio;
 }
 
 // Observation rows of every unit of the workgroup's envs, visibility masks, action masks.
@@ -482,9 +500,10 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
 // packed in the workgroup) are assembled in LDS as exact images of the HBM rows, pitch
 // row_pitch = D rounded up to 4 floats, and then go out in 16-byte chunks, chunk t of the
 // staged rows handled by lane t % lanes of store pass t / lanes.
-template <int WAVES>
+template <int WAVES, bool CARRIED>
 __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *stg,
-                                            const Place &P, const Unit &U, int code_u)
+                                            const Place &P, const Unit &U, int code_u,
+                                            const Carry &C)
 {
     constexpr int LANES = 64 * WAVES;
     const int N = a.p.num_units;
@@ -507,11 +526,16 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
     const int my_code = code_u & 0xff;
     const bool hidden = in_bush && !(U.reveal > 0.0f);
-    const float ratio = U.hp / U.hmax;
+    const float ratio = CARRIED ? C.ratio : U.hp / U.hmax;   // disabled units: masked below
     const float cd_ratio = U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f;
     const float r2_me = U.radius * U.radius;
     {
-        if (has) heading_sincos(U.theta, su, cu);
+        if (CARRIED) {
+            cu = C.cu;
+            su = C.su;
+        } else if (has) {
+            heading_sincos(U.theta, su, cu);
+        }
         const int key = in_bush ? my_code : 0x100;         // 0x100 matches no cell code
         sh.ob.pose[P.l] = make_float4(U.x, U.y, cu, su);
         sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
@@ -553,16 +577,23 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     // ---- store passes: chunk t = p * LANES + l of the staged rows -> (row slot, chunk in row)
     unsigned dst_off[kMaxPasses];
     int valid[kMaxPasses];
+    {
+        const int RC = R * CPR;                    // chunks per env slot and flush
+        int tg = P.l / RC;                         // env slot of chunk t
+        int q = P.l - tg * RC;                     // chunk within the env's R staged rows
 #pragma unroll
-    for (int p = 0; p < kMaxPasses; ++p) {
-        const int t = p * LANES + P.l;
-        const int tg = t / (R * CPR);              // env slot
-        const int q = t - tg * (R * CPR);          // chunk within the env's R staged rows
-        int vm = 0;                                // R > 1 only when D is a multiple of 4
+        for (int p = 0; p < kMaxPasses; ++p) {
+            int vm = 0;                            // R > 1 only when D is a multiple of 4
 #pragma unroll
-        for (int k = 0; k < 4; ++k) vm |= (R > 1 || 4 * q + k < D) ? (1 << k) : 0;
-        valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
-        dst_off[p] = (unsigned)(tg * N * D + 4 * q);
+            for (int k = 0; k < 4; ++k) vm |= (R > 1 || 4 * q + k < D) ? (1 << k) : 0;
+            valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
+            dst_off[p] = (unsigned)(tg * N * D + 4 * q);
+            q += LANES;                            // chunk t + LANES of the next pass
+            while (q >= RC) {
+                q -= RC;
+                tg += 1;
+            }
+        }
     }
 
     lds_barrier<WAVES>();
@@ -692,9 +723,10 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         load_spec(a, P.k, U);
         load_state(a, P.k, U);
     }
-    if (DO_STEP) step_env<WAVES>(a, sh, P, U, code_u);
+    Carry C = {1.0f, 0.0f, 0.0f};
+    if (DO_STEP) step_env<WAVES>(a, sh, P, U, code_u, C);
     else if (P.has) code_u = terrain_code(a, P.e, U.x, U.y);
-    if (DO_OBS) observe_env<WAVES>(a, sh, dyn_lds, P, U, code_u);
+    if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C);
 }
 
 template <int WAVES>
@@ -868,6 +900,12 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         (a.obs_dim * 8) % 128 == 0 && (2 * G * cpr + 63) / 64 <= kMaxPasses)
         R = 2;
     a.rows_per_flush = R;
+    {
+        int ex = 0;
+        const float mant = frexpf(p->cell_size, &ex);
+        a.cell_pow2 = (mant == 0.5f && ex > -100 && ex < 100) ? 1 : 0;
+        a.inv_cell = 1.0f / p->cell_size;
+    }
     a.copy_passes = (G * R * cpr + 64 * waves - 1) / (64 * waves);
     if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
     if (waves == 1) launch_mode<1>(mode, a, s);
