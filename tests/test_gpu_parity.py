@@ -124,6 +124,60 @@ def test_zone_descriptor_slots_and_full_cone():
     _rollout(w, 9, 40, False, scenario=sc, max_steps=30)
 
 
+@pytest.mark.parametrize("zones", [1, 2, 3, 5, 7])
+@pytest.mark.parametrize("team_size", [2, 5, 10, 40])
+def test_odd_zone_counts_and_row_alignment(zones, team_size):
+    """Rows whose length is not a multiple of 4 floats (odd zone counts) and of every
+    alignment class, in single-wave and two-wave workgroups."""
+    w = I.Workload(f"z{zones}_n{team_size}", 7, team_size, 36.0, 18, "iid", 0.6, "iid",
+                   max_zones=zones, steps=30, seed=900 + zones)
+    sc = I.make_scenario(w, 7)
+    rng = np.random.default_rng(zones * 100 + team_size)
+    zd = np.zeros((7, zones, 6), np.float32)
+    zd[..., 0] = rng.integers(0, 4, size=(7, zones))
+    zd[..., 1:] = rng.uniform(0.5, 30.0, size=(7, zones, 5))
+    sc["zone_desc"] = zd
+    _say(f"[gpu] zones={zones} N={w.num_units}")
+    _rollout(w, 7, 30, True, scenario=sc, max_steps=12)
+    _rollout(w, 7, 12, False, scenario=sc, max_steps=12)
+
+
+def test_degenerate_team_shapes():
+    """One unit, an odd number of units, an empty enemy team, everybody on one team."""
+    cases = {
+        "single": [dict(unit="archer", team=0, x=5.0, y=5.0)],
+        "odd_2v1": [dict(unit="assassin", team=0, x=5.0, y=5.0), dict(unit="healer", team=0, x=6.0, y=5.0),
+                    dict(unit="assassin", team=1, x=7.0, y=5.0, theta=3.14)],
+        "one_team": [dict(unit="healer", team=0, x=5.0, y=5.0), dict(unit="farmer", team=0, x=7.0, y=5.0)],
+        "enemy_disabled": [dict(unit="assassin", team=0, x=5.0, y=5.0),
+                           dict(unit="assassin", team=1, x=6.0, y=5.0, enabled=0)],
+    }
+    for name, units in cases.items():
+        one = I.custom_scenario(units, 16.0)
+        E = 11
+        sc = {k: (None if v is None else np.ascontiguousarray(np.repeat(v, E, axis=0)))
+              for k, v in one.items()}
+        w = I.Workload(name, E, 1, 16.0, 0, "none", 1.0, "iid", steps=20, seed=5)
+        p = I.custom_params(len(units), 16.0, max_steps=6)
+        p["num_envs"] = E
+        _say(f"[gpu] degenerate case {name}")
+        import torch
+        from oracle.ref import RefEnv
+        from paper_2602_01665_amd.binding import TabxEnv
+        ref, gpu = RefEnv(p, sc), TabxEnv(p, sc)
+        ref.reset()
+        gpu.reset()
+        rng = np.random.default_rng(1)
+        for s in range(20):
+            a = rng.integers(0, 8, size=(E, len(units)), dtype=np.uint8)
+            ref.step(a)
+            ref.observe()
+            gpu.step_observe(torch.from_numpy(a).to("cuda:0"))
+            torch.cuda.synchronize()
+            compare_state(gpu.state_numpy(), ref.st, f"{name} step {s}: ")
+            compare_outputs(gpu, ref, f"{name} step {s}: ")
+
+
 def test_other_roster_units():
     """Every roster row (big bodies, wide hurtboxes, long cooldowns) in one battle."""
     names = list(I.ROSTER)
