@@ -684,8 +684,12 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 const float4 v = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
                 float *dp = row + dst_off[p];
                 if (vm == 15) {
+                    // single-wave workgroups stream with the non-temporal hint: the rows are
+                    // never read back by the kernel, and the hint measurably raises the store
+                    // rate there (it lowers it for the two-wave, 8 KB-row case)
                     f4u o = {v.x, v.y, v.z, v.w};
-                    *reinterpret_cast<f4u *>(dp) = o;
+                    if (WAVES == 1) __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(dp));
+                    else *reinterpret_cast<f4u *>(dp) = o;
                 } else {
                     if (vm & 1) dp[0] = v.x;
                     if (vm & 2) dp[1] = v.y;
@@ -894,10 +898,10 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         if (G < 1) G = 1;
     }
     a.envs_per_block = G;
-    // two rows per flush when that turns half-line rows into whole 128-byte lines
+    // two rows per flush: longer contiguous runs per env, and whole 128-byte lines where a
+    // single row ends on half a line
     int R = 1;
-    if (waves == 1 && a.obs_dim % 4 == 0 && N % 2 == 0 && (a.obs_dim * 4) % 128 != 0 &&
-        (a.obs_dim * 8) % 128 == 0 && (2 * G * cpr + 63) / 64 <= kMaxPasses)
+    if (waves == 1 && a.obs_dim % 4 == 0 && N % 2 == 0 && (2 * G * cpr + 63) / 64 <= kMaxPasses)
         R = 2;
     a.rows_per_flush = R;
     {
