@@ -677,24 +677,42 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
         const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
         float *row = out + i0 * D;
+        if (D == Dp) {
+            // every chunk is whole: fetch all passes from LDS first, then issue the stores
+            float4 v[kMaxPasses];
 #pragma unroll
-        for (int p = 0; p < kMaxPasses; ++p) {
-            const int vm = valid[p];
-            if (p < a.copy_passes && vm != 0) {
-                const float4 v = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
-                float *dp = row + dst_off[p];
-                if (vm == 15) {
+            for (int p = 0; p < kMaxPasses; ++p)
+                if (p < a.copy_passes)
+                    v[p] = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
+#pragma unroll
+            for (int p = 0; p < kMaxPasses; ++p) {
+                if (p < a.copy_passes && valid[p] != 0) {
                     // single-wave workgroups stream with the non-temporal hint: the rows are
                     // never read back by the kernel, and the hint measurably raises the store
                     // rate there (it lowers it for the two-wave, 8 KB-row case)
-                    f4u o = {v.x, v.y, v.z, v.w};
-                    if (WAVES == 1) __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(dp));
-                    else *reinterpret_cast<f4u *>(dp) = o;
-                } else {
-                    if (vm & 1) dp[0] = v.x;
-                    if (vm & 2) dp[1] = v.y;
-                    if (vm & 4) dp[2] = v.z;
-                    if (vm & 8) dp[3] = v.w;
+                    f4u o = {v[p].x, v[p].y, v[p].z, v[p].w};
+                    f4u *dp = reinterpret_cast<f4u *>(row + dst_off[p]);
+                    if (WAVES == 1) __builtin_nontemporal_store(o, dp);
+                    else *dp = o;
+                }
+            }
+        } else {
+            // rows that are not a multiple of 16 bytes end in a partial chunk
+#pragma unroll
+            for (int p = 0; p < kMaxPasses; ++p) {
+                const int vm = valid[p];
+                if (p < a.copy_passes && vm != 0) {
+                    const float4 v = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
+                    float *dp = row + dst_off[p];
+                    if (vm == 15) {
+                        f4u o = {v.x, v.y, v.z, v.w};
+                        *reinterpret_cast<f4u *>(dp) = o;
+                    } else {
+                        if (vm & 1) dp[0] = v.x;
+                        if (vm & 2) dp[1] = v.y;
+                        if (vm & 4) dp[2] = v.z;
+                        if (vm & 8) dp[3] = v.w;
+                    }
                 }
             }
         }
@@ -827,7 +845,11 @@ static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
     // buffers for a two-wave workgroup)
     const size_t rows_staged = WAVES == 1 ? (size_t)G * a.rows_per_flush : 2;
-    const size_t dyn_bytes = rows_staged * a.row_pitch * sizeof(float);
+    // ... rounded up to whole store passes, which read their 16 bytes per lane unconditionally
+    size_t dyn_floats = rows_staged * a.row_pitch;
+    const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
+    if (dyn_floats < pass_floats) dyn_floats = pass_floats;
+    const size_t dyn_bytes = dyn_floats * sizeof(float);
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
