@@ -39,9 +39,17 @@ class RefScenario(C.Structure):
                                                 ("zone_desc", _F)]
 
 
+_I8 = C.POINTER(C.c_byte)
+_I32 = C.POINTER(C.c_int)
+_METRICS = (("ret_run", _F, np.float32), ("kill_run", _I8, np.int8), ("ep_count", _I32, np.int32),
+            ("ep_len", _I32, np.int32), ("ep_return", _F, np.float32), ("ep_win", _I8, np.int8),
+            ("ep_first_kill", _I8, np.int8))
+
+
 class RefState(C.Structure):
     _fields_ = [(n, _F) for n in _ST_FLOAT] + [("alive", _B), ("t", C.POINTER(C.c_int)),
-                                                ("phi_prev", _F)]
+                                                ("phi_prev", _F)] + \
+               [(n, t) for n, t, _ in _METRICS]
 
 
 def build(force: bool = False) -> str:
@@ -67,7 +75,7 @@ def lib():
         _lib.tabx_ref_sincos.argtypes = [C.c_float, _F, _F]
         _lib.tabx_ref_sincos_n.argtypes = [_F, C.c_int, _F, _F]
         for fn in (_lib.tabx_ref_reset, _lib.tabx_ref_step, _lib.tabx_ref_observe,
-                   _lib.tabx_ref_sincos, _lib.tabx_ref_sincos_n):
+                   _lib.tabx_ref_sincos, _lib.tabx_ref_sincos_n, _lib.tabx_ref_global_state):
             fn.restype = None
     return _lib
 
@@ -94,8 +102,9 @@ def _ptr(a, typ):
 class RefEnv:
     """Batched CPU environment: numpy state, calls into the checker per tick."""
 
-    def __init__(self, params: dict, scenario: dict):
+    def __init__(self, params: dict, scenario: dict, metrics: bool = True):
         self.p = dict(params)
+        self.metrics = metrics
         E, N = self.p["num_envs"], self.p["num_units"]
         self.E, self.N = E, N
         self.sc = {}
@@ -132,7 +141,11 @@ class RefEnv:
         self.st["alive"] = np.zeros((E, N), np.uint8)
         self.st["t"] = np.zeros(E, np.int32)
         self.st["phi_prev"] = np.zeros(E, np.float32)
+        if metrics:
+            for n, _, dt in _METRICS:
+                self.st[n] = np.zeros(E, dt)
         self._bind_state()
+        self.gstate = np.zeros((E, 16 * N + 6 * self.p["max_zones"]), np.float32)
         self.rewards = np.zeros((E, N), np.float32)
         self.dones = np.zeros(E, np.uint8)
         self.obs = np.zeros((E, N, self.D), np.float32)
@@ -145,7 +158,9 @@ class RefEnv:
         self.cst = RefState(**{k: _ptr(self.st[k], _F) for k in _ST_FLOAT},
                             alive=_ptr(self.st["alive"], _B),
                             t=_ptr(self.st["t"], C.POINTER(C.c_int)),
-                            phi_prev=_ptr(self.st["phi_prev"], _F))
+                            phi_prev=_ptr(self.st["phi_prev"], _F),
+                            **({n: _ptr(self.st[n], t) for n, t, _ in _METRICS}
+                               if self.metrics else {}))
 
     def set_state(self, **arrays):
         """Overwrites state fields in place (hand-worked cases)."""
@@ -181,3 +196,8 @@ class RefEnv:
                                _ptr(self.vis, C.POINTER(C.c_ulonglong)),
                                _ptr(self.amask, _B), self._mm())
         return self.obs, self.vis, self.amask
+
+    def global_state(self):
+        lib().tabx_ref_global_state(C.byref(self.cp), C.byref(self.csc), C.byref(self.cst),
+                                    _ptr(self.gstate, _F))
+        return self.gstate

@@ -119,6 +119,8 @@ void reset_env(const RefParams &P, const RefScenario &S, RefState &st, int e)
     }
     st.t[e] = 0;
     st.phi_prev[e] = team_ratio(P, S, st, e, 0) - team_ratio(P, S, st, e, 1);
+    if (st.ret_run) st.ret_run[e] = 0.0f;
+    if (st.kill_run) st.kill_run[e] = 0;
 }
 
 /* Hurtbox test (App. A "Attack range geometry"): the attacker's forward
@@ -274,9 +276,11 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
     const float dense = phi - st.phi_prev[e];
     float r0 = dense, r1 = -dense;
 
-    int alive_cnt[2] = {0, 0};
-    for (int u = 0; u < N; ++u)
+    int alive_cnt[2] = {0, 0}, before_cnt[2] = {0, 0};
+    for (int u = 0; u < N; ++u) {
         if (st.alive[b + u]) alive_cnt[S.team[b + u] ? 1 : 0] += 1;
+        if (alive0[u]) before_cnt[S.team[b + u] ? 1 : 0] += 1;
+    }
     const bool done = alive_cnt[0] == 0 || alive_cnt[1] == 0 || st.t[e] >= P.max_steps;
     if (done) {
         /* one rule for wipe-out and truncation: the allies win only with a
@@ -290,8 +294,63 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
         rewards[k] = S.enabled[k] ? (S.team[k] ? r1 : r0) : 0.0f;
     }
     dones[e] = done ? 1 : 0;
+
+    /* episode metrics: first loss of a unit, running allied return, summary at the end */
+    if (st.kill_run && st.kill_run[e] == 0) {
+        const bool enemy_died = alive_cnt[1] < before_cnt[1];
+        const bool ally_died = alive_cnt[0] < before_cnt[0];
+        st.kill_run[e] = (signed char)((enemy_died ? 1 : 0) | (ally_died ? 2 : 0));
+    }
+    if (st.ret_run) st.ret_run[e] = st.ret_run[e] + r0;
+    if (done) {
+        if (st.ep_count) st.ep_count[e] += 1;
+        if (st.ep_len) st.ep_len[e] = st.t[e];
+        if (st.ep_return && st.ret_run) st.ep_return[e] = st.ret_run[e];
+        if (st.ep_win) st.ep_win[e] = (ratio0 > ratio1) ? 1 : 0;
+        if (st.ep_first_kill && st.kill_run) st.ep_first_kill[e] = st.kill_run[e];
+    }
     if (done) reset_env(P, S, st, e);
     else st.phi_prev[e] = phi;
+}
+
+/* The 16 own-unit features of App. A "Own-unit features" (+ zone type underfoot, team). */
+void own_block(const RefParams &P, const RefScenario &S, const RefState &st, int e, int u,
+               int code, float *row)
+{
+    const int k = e * P.num_units + u;
+    row[0] = st.hp[k];
+    row[1] = st.hp[k] / S.hmax[k];
+    row[2] = st.x[k];
+    row[3] = st.y[k];
+    row[4] = st.theta[k];
+    row[5] = S.range[k];
+    row[6] = S.dmg[k];
+    row[7] = st.cd[k];
+    row[8] = S.cooldown[k] != 0.0f ? st.cd[k] / S.cooldown[k] : 0.0f;
+    row[9] = S.radius[k];
+    row[10] = S.mass[k];
+    row[11] = S.sight_angle[k];
+    row[12] = st.alive[k] ? 1.0f : 0.0f;
+    row[13] = st.cur_speed[k];
+    row[14] = (float)(code & 3);
+    row[15] = (float)S.team[k];
+}
+
+void global_state_env(const RefParams &P, const RefScenario &S, const RefState &st, int e,
+                      float *out)
+{
+    const int N = P.num_units, Z = P.max_zones;
+    for (int o = 0; o < 16 * N + 6 * Z; ++o) out[o] = 0.0f;
+    for (int u = 0; u < N; ++u) {
+        const int k = e * N + u;
+        if (!S.enabled[k]) continue;
+        own_block(P, S, st, e, u, cell_code(P, S, e, st.x[k], st.y[k]), out + 16 * u);
+    }
+    for (int z = 0; z < Z && S.zone_desc; ++z) {
+        const float *d = S.zone_desc + ((long)e * Z + z) * 6;
+        if (d[0] == 0.0f) continue;
+        for (int c = 0; c < 6; ++c) out[16 * N + 6 * z + c] = d[c];
+    }
 }
 
 void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, int e,
@@ -319,22 +378,7 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
         if (!S.enabled[ki]) continue;
 
         /* own block */
-        row[0] = st.hp[ki];
-        row[1] = st.hp[ki] / S.hmax[ki];
-        row[2] = st.x[ki];
-        row[3] = st.y[ki];
-        row[4] = st.theta[ki];
-        row[5] = S.range[ki];
-        row[6] = S.dmg[ki];
-        row[7] = st.cd[ki];
-        row[8] = S.cooldown[ki] != 0.0f ? st.cd[ki] / S.cooldown[ki] : 0.0f;
-        row[9] = S.radius[ki];
-        row[10] = S.mass[ki];
-        row[11] = S.sight_angle[ki];
-        row[12] = st.alive[ki] ? 1.0f : 0.0f;
-        row[13] = st.cur_speed[ki];
-        row[14] = (float)(code[i] & 3);
-        row[15] = (float)S.team[ki];
+        own_block(P, S, st, e, i, code[i], row);
 
         /* other units, ascending index, self skipped */
         int slot = 0;
@@ -453,6 +497,13 @@ void tabx_ref_observe(const RefParams *p, const RefScenario *sc, const RefState 
 {
     for (int e = 0; e < p->num_envs; ++e)
         observe_env(*p, *sc, *st, e, obs, vis_mask, action_mask, min_margin);
+}
+
+void tabx_ref_global_state(const RefParams *p, const RefScenario *sc, const RefState *st,
+                           float *out)
+{
+    const long Dg = 16 * p->num_units + 6 * p->max_zones;
+    for (int e = 0; e < p->num_envs; ++e) global_state_env(*p, *sc, *st, e, out + e * Dg);
 }
 
 } /* extern "C" */

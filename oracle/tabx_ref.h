@@ -54,6 +54,16 @@ typedef struct RefState {
     unsigned char *alive;
     int   *t;          /* [E] */
     float *phi_prev;   /* [E] */
+    /* episode metrics (the paper's "Additional Performance Metrics": return, length,
+     * first kill, win); all [E], all optional (NULL) */
+    float *ret_run;          /* allied return accumulated in the running episode       */
+    signed char *kill_run;   /* which team lost a unit first in the running episode:
+                                0 nobody yet, 1 adversaries, 2 allies, 3 both same tick */
+    int   *ep_count;         /* episodes finished so far                               */
+    int   *ep_len;           /* length of the last finished episode                    */
+    float *ep_return;        /* allied return of the last finished episode             */
+    signed char *ep_win;     /* 1 if the allies won it                                 */
+    signed char *ep_first_kill; /* kill_run at its end                                 */
 } RefState;
 
 int  tabx_ref_obs_dim(const RefParams *p);
@@ -77,6 +87,12 @@ void tabx_ref_step(const RefParams *p, const RefScenario *sc, RefState *st,
 void tabx_ref_observe(const RefParams *p, const RefScenario *sc, const RefState *st,
                       float *obs, unsigned long long *vis_mask,
                       unsigned char *action_mask, double *min_margin);
+
+/* Global state (App. A "Global state"): out [E][16 * N + 6 * Z]: every unit's own block
+ * (as in its observation row, absolute position, zero if disabled), then the zone slots
+ * with absolute centres (zero for type 0).  No visibility masking. */
+void tabx_ref_global_state(const RefParams *p, const RefScenario *sc, const RefState *st,
+                           float *out);
 
 #ifdef __cplusplus
 }

@@ -423,3 +423,55 @@ def test_reset_mask():
         assert np.array_equal(v[keep], before[k][keep]), k
     assert list(env.st["t"][[2, 7]]) == [0, 0]
     assert np.array_equal(env.st["x"][[2, 7]], sc["init_x"][[2, 7]])
+
+
+# ------------------------------------------------------------------ episode metrics, global state
+def test_episode_metrics():
+    env = make_ref([unit("assassin", 0, 10.0, 10.0, 0.0), unit("healer", 1, 12.0, 10.0)])
+    for k in range(7):
+        assert env.st["ep_count"][0] == 0
+        env.step(acts(A.ACT_ATTACK, A.ACT_NOOP))
+    n, ret, win, fk = G["metrics_kill_episode"]
+    assert env.st["ep_count"][0] == 1 and env.st["ep_len"][0] == n
+    assert env.st["ep_return"][0] == pytest.approx(ret, abs=1e-6)
+    assert env.st["ep_win"][0] == win and env.st["ep_first_kill"][0] == fk
+    assert env.st["ret_run"][0] == 0.0 and env.st["kill_run"][0] == 0      # fresh episode
+    env = make_ref([unit("assassin", 0, 5.0, 5.0), unit("assassin", 1, 25.0, 25.0)], max_steps=4)
+    for k in range(4):
+        env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    n, ret, win, fk = G["metrics_truncation_tie"]
+    assert (env.st["ep_len"][0], env.st["ep_return"][0], env.st["ep_win"][0],
+            env.st["ep_first_kill"][0]) == (n, ret, win, fk)
+    # an ally dying first (lava) is recorded as 2; both teams losing a unit in one tick as 3
+    g = np.zeros((8, 8), np.int8)
+    g[1, 1] = I.ZONE_LAVA
+    env = make_ref([unit("healer", 0, 6.0, 6.0), unit("archer", 0, 20.0, 20.0),
+                    unit("archer", 1, 25.0, 25.0)], grid=8, terrain=g)
+    for _ in range(25):
+        env.step(acts(A.ACT_NOOP, A.ACT_NOOP, A.ACT_NOOP))
+    assert env.st["kill_run"][0] == 2
+    env = make_ref([unit("assassin", 0, 10.0, 10.0, 0.0), unit("assassin", 0, 20.0, 20.0),
+                    unit("assassin", 1, 12.0, 10.0, math.pi), unit("assassin", 1, 25.0, 5.0)])
+    env.set_state(hp=np.array([[20.0, 70.0, 20.0, 70.0]], np.float32))
+    env.step(acts(A.ACT_ATTACK, A.ACT_NOOP, A.ACT_ATTACK, A.ACT_NOOP))
+    assert env.st["kill_run"][0] == 3
+
+
+def test_global_state_is_every_own_block_plus_absolute_zones():
+    w = I.WORKLOADS["c3_16384env_10v10"]
+    p, sc = I.make_params(w, 6), I.make_scenario(w, 6)
+    sc["enabled"][2, 5] = 0
+    env = ref.RefEnv(p, sc)
+    env.reset()
+    for s in range(40):
+        env.step(I.actions_for_step(w.seed, s, 6, w.num_units))
+    obs, _, _ = env.observe()
+    gs = env.global_state()
+    N, Z = w.num_units, w.max_zones
+    assert gs.shape == (6, 16 * N + 6 * Z)
+    for u in range(N):
+        assert np.array_equal(gs[:, 16 * u:16 * u + 16], obs[:, u, :16])
+    assert not gs[2, 16 * 5:16 * 6].any()
+    zd = sc["zone_desc"].reshape(6, Z * 6).copy()
+    zd[np.repeat(sc["zone_desc"][:, :, 0] == 0, 6, axis=1)] = 0.0
+    assert np.array_equal(gs[:, 16 * N:], zd)
