@@ -100,6 +100,18 @@ typedef struct TabxState {
     uint8_t *alive;
     int32_t *t;          /* [E] ticks since the episode began                 */
     float   *phi_prev;   /* [E] health-ratio potential after the previous tick */
+    /* Episode metrics (the paper's appendix "Additional Performance Metrics": episode
+     * return, episode length, first kill, win).  All [E]; each may be NULL, but the
+     * summaries need their running counterpart (ep_return needs ret_run, ep_first_kill
+     * needs kill_run).  tabx_reset clears the running ones. */
+    float   *ret_run;        /* allied return accumulated in the running episode        */
+    int8_t  *kill_run;       /* which team lost a unit first in the running episode:
+                                0 nobody yet, 1 adversaries, 2 allies, 3 both, same tick */
+    int32_t *ep_count;       /* episodes finished so far (incremented, never cleared)   */
+    int32_t *ep_len;         /* length of the last finished episode                     */
+    float   *ep_return;      /* allied return of the last finished episode              */
+    int8_t  *ep_win;         /* 1 if the allies won it                                  */
+    int8_t  *ep_first_kill;  /* kill_run at its end                                     */
 } TabxState;
 
 /* Floats per agent observation: 16 * N + 6 * max_zones.
@@ -145,6 +157,14 @@ int tabx_step_observe(const TabxParams *params, const TabxScenario *scenario,
                       const TabxState *state, const uint8_t *actions,
                       float *rewards, uint8_t *dones, float *obs,
                       uint64_t *vis_mask, uint8_t *action_mask, void *stream);
+
+/* Global state for centralised critics (App. A "Global state"): all unit features without
+ * visibility masking plus the zone slots.
+ *   out [E][16 * N + 6 * max_zones] f32: unit u's own block (as in its observation row,
+ *   absolute position; zero if disabled) at floats [16 u, 16 u + 16), then the zone slots
+ *   with absolute centres (zero for type 0).  16-byte aligned. */
+int tabx_global_state(const TabxParams *params, const TabxScenario *scenario,
+                      const TabxState *state, float *out, void *stream);
 
 const char *tabx_strerror(int code);
 

@@ -24,7 +24,14 @@ SCENARIO_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "s
 STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
 
 EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
-           "tabx_step_observe", "tabx_strerror")
+           "tabx_step_observe", "tabx_global_state", "tabx_strerror")
+
+_I8 = C.POINTER(C.c_int8)
+_I32 = C.POINTER(C.c_int32)
+METRICS = (("ret_run", _F, torch.float32), ("kill_run", _I8, torch.int8),
+           ("ep_count", _I32, torch.int32), ("ep_len", _I32, torch.int32),
+           ("ep_return", _F, torch.float32), ("ep_win", _I8, torch.int8),
+           ("ep_first_kill", _I8, torch.int8))
 
 
 class TabxParams(C.Structure):
@@ -43,7 +50,8 @@ class TabxScenario(C.Structure):
 
 class TabxState(C.Structure):
     _fields_ = [(n, _F) for n in STATE_FLOAT] + \
-               [("alive", _U8), ("t", C.POINTER(C.c_int32)), ("phi_prev", _F)]
+               [("alive", _U8), ("t", C.POINTER(C.c_int32)), ("phi_prev", _F)] + \
+               [(n, t) for n, t, _ in METRICS]
 
 
 class TabxError(RuntimeError):
@@ -63,6 +71,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.tabx_step.argtypes = [P, S, T, V, V, V, V]
     lib.tabx_observe.argtypes = [P, S, T, V, V, V, V]
     lib.tabx_step_observe.argtypes = [P, S, T, V, V, V, V, V, V, V]
+    lib.tabx_global_state.argtypes = [P, S, T, V, V]
     lib.tabx_strerror.argtypes = [C.c_int]
     lib.tabx_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -131,11 +140,16 @@ def tabx_step_observe(params, scenario, state, actions, rewards, dones, obs, vis
            "tabx_step_observe")
 
 
+def tabx_global_state(params, scenario, state, out, stream=None):
+    _check(_lib.tabx_global_state(C.byref(params), C.byref(scenario), C.byref(state), _ptr(out),
+                                  _stream_ptr(stream)), "tabx_global_state")
+
+
 class TabxEnv:
     """Device buffers of one batch of environments plus the calls on them."""
 
     def __init__(self, params: dict, scenario: dict, device="cuda:0", want_vis=True,
-                 want_action_mask=True):
+                 want_action_mask=True, want_metrics=False):
         self.device = torch.device(device)
         self.p = dict(params)
         self.params = make_params(self.p)
@@ -165,7 +179,11 @@ class TabxEnv:
         self.st["alive"] = torch.zeros(E * N, dtype=torch.uint8, device=dev)
         self.st["t"] = torch.zeros(E, dtype=torch.int32, device=dev)
         self.st["phi_prev"] = torch.zeros(E, dtype=torch.float32, device=dev)
-        self.state = self._state_struct(self.st)
+        self.metrics = {}
+        if want_metrics:
+            self.metrics = {n: torch.zeros(E, dtype=dt, device=dev) for n, _, dt in METRICS}
+        self.state = self._state_struct(self.st, self.metrics)
+        self.gstate = None
 
         self.rewards = torch.zeros(E, N, dtype=torch.float32, device=dev)
         self.dones = torch.zeros(E, dtype=torch.uint8, device=dev)
@@ -176,11 +194,19 @@ class TabxEnv:
                       if want_action_mask else None)
 
     @staticmethod
-    def _state_struct(st: dict) -> TabxState:
+    def _state_struct(st: dict, metrics: dict) -> TabxState:
         return TabxState(**{k: _cast(st[k], _F) for k in STATE_FLOAT},
                          alive=_cast(st["alive"], _U8),
                          t=_cast(st["t"], C.POINTER(C.c_int32)),
-                         phi_prev=_cast(st["phi_prev"], _F))
+                         phi_prev=_cast(st["phi_prev"], _F),
+                         **{n: _cast(metrics[n], t) for n, t, _ in METRICS if n in metrics})
+
+    def global_state(self, stream=None):
+        if self.gstate is None:
+            self.gstate = torch.zeros(self.E, 16 * self.N + 6 * self.p["max_zones"],
+                                      dtype=torch.float32, device=self.device)
+        tabx_global_state(self.params, self.scenario, self.state, self.gstate, stream)
+        return self.gstate
 
     def reset(self, env_mask=None, stream=None):
         tabx_reset(self.params, self.scenario, self.state, env_mask, stream)

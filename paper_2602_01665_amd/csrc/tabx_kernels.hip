@@ -439,6 +439,13 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
                           has && U.alive && U.team == 0, has && U.alive && U.team != 0};
     int cnt[4];
     env_counts(sh, P, N, pred, cnt);
+    // episode metrics need the alive counts at entry as well (first loss of a unit)
+    const bool want_kills = a.st.kill_run != nullptr;
+    int before[4] = {0, 0, 0, 0};
+    if (want_kills) {
+        const bool pred0[4] = {alive0 && U.team == 0, alive0 && U.team != 0, false, false};
+        env_counts(sh, P, N, pred0, before);
+    }
     lds_barrier<WAVES>();
 
     // reward (Eq. 1), termination, terminal bonus
@@ -486,6 +493,25 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
         a.st.t[P.e] = done ? 0 : t_new;
         a.st.phi_prev[P.e] = phi_next;
         a.dones[P.e] = done ? 1 : 0;
+        // episode metrics: first loss of a unit, running allied return, summary at the end
+        int kills = 0;
+        if (want_kills) {
+            kills = a.st.kill_run[P.e];
+            if (kills == 0) kills = (cnt[3] < before[1] ? 1 : 0) | (cnt[2] < before[0] ? 2 : 0);
+            a.st.kill_run[P.e] = (int8_t)(done ? 0 : kills);
+        }
+        float ret = 0.0f;
+        if (a.st.ret_run) {
+            ret = a.st.ret_run[P.e] + r0;
+            a.st.ret_run[P.e] = done ? 0.0f : ret;
+        }
+        if (done) {
+            if (a.st.ep_count) a.st.ep_count[P.e] += 1;
+            if (a.st.ep_len) a.st.ep_len[P.e] = t_new;
+            if (a.st.ep_return && a.st.ret_run) a.st.ep_return[P.e] = ret;
+            if (a.st.ep_win) a.st.ep_win[P.e] = (m0 > m1) ? 1 : 0;
+            if (a.st.ep_first_kill && want_kills) a.st.ep_first_kill[P.e] = (int8_t)kills;
+        }
     }
     if (has) store_state(a, P.k, U);
     C.cu = cu;
@@ -778,6 +804,53 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
     if (go && P.u == 0) {
         a.st.t[P.e] = 0;
         a.st.phi_prev[P.e] = m0 - m1;
+        if (a.st.ret_run) a.st.ret_run[P.e] = 0.0f;
+        if (a.st.kill_run) a.st.kill_run[P.e] = 0;
+    }
+}
+
+// Global state: every enabled unit's own block, then the zone slots with absolute centres.
+// One thread per unit (16 floats, four 16-byte stores) or per zone chunk.
+__global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, float *out)
+{
+    const int N = a.p.num_units;
+    const int zlen = 6 * a.p.max_zones;
+    const int Dg = 16 * N + zlen;
+    const size_t units = (size_t)a.p.num_envs * N;
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid < units) {
+        const int e = (int)(tid / N);
+        const int u = (int)(tid - (size_t)e * N);
+        Unit U = {};
+        load_spec(a, tid, U);
+        load_state(a, tid, U);
+        float4 q[4];
+        if (U.enabled) {
+            const int code = terrain_code(a, e, U.x, U.y);
+            q[0] = make_float4(U.hp, U.hp / U.hmax, U.x, U.y);
+            q[1] = make_float4(U.theta, U.range, U.dmg, U.cd);
+            q[2] = make_float4(U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f, U.radius, U.mass,
+                               U.sight_angle);
+            q[3] = make_float4(U.alive ? 1.0f : 0.0f, U.cur_speed, (float)(code & 3), (float)U.team);
+        } else {
+            q[0] = q[1] = q[2] = q[3] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+        float *d = out + (size_t)e * Dg + 16 * u;       // Dg may be 2 mod 4: 8-byte aligned rows
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f4u o = {q[k].x, q[k].y, q[k].z, q[k].w};
+            *reinterpret_cast<f4u *>(d + 4 * k) = o;
+        }
+    }
+    // zone floats: one thread per float, after the unit threads
+    const size_t zt = tid;
+    const size_t zones = (size_t)a.p.num_envs * zlen;
+    if (zlen > 0 && zt < zones) {
+        const int e = (int)(zt / zlen);
+        const int zz = (int)(zt - (size_t)e * zlen);
+        const float *d = a.sc.zone_desc + (size_t)e * zlen;
+        const int comp = zz % 6;
+        out[(size_t)e * Dg + 16 * N + zz] = d[zz - comp] != 0.0f ? d[zz] : 0.0f;
     }
 }
 
@@ -834,6 +907,9 @@ static int check_state(const TabxState *s)
     }
     if (!s->alive || !s->t) return TABX_ERR_NULL;
     if (!aligned(s->t, 4)) return TABX_ERR_ALIGN;
+    const void *m4[] = {s->ret_run, s->ep_count, s->ep_len, s->ep_return};
+    for (const void *q : m4)
+        if (q && !aligned(q, 4)) return TABX_ERR_ALIGN;
     return TABX_OK;
 }
 
@@ -979,6 +1055,35 @@ int tabx_step_observe(const TabxParams *p, const TabxScenario *sc, const TabxSta
 {
     return tabx::run(tabx::MODE_STEP_OBSERVE, p, sc, st, actions, nullptr, rewards, dones, obs,
                      vis_mask, action_mask, stream);
+}
+
+int tabx_global_state(const TabxParams *p, const TabxScenario *sc, const TabxState *st,
+                      float *out, void *stream)
+{
+    int rc = tabx::check_params(p);
+    if (rc) return rc;
+    if (p->num_envs == 0) return TABX_OK;
+    if ((rc = tabx::check_scenario(p, sc))) return rc;
+    if ((rc = tabx::check_state(st))) return rc;
+    if (!out) return TABX_ERR_NULL;
+    if (!tabx::aligned(out, 16)) return TABX_ERR_ALIGN;
+    tabx::KArgs a = {};
+    a.p = *p;
+    a.sc = *sc;
+    a.st = *st;
+    {
+        int ex = 0;
+        const float mant = frexpf(p->cell_size, &ex);
+        a.cell_pow2 = (mant == 0.5f && ex > -100 && ex < 100) ? 1 : 0;
+        a.inv_cell = 1.0f / p->cell_size;
+    }
+    const size_t units = (size_t)p->num_envs * p->num_units;
+    const size_t zones = (size_t)p->num_envs * 6 * p->max_zones;
+    const size_t threads = units > zones ? units : zones;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(tabx::tabx_global_state_kernel, dim3((unsigned)((threads + 255) / 256)),
+                       dim3(256), 0, (hipStream_t)stream, a, out);
+    return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
 }
 
 const char *tabx_strerror(int code)

@@ -42,6 +42,23 @@ def compare_state(gpu_state: dict, ref_state: dict, where="", rows=None):
     return inexact
 
 
+METRIC_FLOAT = ("ret_run", "ep_return")
+METRIC_INT = ("kill_run", "ep_count", "ep_len", "ep_win", "ep_first_kill")
+
+
+def compare_metrics(gpu, ref, where="", rows=None):
+    """Episode metrics of a TabxEnv built with want_metrics=True against the checker's."""
+    inexact = 0
+    for k in METRIC_FLOAT + METRIC_INT:
+        g = gpu.metrics[k] if rows is None else gpu.metrics[k][rows]
+        g = g.cpu().numpy()
+        if k in METRIC_FLOAT:
+            inexact += _cmp_float(k, g, ref.st[k], where)
+        else:
+            _cmp_int(k, g, ref.st[k], where)
+    return inexact
+
+
 def compare_outputs(gpu, ref, where="", rows=None, check_obs=True):
     """gpu: TabxEnv (torch tensors), ref: RefEnv.  Returns the number of float entries that
     are within tolerance but not bit-identical."""

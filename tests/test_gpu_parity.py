@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 from paper_2602_01665_amd import inputs as I
-from tests.parity import compare_outputs, compare_state
+from tests.parity import compare_metrics, compare_outputs, compare_state
 
 pytestmark = pytest.mark.gpu
 
@@ -32,7 +32,7 @@ def _pair(w, E, scenario=None, **override):
     p = I.make_params(w, E, **override)
     sc = I.make_scenario(w, E) if scenario is None else scenario
     ref = RefEnv(p, sc)
-    gpu = TabxEnv(p, sc)
+    gpu = TabxEnv(p, sc, want_metrics=True)
     ref.reset()
     gpu.reset()
     torch.cuda.synchronize()
@@ -62,7 +62,13 @@ def _rollout(w, E, steps, fused, scenario=None, obs_every=1, **override):
         where = f"{w.name} E={E} step {s}: "
         inexact += compare_state(gpu.state_numpy(), ref.st, where)
         inexact += compare_outputs(gpu, ref, where, check_obs=look or fused)
+        inexact += compare_metrics(gpu, ref, where)
+        if s % 16 == 0:
+            g = gpu.global_state()
+            torch.cuda.synchronize()
+            assert np.array_equal(g.cpu().numpy(), ref.global_state()), where + "global state"
         dones += int(ref.dones.sum())
+    assert int(ref.st["ep_count"].sum()) == dones
     return inexact, dones
 
 
@@ -312,7 +318,7 @@ def test_full_size_sampled_envs(name, steps, n_sample):
     rows = np.unique(np.concatenate([[0, 1, E - 1], rng.choice(E, n_sample - 3, replace=False)]))
     ref = RefEnv(I.make_params(w, len(rows)), I.take_envs(sc, rows))
     ref.track_margin = True
-    gpu = TabxEnv(p, sc)
+    gpu = TabxEnv(p, sc, want_metrics=True)
     ref.reset()
     gpu.reset()
     rows_t = torch.from_numpy(rows).to("cuda:0")
@@ -327,11 +333,14 @@ def test_full_size_sampled_envs(name, steps, n_sample):
         where = f"{name} full size step {s}: "
         inexact += compare_state(st, ref.st, where)
         inexact += compare_outputs(gpu, ref, where, rows=rows_t)
+        inexact += compare_metrics(gpu, ref, where, rows=rows_t)
         dones += int(ref.dones.sum())
         if s % 100 == 0:
             _say(f"[gpu]   step {s} ok")
     _say(f"[gpu]   inexact floats {inexact}; sampled episodes ended {dones}; smallest "
          f"boundary margin seen by the checker {ref.margin.min():.3e}")
+    gs = gpu.global_state()[rows_t].cpu().numpy()
+    assert np.array_equal(gs, ref.global_state()), "global state of the sampled envs"
     # properties that hold for every env at any size
     obs = gpu.obs
     assert torch.isfinite(obs).all()
