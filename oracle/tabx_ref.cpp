@@ -178,6 +178,52 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
         st.y[k] = clampf(y, 0.0f, P.map_h);
     }
 
+    /* ---- stage 1b: overlapping bodies are pushed apart (App. A "Collision detection and
+     * resolution").  Circle against circle: penetration depth pen = r_i + r_j - |p_j - p_i|
+     * along the normal n = (p_j - p_i) / |p_j - p_i|; what exceeds the slop is corrected by
+     * the fraction alpha, split by inverse mass (unit i takes m_j / (m_i + m_j) of it).
+     * All pairs are evaluated on the positions after the kinematic update and each unit
+     * adds its corrections in ascending partner index (Jacobi style), then is clipped to
+     * the arena again.  Dead bodies collide like live ones; disabled placeholders do not
+     * exist.  The impulse part of the paper's response changes velocities only, and the
+     * action stage rewrites every velocity later in the same tick, so it has no effect
+     * under this kinematic reading and is not modelled. */
+    if (P.collision_alpha > 0.0f) {
+        std::vector<float> px(N), py(N), ax(N, 0.0f), ay(N, 0.0f);
+        for (int u = 0; u < N; ++u) {
+            px[u] = st.x[b + u];
+            py[u] = st.y[b + u];
+        }
+        for (int i = 0; i < N; ++i) {
+            if (!S.enabled[b + i]) continue;
+            for (int j = 0; j < N; ++j) {
+                if (j == i || !S.enabled[b + j]) continue;
+                float dx = px[j] - px[i];
+                float dy = py[j] - py[i];
+                float dist = std::sqrt((dx * dx) + (dy * dy));
+                float pen = (S.radius[b + i] + S.radius[b + j]) - dist;
+                if (!(pen > P.collision_slop)) continue;
+                float nx, ny;
+                if (dist > 0.0f) {
+                    nx = dx / dist;
+                    ny = dy / dist;
+                } else {               /* coincident centres: separate along x by index */
+                    nx = (i < j) ? 1.0f : -1.0f;
+                    ny = 0.0f;
+                }
+                float share = S.mass[b + j] / (S.mass[b + i] + S.mass[b + j]);
+                float c = ((pen - P.collision_slop) * P.collision_alpha) * share;
+                ax[i] = ax[i] - (c * nx);
+                ay[i] = ay[i] - (c * ny);
+            }
+        }
+        for (int u = 0; u < N; ++u) {
+            if (!S.enabled[b + u]) continue;
+            st.x[b + u] = clampf(px[u] + ax[u], 0.0f, P.map_w);
+            st.y[b + u] = clampf(py[u] + ay[u], 0.0f, P.map_h);
+        }
+    }
+
     /* ---- stage 2: actions ---------------------------------------------------- */
     const float dtheta = P.turn_rate * P.dt;
     for (int u = 0; u < N; ++u) {

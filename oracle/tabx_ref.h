@@ -38,6 +38,8 @@ typedef struct RefParams {
     float map_w, map_h, cell_size;
     float dt, turn_rate;
     float lava_dps, swamp_mult, reveal_time, boundary_frac;
+    float collision_alpha;      /* fraction of an overlap corrected per tick; 0 = bodies pass through */
+    float collision_slop;       /* overlap tolerated without correction */
 } RefParams;
 
 typedef struct RefScenario {

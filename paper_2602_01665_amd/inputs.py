@@ -53,6 +53,8 @@ DEFAULTS = dict(
     boundary_frac=0.1,            # App. A "Movement and kinematic update"
     sight_angle=2.0 * math.pi / 3.0,
     sight_range=16.0,
+    collision_alpha=0.0,          # the benchmark tick has no body collisions; tests use 0.8
+    collision_slop=0.01,
 )
 
 FLOAT_UNIT_FIELDS = (
@@ -120,6 +122,7 @@ def make_params(w: Workload, num_envs: int | None = None, **override) -> dict:
         dt=DEFAULTS["dt"], turn_rate=DEFAULTS["turn_rate"],
         lava_dps=DEFAULTS["lava_dps"], swamp_mult=DEFAULTS["swamp_mult"],
         reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"],
+        collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"],
     )
     p.update(override)
     return p
@@ -301,6 +304,7 @@ def custom_params(num_units, map_size=32.0, grid=0, max_zones=0, **override) -> 
              cell_size=float(map_size / grid) if grid else 1.0,
              dt=DEFAULTS["dt"], turn_rate=DEFAULTS["turn_rate"],
              lava_dps=DEFAULTS["lava_dps"], swamp_mult=DEFAULTS["swamp_mult"],
-             reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"])
+             reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"],
+             collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"])
     p.update(override)
     return p

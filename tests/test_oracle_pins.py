@@ -475,3 +475,81 @@ def test_global_state_is_every_own_block_plus_absolute_zones():
     zd = sc["zone_desc"].reshape(6, Z * 6).copy()
     zd[np.repeat(sc["zone_desc"][:, :, 0] == 0, 6, axis=1)] = 0.0
     assert np.array_equal(gs[:, 16 * N:], zd)
+
+
+# ------------------------------------------------------------------ body collisions
+COLL = dict(collision_alpha=0.8, collision_slop=0.01)
+
+
+def test_collision_pushes_overlapping_bodies_apart():
+    env = make_ref([unit("assassin", 0, 10.0, 10.0), unit("assassin", 1, 11.5, 10.0)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    sh = G["collision_equal_mass_shift"][0]
+    assert env.st["x"][0, 0] == pytest.approx(10.0 - sh, abs=1e-6)
+    assert env.st["x"][0, 1] == pytest.approx(11.5 + sh, abs=1e-6)
+    assert env.st["x"][0, 1] - env.st["x"][0, 0] == pytest.approx(G["collision_equal_mass_dist"][0], abs=1e-6)
+    assert list(env.st["y"][0]) == [10.0, 10.0]
+    # along a diagonal the shift splits over both axes
+    d = 1.5 / math.sqrt(2)
+    env = make_ref([unit("assassin", 0, 10.0, 10.0), unit("assassin", 1, 10.0 + d, 10.0 + d)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    assert math.hypot(env.st["x"][0, 1] - env.st["x"][0, 0],
+                      env.st["y"][0, 1] - env.st["y"][0, 0]) == pytest.approx(1.892, abs=1e-5)
+    # touching within the slop, or apart: untouched; collisions off: untouched
+    for gap, kw in ((1.995, COLL), (2.5, COLL), (1.5, {})):
+        env = make_ref([unit("assassin", 0, 10.0, 10.0), unit("assassin", 1, 10.0 + gap, 10.0)], **kw)
+        env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+        assert list(env.st["x"][0]) == [10.0, np.float32(10.0 + gap)]
+
+
+def test_collision_is_mass_aware_and_ignores_liveness_and_teams():
+    env = make_ref([unit("mammoth", 0, 10.0, 10.0), unit("assassin", 0, 14.25, 10.0),
+                    unit("archer", 1, 28.0, 28.0)], **COLL)
+    env.set_state(hp=np.array([[685.0, 0.0, 40.0]], np.float32),
+                  alive=np.array([[1, 0, 1]], np.uint8))
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP, A.ACT_NOOP))
+    assert 10.0 - env.st["x"][0, 0] == pytest.approx(G["collision_heavy_shift"][0], abs=1e-6)
+    assert env.st["x"][0, 1] - 14.25 == pytest.approx(G["collision_light_shift"][0], abs=1e-6)
+    # disabled placeholders are not bodies
+    env = make_ref([unit("assassin", 0, 10.0, 10.0), unit("assassin", 1, 11.0, 10.0, enabled=0),
+                    unit("assassin", 1, 20.0, 20.0)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP, A.ACT_NOOP))
+    assert env.st["x"][0, 0] == 10.0
+    # coincident centres separate along x, lower index to the left
+    env = make_ref([unit("assassin", 0, 10.0, 10.0), unit("assassin", 1, 10.0, 10.0)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    assert env.st["x"][0, 0] < 10.0 < env.st["x"][0, 1] and list(env.st["y"][0]) == [10.0, 10.0]
+    # a correction that would leave the arena is clipped, without the out-of-arena penalty
+    env = make_ref([unit("assassin", 0, 0.05, 10.0), unit("mammoth", 1, 4.0, 10.0, theta=1.0)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    assert env.st["x"][0, 0] == 0.0 and env.st["hp"][0, 0] == 70.0
+
+
+def test_collision_keeps_the_centre_of_mass_and_matches_float64():
+    """Random crowded env: with no clipping the mass-weighted mean position is unchanged, and
+    every displacement agrees with a float64 evaluation of the same pair sum."""
+    rng = np.random.default_rng(12)
+    names = list(I.ROSTER)
+    units = [unit(names[k % 9], k % 2, float(rng.uniform(30, 50)), float(rng.uniform(30, 50)))
+             for k in range(24)]
+    env = make_ref(units, map_size=80.0, **COLL)
+    x0, y0 = env.st["x"][0].astype(np.float64), env.st["y"][0].astype(np.float64)
+    m = env.sc["mass"][0].astype(np.float64)
+    r = env.sc["radius"][0].astype(np.float64)
+    env.step(np.zeros((1, 24), np.uint8))
+    x1, y1 = env.st["x"][0].astype(np.float64), env.st["y"][0].astype(np.float64)
+    assert np.abs(x1 - x0).max() > 0.1
+    assert abs((m * (x1 - x0)).sum()) < 1e-3 and abs((m * (y1 - y0)).sum()) < 1e-3
+    ex, ey = np.zeros(24), np.zeros(24)
+    for i in range(24):
+        for j in range(24):
+            if i == j:
+                continue
+            dx, dy = x0[j] - x0[i], y0[j] - y0[i]
+            dist = math.hypot(dx, dy)
+            pen = r[i] + r[j] - dist
+            if pen > 0.01:
+                c = (pen - 0.01) * 0.8 * m[j] / (m[i] + m[j])
+                ex[i] -= c * dx / dist
+                ey[i] -= c * dy / dist
+    assert np.allclose(x1 - x0, ex, atol=2e-5) and np.allclose(y1 - y0, ey, atol=2e-5)
