@@ -74,6 +74,14 @@ typedef struct TabxParams {
     float   swamp_mult;           /* speed multiplier inside a swamp                 */
     float   reveal_time;          /* how long combat exposes a unit hidden in a bush */
     float   boundary_frac;        /* out-of-arena damage = boundary_frac*hmax*dt     */
+    /* Body collisions (App. A "Collision detection and resolution"): after the kinematic
+     * update overlapping body circles are pushed apart: of the penetration depth beyond
+     * collision_slop the fraction collision_alpha is corrected per tick, split by inverse
+     * mass (needs mass > 0), every unit summing its corrections over its partners in
+     * ascending index on the pre-correction positions, then clipped to the arena.  Dead
+     * bodies collide, disabled placeholders do not.  collision_alpha = 0 switches it off. */
+    float   collision_alpha;
+    float   collision_slop;
 } TabxParams;
 
 /* The scenario: unit specifications and zones (the unit and zone axes of the

@@ -339,6 +339,39 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
         }
     }
 
+    // stage 1b: overlapping bodies are pushed apart.  Every unit sums, over its partners in
+    // ascending index, the share of each overlap it has to give way for; all pairs are taken
+    // on the positions after the kinematic update; then the unit is clipped again.
+    if (a.p.collision_alpha > 0.0f) {
+        // partner record: x, y, radius, mass (negative mass: not a body)
+        sh.st.pj[P.l] = make_float4(U.x, U.y, U.radius, (has && U.enabled) ? U.mass : -1.0f);
+        lds_barrier<WAVES>();
+        float ax = 0.0f, ay = 0.0f;
+        for (int jj = 0; jj < N; ++jj) {
+            const float4 J = sh.st.pj[P.base + jj];
+            const float dx = J.x - U.x;
+            const float dy = J.y - U.y;
+            const float dist = __builtin_sqrtf((dx * dx) + (dy * dy));
+            const float pen = (U.radius + J.z) - dist;
+            const bool apart = dist > 0.0f;
+            // coincident centres separate along x, the lower index to the left
+            const float nx = apart ? dx / dist : (P.u < jj ? 1.0f : -1.0f);
+            const float ny = apart ? dy / dist : 0.0f;
+            const float share = J.w / (U.mass + J.w);
+            const float c = ((pen - a.p.collision_slop) * a.p.collision_alpha) * share;
+            const bool push = (pen > a.p.collision_slop) && (jj != P.u) && (J.w >= 0.0f);
+            // subtracting a zero product leaves the finite sum unchanged
+            const float ce = push ? c : 0.0f;
+            ax = ax - (ce * nx);
+            ay = ay - (ce * ny);
+        }
+        if (has && U.enabled) {
+            U.x = clamp_between(U.x + ax, 0.0f, a.p.map_w);
+            U.y = clamp_between(U.y + ay, 0.0f, a.p.map_h);
+        }
+        lds_barrier<WAVES>();          // the partner records are rewritten for the combat stage
+    }
+
     // the position is final for this tick: fetch the terrain cell under it now, the zone
     // effects of stage 3 use it after the combat exchange
     if (has && U.enabled) code_u = terrain_code(a, P.e, U.x, U.y);
@@ -873,7 +906,7 @@ static int check_params(const TabxParams *p)
     for (float v : pos)
         if (!(v > 0.0f) || !(v < 3.0e38f)) return TABX_ERR_PARAM;
     const float fin[] = {p->turn_rate, p->lava_dps, p->swamp_mult, p->reveal_time,
-                         p->boundary_frac};
+                         p->boundary_frac, p->collision_alpha, p->collision_slop};
     for (float v : fin)
         if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
     return TABX_OK;

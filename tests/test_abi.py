@@ -36,7 +36,8 @@ def test_every_declared_symbol_is_exported(B):
 def _params(B, **kw):
     base = dict(num_envs=4, num_units=20, grid_w=0, grid_h=0, max_zones=8, max_steps=10,
                 map_w=8.0, map_h=8.0, cell_size=1.0, dt=0.25, turn_rate=1.0, lava_dps=1.0,
-                swamp_mult=0.5, reveal_time=1.0, boundary_frac=0.1)
+                swamp_mult=0.5, reveal_time=1.0, boundary_frac=0.1, collision_alpha=0.0,
+                collision_slop=0.01)
     base.update(kw)
     return B.TabxParams(**base)
 

@@ -184,6 +184,38 @@ def test_degenerate_team_shapes():
             compare_outputs(gpu, ref, f"{name} step {s}: ")
 
 
+@pytest.mark.parametrize("name,E,steps", [("c1_16env_3v3", 16, 100), ("c3_16384env_10v10", 48, 120),
+                                          ("c5_1024env_64v64", 2, 40)])
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_rollout_with_body_collisions(name, E, steps, fused):
+    """The optional collision correction of the physics stage, crowded spawns included."""
+    _say(f"[gpu] collisions on: {name} E={E} fused={fused}")
+    inexact, dones = _rollout(I.WORKLOADS[name], E, steps, fused, max_steps=40,
+                              collision_alpha=0.8, collision_slop=0.01)
+    assert dones > 0
+
+
+def test_collisions_in_a_crowd_of_mixed_bodies():
+    names = list(I.ROSTER)
+    rng = np.random.default_rng(9)
+    units = [dict(unit=names[k % 9], team=k % 2, x=float(rng.uniform(10, 22)),
+                  y=float(rng.uniform(10, 22)), theta=float(rng.uniform(0, 6.28)))
+             for k in range(30)]
+    one = I.custom_scenario(units, 32.0)
+    E = 21
+    sc = {k: (None if v is None else np.ascontiguousarray(np.repeat(v, E, axis=0)))
+          for k, v in one.items()}
+    sc["init_x"] = (sc["init_x"] + rng.uniform(-3, 3, sc["init_x"].shape)).astype(np.float32)
+    sc["init_y"] = (sc["init_y"] + rng.uniform(-3, 3, sc["init_y"].shape)).astype(np.float32)
+    sc["init_x"][:, 3] = sc["init_x"][:, 2]          # coincident centres
+    sc["init_y"][:, 3] = sc["init_y"][:, 2]
+    w = I.Workload("crowd", E, 15, 32.0, 0, "none", 1.0, "iid", steps=80, seed=77)
+    _say("[gpu] collisions in a crowd of 30 mixed bodies")
+    inexact, dones = _rollout(w, E, 80, True, scenario=sc, max_steps=30, collision_alpha=0.5,
+                              collision_slop=0.05)
+    assert dones > 0
+
+
 def test_other_roster_units():
     """Every roster row (big bodies, wide hurtboxes, long cooldowns) in one battle."""
     names = list(I.ROSTER)
