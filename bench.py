@@ -65,6 +65,9 @@ def main() -> int:
     ap.add_argument("--calibrate", action="store_true",
                     help="also time a plain device fill and copy of the obs-sized buffer "
                          "(reference points for the HBM roofline and for rocprofv3 byte counters)")
+    ap.add_argument("--collisions", action="store_true",
+                    help="switch the optional body-collision correction on (alpha 0.8, slop 0.01); "
+                         "not part of the headline tick")
     ap.add_argument("--separate", action="store_true",
                     help="time tabx_step + tabx_observe as two launches instead of the fused one")
     args = ap.parse_args()
@@ -87,7 +90,7 @@ def main() -> int:
     name = args.workload or I.HEADLINE
     w = I.WORKLOADS[name]
     E, N = w.num_envs, w.num_units
-    p = I.make_params(w)
+    p = I.make_params(w, **(dict(collision_alpha=0.8) if args.collisions else {}))
     scenario = I.make_scenario(w)
     env = TabxEnv(p, scenario)
     env.reset()
@@ -131,6 +134,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": name, "num_envs": E, "units_per_env": N, "obs_dim": env.D,
                    "launch": "separate step+observe" if args.separate else "fused step_observe",
+                   "body_collisions": bool(args.collisions),
                    "actions": f"{n_act} pre-generated seeded uniform action batches, cycled"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
