@@ -48,6 +48,8 @@ struct KArgs {
     int       row_pitch;           // floats between staged rows: D rounded up to 4
     int       copy_passes;         // ceil(G * R * row_pitch / 4 / lanes), <= kMaxPasses
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
+    int       num_groups;          // workgroups that have envs to process
+    int       groups_per_xcd;      // ceil(num_groups / 8)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
     int       cell_pow2;
 };
@@ -114,6 +116,7 @@ struct Unit {
 // Where a lane sits: env slot g of the workgroup, unit u of that env, `base` =
 // workgroup lane of the env's unit 0, e = env index, k = e * N + u.
 struct Place {
+    int grp;           // which run of G envs this workgroup owns
     int l, g, u, base, e;
     bool has;
     size_t k;
@@ -244,8 +247,12 @@ __device__ __forceinline__ Place locate(const KArgs &a)
         P.g = 0;
         P.u = P.l;
     }
-    P.e = blockIdx.x * a.envs_per_block + P.g;
-    P.has = P.g < a.envs_per_block && P.u < N && P.e < a.p.num_envs;
+    // Workgroups are dealt to the 8 XCDs round robin; give each XCD one contiguous eighth of
+    // the env range, so that neighbouring env groups, which share the cache lines at the ends
+    // of their SoA segments, meet in the same L2.
+    P.grp = (int)(blockIdx.x & 7) * a.groups_per_xcd + (int)(blockIdx.x >> 3);
+    P.e = P.grp * a.envs_per_block + P.g;
+    P.has = P.grp < a.num_groups && P.g < a.envs_per_block && P.u < N && P.e < a.p.num_envs;
     P.base = P.has ? P.l - P.u : 0;
     P.k = (size_t)P.e * N + P.u;
     return P;
@@ -574,7 +581,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const bool has = P.has;
     const int lane = P.l & 63;
     const int wv = P.l >> 6;
-    const int envs_here = (a.p.num_envs - blockIdx.x * G) < G ? (a.p.num_envs - blockIdx.x * G) : G;
+    const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
+    const int envs_here = envs_left < G ? envs_left : G;
 
     lds_barrier<WAVES>();                        // the step stage is done with the LDS union
 
@@ -616,7 +624,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     float zval[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     int zsx[4] = {0, 0, 0, 0}, zsy[4] = {0, 0, 0, 0};
     if (zone_lane) {
-        const float *d = a.sc.zone_desc + (size_t)(blockIdx.x * G + zg) * zlen;
+        const float *d = a.sc.zone_desc + (size_t)(P.grp * G + zg) * zlen;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int zz = 4 * zc + k;
@@ -658,7 +666,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     lds_barrier<WAVES>();
 
     // ---- one pass per observer index i: every lane's unit seen from observer i of its env
-    float *out = a.obs + (size_t)blockIdx.x * G * N * D;
+    float *out = a.obs + (size_t)P.grp * G * N * D;
     uint64_t my_row = 0;
     const int blk_row0 = (WAVES == 1) ? P.g * R * Dp : 0;
     for (int i0 = 0; i0 < N; i0 += R) {
@@ -949,11 +957,10 @@ static int check_state(const TabxState *s)
 template <int WAVES>
 static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
 {
-    const int G = a.envs_per_block;
-    const dim3 grid((unsigned)((a.p.num_envs + G - 1) / G)), block(64 * WAVES);
+    const dim3 grid((unsigned)(8 * a.groups_per_xcd)), block(64 * WAVES);
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
     // buffers for a two-wave workgroup)
-    const size_t rows_staged = WAVES == 1 ? (size_t)G * a.rows_per_flush : 2;
+    const size_t rows_staged = WAVES == 1 ? (size_t)a.envs_per_block * a.rows_per_flush : 2;
     // ... rounded up to whole store passes, which read their 16 bytes per lane unconditionally
     size_t dyn_floats = rows_staged * a.row_pitch;
     const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
@@ -1035,6 +1042,8 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     if (waves == 1 && a.obs_dim % 4 == 0 && N % 2 == 0 && (2 * G * cpr + 63) / 64 <= kMaxPasses)
         R = 2;
     a.rows_per_flush = R;
+    a.num_groups = (p->num_envs + G - 1) / G;
+    a.groups_per_xcd = (a.num_groups + 7) / 8;
     {
         int ex = 0;
         const float mant = frexpf(p->cell_size, &ex);
