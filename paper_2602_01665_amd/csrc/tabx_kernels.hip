@@ -566,10 +566,50 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
 // packed in the workgroup) are assembled in LDS as exact images of the HBM rows, pitch
 // row_pitch = D rounded up to 4 floats, and then go out in 16-byte chunks, chunk t of the
 // staged rows handled by lane t % lanes of store pass t / lanes.
+// Zone slots of the observation rows: lane (env slot zg, 16-byte chunk zc of the zone part)
+// keeps its four zone floats in registers for the whole launch: the value (zero if the slot
+// is inactive) and which observer coordinate to subtract (centre x / y of an active slot).
+struct ZoneRegs {
+    bool  lane;
+    int   zg, zc;
+    float val[4];
+    int   sx[4], sy[4];
+};
+
+// Issued at the top of the kernel so that the descriptor loads are long done when the
+// observe stage needs them.
+template <int WAVES>
+__device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &P)
+{
+    ZoneRegs Z = {};
+    const int G = a.envs_per_block;
+    const int zlen = 6 * a.p.max_zones;
+    const int ZC = (zlen + 3) >> 2;
+    const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
+    Z.zg = ZC > 0 ? P.l / ZC : 0;
+    Z.zc = P.l - Z.zg * ZC;
+    Z.lane = ZC > 0 && Z.zg < (envs_left < G ? envs_left : G);
+    if (Z.lane) {
+        const float *d = a.sc.zone_desc + (size_t)(P.grp * G + Z.zg) * zlen;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int zz = 4 * Z.zc + k;
+            if (zz < zlen) {
+                const int comp = zz % 6;
+                const bool active = d[zz - comp] != 0.0f;
+                Z.val[k] = active ? d[zz] : 0.0f;
+                Z.sx[k] = (active && comp == 1) ? -1 : 0;
+                Z.sy[k] = (active && comp == 2) ? -1 : 0;
+            }
+        }
+    }
+    return Z;
+}
+
 template <int WAVES, bool CARRIED>
 __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *stg,
                                             const Place &P, const Unit &U, int code_u,
-                                            const Carry &C)
+                                            const Carry &C, const ZoneRegs &Zr)
 {
     constexpr int LANES = 64 * WAVES;
     const int N = a.p.num_units;
@@ -615,28 +655,12 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const float own_zone = (float)(code_u & 3);
     const float own_team = (float)U.team;
 
-    // ---- zone chunks: lane (env slot zg, chunk zc) keeps its four zone floats in registers:
-    // value (zero if the slot is inactive) and which observer coordinate to subtract
-    const int ZC = (zlen + 3) >> 2;
-    const int zg = ZC > 0 ? P.l / ZC : 0;
-    const int zc = P.l - zg * ZC;
-    const bool zone_lane = ZC > 0 && zg < envs_here;
-    float zval[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    int zsx[4] = {0, 0, 0, 0}, zsy[4] = {0, 0, 0, 0};
-    if (zone_lane) {
-        const float *d = a.sc.zone_desc + (size_t)(P.grp * G + zg) * zlen;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int zz = 4 * zc + k;
-            if (zz < zlen) {
-                const int comp = zz % 6;
-                const bool active = d[zz - comp] != 0.0f;
-                zval[k] = active ? d[zz] : 0.0f;
-                zsx[k] = (active && comp == 1) ? -1 : 0;
-                zsy[k] = (active && comp == 2) ? -1 : 0;
-            }
-        }
-    }
+    // ---- zone chunks: lane (env slot zg, chunk zc) holds its four zone floats in registers
+    const int zg = Zr.zg, zc = Zr.zc;
+    const bool zone_lane = Zr.lane;
+    const float (&zval)[4] = Zr.val;
+    const int (&zsx)[4] = Zr.sx;
+    const int (&zsy)[4] = Zr.sy;
     const int zone_seer0 = (WAVES == 1) ? zg * N : 0;     // lane of observer 0 of the zone lane's env
     const int R = a.rows_per_flush;
     const int zone_dst0 = ((WAVES == 1) ? zg * R * Dp : 0) + 16 * N + 4 * zc;
@@ -812,10 +836,12 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         load_spec(a, P.k, U);
         load_state(a, P.k, U);
     }
+    ZoneRegs Zr = {};
+    if (DO_OBS) Zr = load_zone_regs<WAVES>(a, P);
     Carry C = {1.0f, 0.0f, 0.0f};
     if (DO_STEP) step_env<WAVES>(a, sh, P, U, code_u, C);
     else if (P.has) code_u = terrain_code(a, P.e, U.x, U.y);
-    if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C);
+    if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C, Zr);
 }
 
 template <int WAVES>
