@@ -24,7 +24,8 @@ class RefParams(C.Structure):
                 ("num_envs", "num_units", "grid_w", "grid_h", "max_zones", "max_steps")] + \
                [(n, C.c_float) for n in
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
-                 "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")]
+                 "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
+               [("zone_shapes", C.c_int)]
 
 
 _SC_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",
@@ -129,7 +130,7 @@ class RefEnv:
             zd = None
         self.sc["zone_desc"] = zd
 
-        self.cp = RefParams(**{k: self.p.get(k, 0.0) for k, _ in RefParams._fields_})
+        self.cp = RefParams(**{k: self.p.get(k, 0) for k, _ in RefParams._fields_})
         self.csc = RefScenario(**{k: _ptr(self.sc[k], _F) for k in _SC_FLOAT},
                                team=_ptr(self.sc["team"], _B),
                                enabled=_ptr(self.sc["enabled"], _B),

@@ -71,9 +71,27 @@ inline float clampf(float v, float lo, float hi)
     return v < lo ? lo : (v > hi ? hi : v);
 }
 
-/* Terrain cell code under a position (0 when there is no terrain). */
+/* Zone code under a position: low two bits = zone type, upper bits = zone identity; 0 = open.
+ * Cell-grid zones: the code stored in the cell.  Elliptical zones (App. A "Zones": type,
+ * centre, two axes, effect magnitude): the last listed active zone whose ellipse
+ * (x-cx)^2/hx^2 + (y-cy)^2/hy^2 <= 1 holds the point, tested without division as
+ * (dx^2)*hy^2 + (dy^2)*hx^2 <= hx^2*hy^2; identity = slot index + 1. */
 int cell_code(const RefParams &P, const RefScenario &S, int e, float x, float y)
 {
+    if (P.zone_shapes == 1) {
+        int code = 0;
+        for (int z = 0; z < P.max_zones && S.zone_desc; ++z) {
+            const float *d = S.zone_desc + ((long)e * P.max_zones + z) * 6;
+            if (d[0] == 0.0f) continue;
+            float dx = x - d[1];
+            float dy = y - d[2];
+            float hx2 = d[3] * d[3];
+            float hy2 = d[4] * d[4];
+            bool inside = ((dx * dx) * hy2) + ((dy * dy) * hx2) <= hx2 * hy2;
+            if (inside) code = ((int)d[0] & 3) | ((z + 1) << 2);
+        }
+        return code;
+    }
     if (!S.terrain || P.grid_w <= 0 || P.grid_h <= 0) return 0;
     int cx = (int)(x / P.cell_size);
     int cy = (int)(y / P.cell_size);
@@ -82,6 +100,15 @@ int cell_code(const RefParams &P, const RefScenario &S, int e, float x, float y)
     if (cx < 0) cx = 0;
     if (cy < 0) cy = 0;
     return (int)S.terrain[((long)e * P.grid_h + cy) * P.grid_w + cx];
+}
+
+/* Effect magnitude of the zone a code names: the zone's own (elliptical zones) or the
+ * global parameter (cell grid). */
+float zone_effect(const RefParams &P, const RefScenario &S, int e, int code, float global_value)
+{
+    if (P.zone_shapes == 1 && (code >> 2) > 0)
+        return S.zone_desc[((long)e * P.max_zones + ((code >> 2) - 1)) * 6 + 5];
+    return global_value;
 }
 
 /* Mean health ratio of one team over its enabled units, ascending index
@@ -114,8 +141,9 @@ void reset_env(const RefParams &P, const RefScenario &S, RefState &st, int e)
         st.cd[k] = 0.0f;
         st.reveal[k] = 0.0f;
         st.alive[k] = S.enabled[k] ? 1 : 0;
-        const int zone = cell_code(P, S, e, st.x[k], st.y[k]) & 3;
-        st.cur_speed[k] = (zone == ZONE_SWAMP) ? S.speed[k] * P.swamp_mult : S.speed[k];
+        const int code = cell_code(P, S, e, st.x[k], st.y[k]);
+        st.cur_speed[k] = ((code & 3) == ZONE_SWAMP)
+                              ? S.speed[k] * zone_effect(P, S, e, code, P.swamp_mult) : S.speed[k];
     }
     st.t[e] = 0;
     st.phi_prev[e] = team_ratio(P, S, st, e, 0) - team_ratio(P, S, st, e, 1);
@@ -302,16 +330,17 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
     }
 
     /* ---- stage 3: zone effects, alive flags, reward, termination -------------- */
-    const float lava_step = P.lava_dps * P.dt;
     for (int u = 0; u < N; ++u) {
         const int k = b + u;
         if (!S.enabled[k]) { st.alive[k] = 0; continue; }
-        const int zone = cell_code(P, S, e, st.x[k], st.y[k]) & 3;
+        const int code = cell_code(P, S, e, st.x[k], st.y[k]);
+        const int zone = code & 3;
         if (alive0[u] && zone == ZONE_LAVA) {
-            float h = st.hp[k] - lava_step;
+            float h = st.hp[k] - (zone_effect(P, S, e, code, P.lava_dps) * P.dt);
             st.hp[k] = h > 0.0f ? h : 0.0f;
         }
-        st.cur_speed[k] = (zone == ZONE_SWAMP) ? S.speed[k] * P.swamp_mult : S.speed[k];
+        st.cur_speed[k] = (zone == ZONE_SWAMP)
+                              ? S.speed[k] * zone_effect(P, S, e, code, P.swamp_mult) : S.speed[k];
         st.alive[k] = st.hp[k] > 0.0f ? 1 : 0;
     }
     st.t[e] += 1;

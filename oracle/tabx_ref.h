@@ -40,6 +40,8 @@ typedef struct RefParams {
     float lava_dps, swamp_mult, reveal_time, boundary_frac;
     float collision_alpha;      /* fraction of an overlap corrected per tick; 0 = bodies pass through */
     float collision_slop;       /* overlap tolerated without correction */
+    int   zone_shapes;          /* 0: zones are the cells of `terrain`; 1: zones are the ellipses of
+                                   zone_desc (centre, semi-axes, own effect magnitude)           */
 } RefParams;
 
 typedef struct RefScenario {

@@ -73,7 +73,7 @@ class Workload:
     team_size: int                 # units per team; N = 2 * team_size
     map_size: float
     grid: int                      # terrain cells per side, 0 = no terrain
-    terrain: str                   # "none" | "iid" | "rects"
+    terrain: str                   # "none" | "iid" | "rects" (cell grids) | "ellipses" (no grid)
     p_open: float
     roles: str                     # "one_each" | "iid" | "ratio"
     role_counts: tuple = ()        # per team, for "ratio"
@@ -123,6 +123,7 @@ def make_params(w: Workload, num_envs: int | None = None, **override) -> dict:
         lava_dps=DEFAULTS["lava_dps"], swamp_mult=DEFAULTS["swamp_mult"],
         reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"],
         collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"],
+        zone_shapes=1 if w.terrain == "ellipses" else 0,
     )
     p.update(override)
     return p
@@ -161,6 +162,22 @@ def _draw_roles(w: Workload, rng: np.random.Generator, E: int) -> np.ndarray:
 def _draw_terrain(w: Workload, rng: np.random.Generator, E: int, Z: int):
     """Returns (terrain int8 [E,G,G] or None, zone_desc float32 [E,Z,6] or None)."""
     G = w.grid
+    if w.terrain == "ellipses":
+        # App. A "Zones": type, centre, two semi-axes, effect magnitude; 4..Z active slots
+        assert Z >= 4 and G == 0
+        desc = np.zeros((E, Z, 6), np.float32)
+        count = rng.integers(4, Z + 1, size=E)
+        kind = rng.integers(1, 4, size=(E, Z))
+        desc[..., 0] = kind
+        desc[..., 1] = rng.uniform(0.0, w.map_size, size=(E, Z))
+        desc[..., 2] = rng.uniform(0.0, w.map_size, size=(E, Z))
+        desc[..., 3] = rng.uniform(2.0, 9.0, size=(E, Z))
+        desc[..., 4] = rng.uniform(2.0, 9.0, size=(E, Z))
+        effect = np.where(kind == ZONE_LAVA, rng.uniform(2.0, 6.0, size=(E, Z)),
+                          np.where(kind == ZONE_SWAMP, rng.uniform(0.3, 0.8, size=(E, Z)), 0.0))
+        desc[..., 5] = effect
+        desc[np.arange(Z)[None, :] >= count[:, None]] = 0.0
+        return None, desc
     if w.terrain == "none" or G == 0:
         return None, (np.zeros((E, Z, 6), np.float32) if Z else None)
     cell = w.map_size / G
@@ -305,6 +322,7 @@ def custom_params(num_units, map_size=32.0, grid=0, max_zones=0, **override) -> 
              dt=DEFAULTS["dt"], turn_rate=DEFAULTS["turn_rate"],
              lava_dps=DEFAULTS["lava_dps"], swamp_mult=DEFAULTS["swamp_mult"],
              reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"],
-             collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"])
+             collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"],
+             zone_shapes=0)
     p.update(override)
     return p

@@ -553,3 +553,79 @@ def test_collision_keeps_the_centre_of_mass_and_matches_float64():
                 ex[i] -= c * dx / dist
                 ey[i] -= c * dy / dist
     assert np.allclose(x1 - x0, ex, atol=2e-5) and np.allclose(y1 - y0, ey, atol=2e-5)
+
+
+# ------------------------------------------------------------------ elliptical zones
+def _ellipse_env(units, zones, **kw):
+    zd = np.zeros((8, 6), np.float32)
+    for k, z in enumerate(zones):
+        zd[k] = z
+    return make_ref(units, zone_desc=zd, max_zones=8, zone_shapes=1, **kw)
+
+
+@pytest.mark.parametrize("off,inside", [((3.9, 0.0), True), ((4.1, 0.0), False), ((0.0, 1.9), True),
+                                        ((0.0, 2.1), False), ((-3.9, 0.0), True), ((0.0, -2.1), False),
+                                        ((2.8, 1.4), True), ((2.88, 1.44), False)])
+def test_ellipse_membership_and_own_effect(off, inside):
+    lava = (I.ZONE_LAVA, 10.0, 10.0, 4.0, 2.0, 8.0)
+    env = _ellipse_env([unit("archer", 0, 10.0 + off[0], 10.0 + off[1]),
+                        unit("archer", 1, 28.0, 28.0)], [lava])
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    lost = 40.0 - env.st["hp"][0, 0]
+    assert lost == (G["ellipse_lava_per_step"][0] if inside else 0.0)
+    obs, _, _ = env.observe()
+    assert obs[0, 0, 14] == (float(I.ZONE_LAVA) if inside else 0.0)
+    # the zone slot of the observation is the descriptor relative to the observer
+    assert list(obs[0, 0, 32:38]) == [1.0, np.float32(10.0) - env.st["x"][0, 0],
+                                      np.float32(10.0) - env.st["y"][0, 0], 4.0, 2.0, 8.0]
+
+
+def test_ellipse_precedence_effects_and_bush_identity():
+    # the later zone wins where two overlap: swamp over lava, no lava damage inside both
+    zones = [(I.ZONE_LAVA, 10.0, 10.0, 5.0, 5.0, 8.0), (I.ZONE_SWAMP, 12.0, 10.0, 2.0, 2.0, 0.5),
+             (I.ZONE_SWAMP, 24.0, 24.0, 3.0, 3.0, 0.25)]
+    env = _ellipse_env([unit("archer", 0, 12.0, 10.0), unit("archer", 0, 24.0, 24.0),
+                        unit("archer", 1, 8.0, 10.0)], zones)
+    assert list(env.st["cur_speed"][0]) == [0.5, 0.25, 1.0]       # spawned inside the swamps
+    x0 = env.st["x"][0].copy()
+    env.step(acts(A.ACT_XP, A.ACT_XP, A.ACT_NOOP))
+    env.step(acts(A.ACT_XP, A.ACT_XP, A.ACT_NOOP))
+    assert list((env.st["x"][0] - x0)[:2]) == G["ellipse_swamp_steps"]
+    assert list(env.st["hp"][0]) == [40.0, 40.0, 40.0 - 2 * 2.0]   # only the unit in plain lava burns
+    # two bushes: same one -> visible, different ones -> hidden, outside -> hidden
+    wide = dict(sight_angle=2 * math.pi, sight_cos_half=-1.0)
+    bushes = [(I.ZONE_BUSH, 10.0, 10.0, 3.0, 3.0, 0.0), (I.ZONE_BUSH, 20.0, 10.0, 3.0, 3.0, 0.0)]
+    def seen(observer_xy):
+        e = _ellipse_env([unit("assassin", 0, observer_xy[0], observer_xy[1], **wide),
+                          unit("assassin", 1, 10.0, 10.0, **wide)], bushes)
+        return vis_bit(e.observe()[1], 0, 0, 1)
+    assert seen((11.0, 11.0)) == 1 and seen((20.0, 10.0)) == 0 and seen((15.0, 10.0)) == 0
+
+
+def test_ellipse_membership_vs_float64_formula():
+    w = I.Workload("ell", 40, 5, 40.0, 0, "ellipses", 1.0, "iid", max_zones=8, steps=10, seed=5)
+    p, sc = I.make_params(w), I.make_scenario(w)
+    assert p["zone_shapes"] == 1 and sc["terrain"] is None
+    env = ref.RefEnv(p, sc)
+    env.reset()
+    checked = inside_n = 0
+    for s in range(10):
+        env.step(I.actions_for_step(w.seed, s, 40, 10))
+        obs, _, _ = env.observe()
+        for e in range(40):
+            for u in range(10):
+                x, y = float(env.st["x"][e, u]), float(env.st["y"][e, u])
+                want, margin = 0, np.inf
+                for z in range(8):
+                    t, cx, cy, hx, hy, _ = (float(v) for v in sc["zone_desc"][e, z])
+                    if t == 0:
+                        continue
+                    q = ((x - cx) / hx) ** 2 + ((y - cy) / hy) ** 2
+                    margin = min(margin, abs(q - 1.0))
+                    if q <= 1.0:
+                        want = int(t)
+                if margin > 1e-4:
+                    assert obs[e, u, 14] == float(want), (s, e, u)
+                    checked += 1
+                    inside_n += want != 0
+    assert checked > 3000 and inside_n > 300
