@@ -82,6 +82,13 @@ typedef struct TabxParams {
      * bodies collide, disabled placeholders do not.  collision_alpha = 0 switches it off. */
     float   collision_alpha;
     float   collision_slop;
+    /* Zone geometry.  0: zones are the cells of `terrain` (codes as in TabxZone) and the lava /
+     * swamp magnitudes are lava_dps / swamp_mult.  1: zones are the ellipses of zone_desc
+     * (App. A "Zones": type, centre, two semi-axes, own effect magnitude: lava loss per time
+     * unit or swamp speed multiplier); needs grid_w = grid_h = 0 and max_zones >= 1; a point
+     * belongs to the last listed active zone with (dx^2)*hy^2 + (dy^2)*hx^2 <= hx^2*hy^2, and
+     * two units share a bush iff they are in the same slot. */
+    int32_t zone_shapes;
 } TabxParams;
 
 /* The scenario: unit specifications and zones (the unit and zone axes of the

@@ -39,7 +39,8 @@ class TabxParams(C.Structure):
                 ("num_envs", "num_units", "grid_w", "grid_h", "max_zones", "max_steps")] + \
                [(n, C.c_float) for n in
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
-                 "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")]
+                 "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
+               [("zone_shapes", C.c_int32)]
 
 
 class TabxScenario(C.Structure):
@@ -96,7 +97,7 @@ def _cast(t, typ):
 
 
 def make_params(p: dict) -> TabxParams:
-    return TabxParams(**{k: p.get(k, 0.0) for k, _ in TabxParams._fields_})
+    return TabxParams(**{k: p.get(k, 0) for k, _ in TabxParams._fields_})
 
 
 def tabx_obs_dim(params: TabxParams) -> int:

@@ -49,6 +49,7 @@ struct KArgs {
     int       copy_passes;         // ceil(G * R * row_pitch / 4 / lanes), <= kMaxPasses
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
     int       num_groups;          // workgroups that have envs to process
+    int       zdesc_offset;        // elliptical zones: descriptor copy in dynamic LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
     int       cell_pow2;
@@ -158,8 +159,29 @@ __device__ __forceinline__ void lds_barrier()
     }
 }
 
-__device__ __forceinline__ int terrain_code(const KArgs &a, int e, float x, float y)
+// Zone code under a position: low two bits = zone type, upper bits = zone identity; 0 = open.
+// Cell-grid zones: the code stored in the cell.  Elliptical zones (App. A "Zones"): the last
+// listed active zone whose ellipse holds the point, tested without division as
+// (dx^2)*hy^2 + (dy^2)*hx^2 <= hx^2*hy^2; identity = slot index + 1, and `own_effect` returns
+// that zone's effect magnitude.  `zd` = the env's zone descriptors (LDS or global).
+__device__ __forceinline__ int zone_at(const KArgs &a, const float *zd, int e, float x, float y,
+                                       float &own_effect)
 {
+    if (a.p.zone_shapes == 1) {
+        int code = 0;
+        for (int z = 0; z < a.p.max_zones; ++z) {
+            const float *d = zd + 6 * z;
+            const float kind = d[0];
+            const float dx = x - d[1];
+            const float dy = y - d[2];
+            const float hx2 = d[3] * d[3];
+            const float hy2 = d[4] * d[4];
+            const bool inside = (kind != 0.0f) && (((dx * dx) * hy2) + ((dy * dy) * hx2) <= hx2 * hy2);
+            code = inside ? (((int)kind & 3) | ((z + 1) << 2)) : code;
+            own_effect = inside ? d[5] : own_effect;
+        }
+        return code;
+    }
     if (a.sc.terrain == nullptr) return 0;
     // dividing by a power of two and multiplying by its reciprocal round identically
     int cx = a.cell_pow2 ? (int)(x * a.inv_cell) : (int)(x / a.p.cell_size);
@@ -169,6 +191,13 @@ __device__ __forceinline__ int terrain_code(const KArgs &a, int e, float x, floa
     cx = cx < 0 ? 0 : cx;
     cy = cy < 0 ? 0 : cy;
     return (int)a.sc.terrain[((size_t)e * a.p.grid_h + cy) * a.p.grid_w + cx];
+}
+
+// Effect magnitude that applies in the zone just found: its own (elliptical zones) or the
+// global parameter (cell grid).
+__device__ __forceinline__ float zone_magnitude(const KArgs &a, float own_effect, float global_value)
+{
+    return a.p.zone_shapes == 1 ? own_effect : global_value;
 }
 
 __device__ __forceinline__ void load_spec(const KArgs &a, size_t k, Unit &U)
@@ -218,7 +247,8 @@ __device__ __forceinline__ void store_state(const KArgs &a, size_t k, const Unit
 
 // Episode start for one unit: spawn pose, full health, timers cleared.  Returns
 // the terrain cell code under the spawn point.
-__device__ __forceinline__ int spawn_unit(const KArgs &a, int e, size_t k, Unit &U)
+__device__ __forceinline__ int spawn_unit(const KArgs &a, const float *zd, int e, size_t k,
+                                          Unit &U, float &zeff)
 {
     U.x = a.sc.init_x[k];
     U.y = a.sc.init_y[k];
@@ -229,8 +259,9 @@ __device__ __forceinline__ int spawn_unit(const KArgs &a, int e, size_t k, Unit 
     U.cd = 0.0f;
     U.reveal = 0.0f;
     U.alive = U.enabled ? 1 : 0;
-    const int code = terrain_code(a, e, U.x, U.y);
-    U.cur_speed = (code & 3) == TABX_ZONE_SWAMP ? U.speed * a.p.swamp_mult : U.speed;
+    const int code = zone_at(a, zd, e, U.x, U.y, zeff);
+    U.cur_speed = (code & 3) == TABX_ZONE_SWAMP
+                      ? U.speed * zone_magnitude(a, zeff, a.p.swamp_mult) : U.speed;
     return code;
 }
 
@@ -317,9 +348,10 @@ __device__ __forceinline__ float hurtbox_gap2(float dx, float dy, float ci, floa
 }
 
 template <int WAVES>
-__device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, const Place &P,
-                                         Unit &U, int &code_u, Carry &C)
+__device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, const float *zd,
+                                         const Place &P, Unit &U, int &code_u, Carry &C)
 {
+    float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
     const int N = a.p.num_units;
     const float dt = a.p.dt;
     const bool has = P.has;
@@ -381,7 +413,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
 
     // the position is final for this tick: fetch the terrain cell under it now, the zone
     // effects of stage 3 use it after the combat exchange
-    if (has && U.enabled) code_u = terrain_code(a, P.e, U.x, U.y);
+    if (has && U.enabled) code_u = zone_at(a, zd, P.e, U.x, U.y, zeff);
 
     // stage 2a: movement sets next tick's velocity, rotation turns the heading now
     float cu = 1.0f, su = 0.0f;
@@ -462,10 +494,11 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
         if (U.enabled) {
             const int zone = code_u & 3;
             if (alive0 && zone == TABX_ZONE_LAVA) {
-                const float h = U.hp - (a.p.lava_dps * dt);
+                const float h = U.hp - (zone_magnitude(a, zeff, a.p.lava_dps) * dt);
                 U.hp = h > 0.0f ? h : 0.0f;
             }
-            U.cur_speed = zone == TABX_ZONE_SWAMP ? U.speed * a.p.swamp_mult : U.speed;
+            U.cur_speed = zone == TABX_ZONE_SWAMP
+                              ? U.speed * zone_magnitude(a, zeff, a.p.swamp_mult) : U.speed;
             U.alive = U.hp > 0.0f ? 1 : 0;
             ratio = U.hp / U.hmax;
         } else {
@@ -518,7 +551,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
     lds_barrier<WAVES>();          // everyone has read the ratio terms of the finished tick
     if (any_done) {
         if (done) {
-            code_u = spawn_unit(a, P.e, P.k, U);
+            code_u = spawn_unit(a, zd, P.e, P.k, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
         }
@@ -838,9 +871,22 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
     }
     ZoneRegs Zr = {};
     if (DO_OBS) Zr = load_zone_regs<WAVES>(a, P);
+    // elliptical zones: the descriptors of the workgroup's envs sit in LDS for the lookups
+    const int zlen = 6 * a.p.max_zones;
+    float *zdesc = dyn_lds + a.zdesc_offset;
+    if (a.p.zone_shapes == 1) {
+        const int G = a.envs_per_block;
+        const size_t first = (size_t)P.grp * G * zlen;
+        const size_t total = (size_t)a.p.num_envs * zlen;
+        for (int q = P.l; q < G * zlen; q += 64 * WAVES)
+            zdesc[q] = (P.grp < a.num_groups && first + q < total) ? a.sc.zone_desc[first + q] : 0.0f;
+        lds_barrier<WAVES>();
+    }
+    const float *zd = zdesc + (P.has ? P.g : 0) * zlen;
     Carry C = {1.0f, 0.0f, 0.0f};
-    if (DO_STEP) step_env<WAVES>(a, sh, P, U, code_u, C);
-    else if (P.has) code_u = terrain_code(a, P.e, U.x, U.y);
+    float zeff_unused = 0.0f;
+    if (DO_STEP) step_env<WAVES>(a, sh, zd, P, U, code_u, C);
+    else if (P.has) code_u = zone_at(a, zd, P.e, U.x, U.y, zeff_unused);
     if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C, Zr);
 }
 
@@ -855,7 +901,8 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
     float ratio = 0.0f;
     if (go) {
         load_spec(a, P.k, U);
-        spawn_unit(a, P.e, P.k, U);
+        float zeff = 0.0f;
+        spawn_unit(a, a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones, P.e, P.k, U, zeff);
         ratio = U.enabled ? U.hp / U.hmax : 0.0f;
         store_state(a, P.k, U);
     }
@@ -893,7 +940,8 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
         load_state(a, tid, U);
         float4 q[4];
         if (U.enabled) {
-            const int code = terrain_code(a, e, U.x, U.y);
+            float zeff = 0.0f;
+            const int code = zone_at(a, a.sc.zone_desc + (size_t)e * zlen, e, U.x, U.y, zeff);
             q[0] = make_float4(U.hp, U.hp / U.hmax, U.x, U.y);
             q[1] = make_float4(U.theta, U.range, U.dmg, U.cd);
             q[2] = make_float4(U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f, U.radius, U.mass,
@@ -935,6 +983,8 @@ static int check_params(const TabxParams *p)
     if (p->grid_w < 0 || p->grid_h < 0 || ((p->grid_w == 0) != (p->grid_h == 0)))
         return TABX_ERR_SHAPE;
     if (p->max_steps < 1) return TABX_ERR_SHAPE;
+    if (p->zone_shapes != 0 && p->zone_shapes != 1) return TABX_ERR_SHAPE;
+    if (p->zone_shapes == 1 && (p->grid_w != 0 || p->max_zones < 1)) return TABX_ERR_SHAPE;
     if ((int64_t)p->num_envs * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     const float pos[] = {p->map_w, p->map_h, p->cell_size, p->dt};
     for (float v : pos)
@@ -981,7 +1031,7 @@ static int check_state(const TabxState *s)
 }
 
 template <int WAVES>
-static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
+static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
 {
     const dim3 grid((unsigned)(8 * a.groups_per_xcd)), block(64 * WAVES);
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
@@ -991,13 +1041,17 @@ static void launch_mode(Mode mode, const KArgs &a, hipStream_t stream)
     size_t dyn_floats = rows_staged * a.row_pitch;
     const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
     if (dyn_floats < pass_floats) dyn_floats = pass_floats;
-    const size_t dyn_bytes = dyn_floats * sizeof(float);
+    // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
+    const size_t zdesc_floats = a.p.zone_shapes == 1 ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
+    const size_t dyn_bytes = (dyn_floats + zdesc_floats) * sizeof(float);
+    const size_t step_bytes = zdesc_floats * sizeof(float);
+    a.zdesc_offset = mode == MODE_STEP ? 0 : (int)dyn_floats;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
         break;
     case MODE_STEP:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false>), grid, block, 0, stream, a);
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false>), grid, block, step_bytes, stream, a);
         break;
     case MODE_OBSERVE:
         hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true>), grid, block, dyn_bytes,

@@ -37,7 +37,7 @@ def _params(B, **kw):
     base = dict(num_envs=4, num_units=20, grid_w=0, grid_h=0, max_zones=8, max_steps=10,
                 map_w=8.0, map_h=8.0, cell_size=1.0, dt=0.25, turn_rate=1.0, lava_dps=1.0,
                 swamp_mult=0.5, reveal_time=1.0, boundary_frac=0.1, collision_alpha=0.0,
-                collision_slop=0.01)
+                collision_slop=0.01, zone_shapes=0)
     base.update(kw)
     return B.TabxParams(**base)
 
@@ -49,7 +49,8 @@ def test_obs_dim_and_shape_errors(B):
     assert lib.tabx_obs_dim(C.byref(_params(B, num_units=128, max_zones=0))) == 16 * 128
     assert lib.tabx_obs_dim(None) == -1
     for bad in (dict(num_units=0), dict(num_units=129), dict(max_zones=17), dict(max_zones=-1),
-                dict(num_envs=-1), dict(grid_w=4), dict(max_steps=0)):
+                dict(num_envs=-1), dict(grid_w=4), dict(max_steps=0), dict(zone_shapes=2),
+                dict(zone_shapes=1, max_zones=0), dict(zone_shapes=1, grid_w=4, grid_h=4)):
         assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -2, bad
     for bad in (dict(dt=0.0), dict(cell_size=-1.0), dict(map_w=float("nan")),
                 dict(lava_dps=float("inf"))):

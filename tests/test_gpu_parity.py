@@ -195,6 +195,17 @@ def test_rollout_with_body_collisions(name, E, steps, fused):
     assert dones > 0
 
 
+@pytest.mark.parametrize("team_size,zones,E", [(3, 4, 37), (10, 8, 40), (10, 16, 9), (40, 6, 3)])
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_rollout_with_elliptical_zones(team_size, zones, E, fused):
+    """Zones as ellipses with their own effect magnitudes instead of the cell grid."""
+    w = I.Workload(f"ell_{team_size}_{zones}", E, team_size, 40.0, 0, "ellipses", 1.0, "iid",
+                   max_zones=zones, steps=80, seed=600 + zones)
+    _say(f"[gpu] elliptical zones N={w.num_units} Z={zones} fused={fused}")
+    inexact, dones = _rollout(w, E, 80, fused, max_steps=30)
+    assert dones > 0
+
+
 def test_collisions_in_a_crowd_of_mixed_bodies():
     names = list(I.ROSTER)
     rng = np.random.default_rng(9)
