@@ -102,6 +102,11 @@ WORKLOADS = {
                                  "ratio", role_counts=(22, 21, 21), spawn="clusters",
                                  steps=500, seed=20260205),
 }
+# the headline shape with the paper's zone geometry (ellipses with their own effect magnitudes)
+# instead of the benchmark's cell grid; not one of the five benchmark configurations
+WORKLOADS["c3e_16384env_10v10_ellipses"] = Workload(
+    "c3e_16384env_10v10_ellipses", 16384, 10, 64.0, 0, "ellipses", 1.0, "ratio",
+    role_counts=(4, 3, 3), max_zones=8, steps=1000, seed=20260213)
 HEADLINE = "c3_16384env_10v10"
 
 
