@@ -53,6 +53,15 @@ class RefState(C.Structure):
                [(n, t) for n, t, _ in _METRICS]
 
 
+class RefPolicy(C.Structure):
+    _fields_ = [("epsilon", C.c_float), ("xi", C.c_float), ("assassin_speed", C.c_float),
+                ("ranger_range", C.c_float), ("seed", C.c_uint)]
+
+
+class RefPolicyMemory(C.Structure):
+    _fields_ = [("mem_x", _F), ("mem_y", _F), ("mem_valid", _B)]
+
+
 def build(force: bool = False) -> str:
     """Compiles the checker with g++ (no contraction, no fast-math)."""
     if force or not os.path.exists(_LIB) or \
@@ -75,6 +84,9 @@ def lib():
         _lib.tabx_ref_obs_dim.restype = C.c_int
         _lib.tabx_ref_sincos.argtypes = [C.c_float, _F, _F]
         _lib.tabx_ref_sincos_n.argtypes = [_F, C.c_int, _F, _F]
+        _lib.tabx_ref_hash.restype = C.c_uint
+        _lib.tabx_ref_hash.argtypes = [C.c_uint] * 5
+        _lib.tabx_ref_heuristic_actions.restype = None
         for fn in (_lib.tabx_ref_reset, _lib.tabx_ref_step, _lib.tabx_ref_observe,
                    _lib.tabx_ref_sincos, _lib.tabx_ref_sincos_n, _lib.tabx_ref_global_state):
             fn.restype = None
@@ -202,3 +214,20 @@ class RefEnv:
         lib().tabx_ref_global_state(C.byref(self.cp), C.byref(self.csc), C.byref(self.cst),
                                     _ptr(self.gstate, _F))
         return self.gstate
+
+    def heuristic_actions(self, policy: dict, controlled, actions):
+        """Fills `actions` (uint8 [E, N], in place) for the controlled, alive units."""
+        if not hasattr(self, "mem"):
+            self.mem = {"mem_x": np.zeros((self.E, self.N), np.float32),
+                        "mem_y": np.zeros((self.E, self.N), np.float32),
+                        "mem_valid": np.zeros((self.E, self.N), np.uint8)}
+            self.cmem = RefPolicyMemory(mem_x=_ptr(self.mem["mem_x"], _F),
+                                        mem_y=_ptr(self.mem["mem_y"], _F),
+                                        mem_valid=_ptr(self.mem["mem_valid"], _B))
+        pol = RefPolicy(**policy)
+        ctl = np.ascontiguousarray(controlled, np.uint8)
+        assert actions.dtype == np.uint8 and actions.flags["C_CONTIGUOUS"]
+        lib().tabx_ref_heuristic_actions(C.byref(self.cp), C.byref(self.csc), C.byref(self.cst),
+                                         C.byref(pol), C.byref(self.cmem), _ptr(ctl, _B),
+                                         _ptr(actions, _B))
+        return actions

@@ -428,6 +428,57 @@ void global_state_env(const RefParams &P, const RefScenario &S, const RefState &
     }
 }
 
+/* What unit i (alive, heading cosine / sine ci, si, zone code code_i) perceives of unit j
+ * (alive): the offset, whether j is visible to i (fan-shaped field of view and the bush
+ * rule) and whether i's combat action could reach j (hurtbox and role filter).  `margin`,
+ * if given, is lowered to the distance of the geometric tests from their boundaries. */
+struct PairView {
+    float dx, dy, d2;
+    bool visible, same_team, attackable;
+};
+
+PairView pair_view(const RefParams &P, const RefScenario &S, const RefState &st, int e, int i,
+                   int j, float ci, float si, int code_i, int code_j, double *margin)
+{
+    (void)P;
+    const int N = P.num_units, ki = e * N + i, kj = e * N + j;
+    PairView V;
+    V.dx = st.x[kj] - st.x[ki];
+    V.dy = st.y[kj] - st.y[ki];
+    V.d2 = (V.dx * V.dx) + (V.dy * V.dy);
+    float R = S.sight_range[ki];
+    bool in_range = V.d2 <= R * R;
+    float dot = (V.dx * ci) + (V.dy * si);
+    float dist = std::sqrt(V.d2);
+    bool in_cone = (V.d2 == 0.0f) || (dot >= S.sight_cos_half[ki] * dist);
+    if (margin) {
+        double m = std::fabs((double)dist - (double)R);
+        if (m < *margin) *margin = m;
+        if (dist > 0.0f) {
+            double cosang = (double)dot / (double)dist;
+            if (cosang > 1.0) cosang = 1.0;
+            if (cosang < -1.0) cosang = -1.0;
+            double half = std::acos((double)S.sight_cos_half[ki]);
+            m = std::fabs(std::acos(cosang) - half);
+            if (in_range && m < *margin) *margin = m;
+        }
+    }
+    V.same_team = S.team[ki] == S.team[kj];
+    bool bush_j = (code_j & 3) == ZONE_BUSH;
+    bool same_bush = bush_j && (code_i & 3) == ZONE_BUSH && code_i == code_j;
+    bool concealed = bush_j && !V.same_team && !same_bush && !(st.reveal[kj] > 0.0f);
+    V.visible = in_range && in_cone && !concealed;
+
+    float d2h;
+    double mh;
+    bool overlap = hurtbox_hit(st.x[ki], st.y[ki], ci, si, S.range[ki], S.hurt_halfwidth[ki],
+                               st.x[kj], st.y[kj], S.radius[kj], &d2h, margin ? &mh : nullptr);
+    bool allowed = role_allows(S.dmg[ki], S.team[ki], S.team[kj]);
+    if (margin && allowed && mh < *margin) *margin = mh;
+    V.attackable = overlap && allowed;
+    return V;
+}
+
 void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, int e,
                  float *obs, unsigned long long *vis_mask, unsigned char *action_mask,
                  double *min_margin)
@@ -464,40 +515,10 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
             slot += 1;
             if (!st.alive[ki] || !st.alive[kj]) continue;
 
-            float dx = st.x[kj] - st.x[ki];
-            float dy = st.y[kj] - st.y[ki];
-            float d2 = (dx * dx) + (dy * dy);
-            float R = S.sight_range[ki];
-            bool in_range = d2 <= R * R;
-            float dot = (dx * c[i]) + (dy * s[i]);
-            float dist = std::sqrt(d2);
-            bool in_cone = (d2 == 0.0f) || (dot >= S.sight_cos_half[ki] * dist);
-            if (min_margin) {
-                double m = std::fabs((double)dist - (double)R);
-                if (m < min_margin[e]) min_margin[e] = m;
-                if (dist > 0.0f) {
-                    double cosang = (double)dot / (double)dist;
-                    if (cosang > 1.0) cosang = 1.0;
-                    if (cosang < -1.0) cosang = -1.0;
-                    double half = std::acos((double)S.sight_cos_half[ki]);
-                    m = std::fabs(std::acos(cosang) - half);
-                    if (in_range && m < min_margin[e]) min_margin[e] = m;
-                }
-            }
-            bool same_team = S.team[ki] == S.team[kj];
-            bool bush_j = (code[j] & 3) == ZONE_BUSH;
-            bool same_bush = bush_j && (code[i] & 3) == ZONE_BUSH && code[i] == code[j];
-            bool concealed = bush_j && !same_team && !same_bush && !(st.reveal[kj] > 0.0f);
-            bool visible = in_range && in_cone && !concealed;
-
-            float d2h;
-            double mh;
-            bool overlap = hurtbox_hit(st.x[ki], st.y[ki], c[i], s[i], S.range[ki],
-                                       S.hurt_halfwidth[ki], st.x[kj], st.y[kj],
-                                       S.radius[kj], &d2h, min_margin ? &mh : nullptr);
-            bool allowed = role_allows(S.dmg[ki], S.team[ki], S.team[kj]);
-            if (min_margin && allowed && mh < min_margin[e]) min_margin[e] = mh;
-            bool attackable = overlap && allowed;
+            const PairView V = pair_view(P, S, st, e, i, j, c[i], s[i], code[i], code[j],
+                                         min_margin ? &min_margin[e] : nullptr);
+            const float dx = V.dx, dy = V.dy;
+            const bool visible = V.visible, same_team = V.same_team, attackable = V.attackable;
 
             if (!visible) continue;
             if (vis_mask) vis_mask[(long)ki * words + (j >> 6)] |= 1ull << (j & 63);
@@ -535,9 +556,200 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
     }
 }
 
+/* ---- heuristic opponent ---------------------------------------------------------------
+ * Counter-based random numbers: a 32-bit integer hash (two multiply / xor-shift rounds) of
+ * (seed, env, unit, tick, draw index); the same function is written out in the GPU library. */
+unsigned hash32(unsigned seed, unsigned env, unsigned unit, unsigned tick, unsigned draw)
+{
+    unsigned x = seed;
+    x ^= env * 0x9E3779B9u;
+    x ^= unit * 0x85EBCA6Bu;
+    x ^= tick * 0xC2B2AE35u;
+    x ^= draw * 0x27D4EB2Fu;
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+/* The cardinal move that closes most of the offset (gx, gy); idle if there is none. */
+int move_along(float gx, float gy)
+{
+    float ax = gx < 0.0f ? -gx : gx;
+    float ay = gy < 0.0f ? -gy : gy;
+    if (ax >= ay) return gx > 0.0f ? ACT_XP : (gx < 0.0f ? ACT_XM : ACT_NOOP);
+    return gy > 0.0f ? ACT_YP : ACT_YM;
+}
+
+/* One unit's decision, in the priority order of App. A "Role-Appropriate Heuristic Policy
+ * Mechanism": attack; rotate to bring the chosen target into the hurtbox; Rangers keep their
+ * distance; navigate to the role's position at the target; pursue the last known position;
+ * search (Rangers head for a bush first).  An epsilon-greedy override comes last. */
+int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
+                const RefPolicy &pol, RefPolicyMemory &mem, int e, int i,
+                const std::vector<float> &c, const std::vector<float> &s,
+                const std::vector<int> &code)
+{
+    const int N = P.num_units, b = e * N, ki = b + i;
+    const bool healer = S.dmg[ki] < 0.0f;
+    const bool assassin = S.speed[ki] >= pol.assassin_speed;
+    const bool ranger = S.range[ki] >= pol.ranger_range;
+
+    /* target selection among the visible units; nearest visible enemy; anything in reach */
+    int tgt = -1, near_enemy = -1;
+    float tgt_d2 = 0.0f, tgt_h = 0.0f, near_d2 = 0.0f;
+    bool tgt_injured = false, can_hit = false, tgt_in_box = false;
+    for (int j = 0; j < N; ++j) {
+        if (j == i || !st.alive[b + j]) continue;
+        const PairView V = pair_view(P, S, st, e, i, j, c[i], s[i], code[i], code[j], nullptr);
+        if (!V.visible) continue;
+        /* the combat action is worth taking: an enemy in the hurtbox, or for a healer an
+         * ally there that is below its maximum health */
+        if (V.attackable && (!healer || st.hp[b + j] < S.hmax[b + j])) can_hit = true;
+        if (!V.same_team && (near_enemy < 0 || V.d2 < near_d2)) {
+            near_enemy = j;
+            near_d2 = V.d2;
+        }
+        bool better = false;
+        if (healer) {          /* nearest injured ally, else nearest ally */
+            if (V.same_team) {
+                const bool injured = st.hp[b + j] < S.hmax[b + j];
+                better = tgt < 0 || (injured && !tgt_injured) ||
+                         (injured == tgt_injured && V.d2 < tgt_d2);
+                if (better) tgt_injured = injured;
+            }
+        } else if (assassin) { /* lowest maximum health, then nearest */
+            if (!V.same_team)
+                better = tgt < 0 || S.hmax[b + j] < tgt_h ||
+                         (S.hmax[b + j] == tgt_h && V.d2 < tgt_d2);
+        } else {               /* nearest enemy */
+            if (!V.same_team) better = tgt < 0 || V.d2 < tgt_d2;
+        }
+        if (better) {
+            tgt = j;
+            tgt_d2 = V.d2;
+            tgt_h = S.hmax[b + j];
+            tgt_in_box = V.attackable;
+        }
+    }
+
+    const unsigned tick = (unsigned)st.t[e];
+    const unsigned coin = hash32(pol.seed, (unsigned)e, (unsigned)i, tick, 2u) & 1u;
+    const int search_turn = coin ? ACT_ROT_L : ACT_ROT_R;
+    int act = ACT_NOOP;
+    if (tgt >= 0) {
+        const int kt = b + tgt;
+        mem.mem_x[ki] = st.x[kt];
+        mem.mem_y[ki] = st.y[kt];
+        mem.mem_valid[ki] = 1;
+        const float tdx = st.x[kt] - st.x[ki];
+        const float tdy = st.y[kt] - st.y[ki];
+        const float reach = S.range[ki] + S.radius[kt];
+        const bool within = tgt_d2 <= reach * reach;
+        const float kite = pol.xi * S.range[ki];
+        if (can_hit && st.cd[ki] <= 0.0f) {
+            act = ACT_ATTACK;
+        } else if (within && !tgt_in_box) {
+            /* turn towards the side the target is on */
+            const float lx = (tdx * c[i]) + (tdy * s[i]);
+            const float ly = (tdy * c[i]) - (tdx * s[i]);
+            act = ly > 0.0f ? ACT_ROT_L : (ly < 0.0f ? ACT_ROT_R : (lx < 0.0f ? ACT_ROT_L : ACT_NOOP));
+        } else if (ranger && near_enemy >= 0 && near_d2 < kite * kite) {
+            act = move_along(st.x[ki] - st.x[b + near_enemy], st.y[ki] - st.y[b + near_enemy]);
+        } else if (tgt_in_box) {
+            act = ACT_NOOP;            /* aligned, waiting for the cooldown */
+        } else {
+            /* Assassins go behind the target, Healers to it, the rest in front of it */
+            float ct, st_;
+            sincos_spec(st.theta[kt], &st_, &ct);
+            const float standoff = 0.5f * S.range[ki];
+            float gx = st.x[kt], gy = st.y[kt];
+            if (!healer) {
+                if (assassin) {
+                    gx = gx - (ct * standoff);
+                    gy = gy - (st_ * standoff);
+                } else {
+                    gx = gx + (ct * standoff);
+                    gy = gy + (st_ * standoff);
+                }
+            }
+            act = move_along(gx - st.x[ki], gy - st.y[ki]);
+        }
+    } else if (mem.mem_valid[ki]) {
+        const float gx = mem.mem_x[ki] - st.x[ki];
+        const float gy = mem.mem_y[ki] - st.y[ki];
+        if ((gx * gx) + (gy * gy) <= 1.0f) {
+            mem.mem_valid[ki] = 0;
+            act = search_turn;
+        } else {
+            act = move_along(gx, gy);
+        }
+    } else {
+        /* Rangers outside a bush walk to the nearest bush zone they know of, then search */
+        int bush = -1;
+        float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
+        if (ranger && (code[i] & 3) != ZONE_BUSH && S.zone_desc) {
+            for (int z = 0; z < P.max_zones; ++z) {
+                const float *d = S.zone_desc + ((long)e * P.max_zones + z) * 6;
+                if ((int)d[0] != ZONE_BUSH) continue;
+                const float zx = d[1] - st.x[ki];
+                const float zy = d[2] - st.y[ki];
+                const float d2 = (zx * zx) + (zy * zy);
+                if (bush < 0 || d2 < bush_d2) {
+                    bush = z;
+                    bush_d2 = d2;
+                    bx = zx;
+                    by = zy;
+                }
+            }
+        }
+        act = bush >= 0 ? move_along(bx, by) : search_turn;
+    }
+
+    /* epsilon-greedy override */
+    const unsigned h0 = hash32(pol.seed, (unsigned)e, (unsigned)i, tick, 0u);
+    const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
+    if (u0 < pol.epsilon) act = (int)(hash32(pol.seed, (unsigned)e, (unsigned)i, tick, 1u) & 7u);
+    return act;
+}
+
+void policy_env(const RefParams &P, const RefScenario &S, const RefState &st,
+                const RefPolicy &pol, RefPolicyMemory &mem, int e,
+                const unsigned char *controlled, unsigned char *actions)
+{
+    const int N = P.num_units, b = e * N;
+    std::vector<float> c(N), s(N);
+    std::vector<int> code(N);
+    for (int u = 0; u < N; ++u) {
+        sincos_spec(st.theta[b + u], &s[u], &c[u]);
+        code[u] = cell_code(P, S, e, st.x[b + u], st.y[b + u]);
+    }
+    for (int i = 0; i < N; ++i) {
+        const int ki = b + i;
+        if (!controlled[ki] || !S.enabled[ki] || !st.alive[ki]) continue;
+        actions[ki] = (unsigned char)policy_unit(P, S, st, pol, mem, e, i, c, s, code);
+    }
+}
+
 } /* namespace */
 
 extern "C" {
+
+unsigned tabx_ref_hash(unsigned seed, unsigned env, unsigned unit, unsigned tick, unsigned draw)
+{
+    return hash32(seed, env, unit, tick, draw);
+}
+
+void tabx_ref_heuristic_actions(const RefParams *p, const RefScenario *sc, const RefState *st,
+                                const RefPolicy *pol, RefPolicyMemory *mem,
+                                const unsigned char *controlled, unsigned char *actions)
+{
+    for (int e = 0; e < p->num_envs; ++e)
+        policy_env(*p, *sc, *st, *pol, *mem, e, controlled, actions);
+}
+
 
 int tabx_ref_obs_dim(const RefParams *p)
 {

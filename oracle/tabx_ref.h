@@ -92,6 +92,28 @@ void tabx_ref_observe(const RefParams *p, const RefScenario *sc, const RefState 
                       float *obs, unsigned long long *vis_mask,
                       unsigned char *action_mask, double *min_margin);
 
+/* Role-appropriate heuristic policy (Sec. 4.2, App. A "Role-Appropriate Heuristic Policy
+ * Mechanism", table "Heuristic policy parameters"). */
+typedef struct RefPolicy {
+    float epsilon;          /* probability of a uniformly random action instead of the intended one */
+    float xi;               /* Rangers retreat from enemies closer than xi * attack range          */
+    float assassin_speed;   /* speed >= this: Assassin class (1.4 in every tier of the table)      */
+    float ranger_range;     /* attack range >= this: Ranger class (10.0)                           */
+    unsigned seed;          /* of the counter-based random numbers                                 */
+} RefPolicy;
+
+typedef struct RefPolicyMemory {   /* last known target position per unit, [E*N] */
+    float *mem_x, *mem_y;
+    unsigned char *mem_valid;
+} RefPolicyMemory;
+
+/* Writes actions[e*N+u] for every unit with controlled[e*N+u] != 0 that is enabled and alive;
+ * other entries are left alone. */
+void tabx_ref_heuristic_actions(const RefParams *p, const RefScenario *sc, const RefState *st,
+                                const RefPolicy *pol, RefPolicyMemory *mem,
+                                const unsigned char *controlled, unsigned char *actions);
+unsigned tabx_ref_hash(unsigned seed, unsigned env, unsigned unit, unsigned tick, unsigned draw);
+
 /* Global state (App. A "Global state"): out [E][16 * N + 6 * Z]: every unit's own block
  * (as in its observation row, absolute position, zero if disabled), then the zone slots
  * with absolute centres (zero for type 0).  No visibility masking. */

@@ -57,6 +57,21 @@ DEFAULTS = dict(
     collision_slop=0.01,
 )
 
+# Paper data: App. A table "Heuristic policy parameters across all difficulty tier":
+# stochasticity of action (epsilon), aggressive threshold (xi), Assassin speed, Ranger range.
+POLICY_TIERS = {
+    "random":   dict(epsilon=1.0,  xi=0.0, assassin_speed=1.4, ranger_range=10.0),
+    "novice":   dict(epsilon=0.5,  xi=0.1, assassin_speed=1.4, ranger_range=10.0),
+    "medium":   dict(epsilon=0.2,  xi=0.3, assassin_speed=1.4, ranger_range=10.0),
+    "advanced": dict(epsilon=0.1,  xi=0.5, assassin_speed=1.4, ranger_range=10.0),
+    "expert":   dict(epsilon=0.01, xi=0.7, assassin_speed=1.4, ranger_range=10.0),
+}
+
+
+def policy(tier: str, seed: int = 1) -> dict:
+    return dict(POLICY_TIERS[tier], seed=int(seed))
+
+
 FLOAT_UNIT_FIELDS = (
     "init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",
     "range", "cooldown", "sight_angle", "sight_cos_half", "sight_range",
