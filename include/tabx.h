@@ -181,6 +181,54 @@ int tabx_step_observe(const TabxParams *params, const TabxScenario *scenario,
 int tabx_global_state(const TabxParams *params, const TabxScenario *scenario,
                       const TabxState *state, float *out, void *stream);
 
+/* Role-appropriate heuristic policy for scripted units (Sec. 4.2; App. A "Role-Appropriate
+ * Heuristic Policy Mechanism"; tier values in the table "Heuristic policy parameters across
+ * all difficulty tier": epsilon / xi = 1.0/0.0 random, 0.5/0.1 novice, 0.2/0.3 medium,
+ * 0.1/0.5 advanced, 0.01/0.7 expert; Assassin speed 1.4, Ranger range 10.0 in all of them). */
+typedef struct TabxPolicy {
+    float    epsilon;          /* probability of a uniformly random action                  */
+    float    xi;               /* Rangers retreat from enemies nearer than xi * attack range */
+    float    assassin_speed;   /* speed >= this: Assassin                                   */
+    float    ranger_range;     /* attack range >= this: Ranger                              */
+    uint32_t seed;             /* of the counter-based random numbers                       */
+} TabxPolicy;
+
+/* Last known target position per unit, device [E * N]; the caller zeroes mem_valid when an
+ * episode of that env starts (or leaves stale memories in, as it prefers). */
+typedef struct TabxPolicyMemory {
+    float   *mem_x, *mem_y;
+    uint8_t *mem_valid;
+} TabxPolicyMemory;
+
+/* Chooses actions[e * N + u] for every enabled, living unit with controlled[e * N + u] != 0
+ * (controlled == NULL: all of them) from the current state; other entries of `actions` are
+ * not written.  Roles: Healer = negative damage, Assassin and Ranger by the two thresholds;
+ * a unit can have several.  Of the units it sees (field of view and bush rule of
+ * tabx_observe) a Healer selects the nearest injured ally, else the nearest ally; an Assassin
+ * the enemy of lowest maximum health, nearer first among equals; any other unit the nearest
+ * enemy; remaining ties go to the lower index.  Then, first rule that applies:
+ *   1. combat action, if the cooldown has elapsed and a visible unit it may strike is in the
+ *      hurtbox (for a Healer: an ally below maximum health);
+ *   2. rotate towards the target's side if it is within range + its body radius of the unit
+ *      but not in the hurtbox;
+ *   3. Ranger: step away (along the larger axis of the offset) from the nearest visible enemy
+ *      if it is nearer than xi * range;
+ *   4. idle if the target is in the hurtbox (waiting for the cooldown);
+ *   5. move along the larger axis of the offset to the role's goal: behind the target by half
+ *      the own range (Assassin), the target itself (Healer), in front of it by half the range
+ *      (others); the target's position is remembered;
+ *   6. no target: move to the remembered position; within distance 1 of it, forget it and
+ *      search;
+ *   7. nothing remembered: a Ranger outside bushes moves to the nearest bush-type zone slot
+ *      centre; otherwise search = rotate left or right by a random bit.
+ * Finally with probability epsilon the action is replaced by one uniform over all eight.
+ * Random numbers are a 32-bit hash of (seed, env, unit, tick t, draw index): reproducible and
+ * independent of launch shape.  Same stream rules and errors as the other calls. */
+int tabx_heuristic_actions(const TabxParams *params, const TabxScenario *scenario,
+                           const TabxState *state, const TabxPolicy *policy,
+                           const TabxPolicyMemory *memory, const uint8_t *controlled,
+                           uint8_t *actions, void *stream);
+
 const char *tabx_strerror(int code);
 
 #ifdef __cplusplus

@@ -24,7 +24,7 @@ SCENARIO_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "s
 STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
 
 EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
-           "tabx_step_observe", "tabx_global_state", "tabx_strerror")
+           "tabx_step_observe", "tabx_global_state", "tabx_heuristic_actions", "tabx_strerror")
 
 _I8 = C.POINTER(C.c_int8)
 _I32 = C.POINTER(C.c_int32)
@@ -59,6 +59,15 @@ class TabxError(RuntimeError):
     pass
 
 
+class TabxPolicy(C.Structure):
+    _fields_ = [("epsilon", C.c_float), ("xi", C.c_float), ("assassin_speed", C.c_float),
+                ("ranger_range", C.c_float), ("seed", C.c_uint32)]
+
+
+class TabxPolicyMemory(C.Structure):
+    _fields_ = [("mem_x", _F), ("mem_y", _F), ("mem_valid", _U8)]
+
+
 def load_library(path: str = LIB_PATH) -> C.CDLL:
     if not os.path.exists(path):
         raise ImportError(
@@ -73,6 +82,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.tabx_observe.argtypes = [P, S, T, V, V, V, V]
     lib.tabx_step_observe.argtypes = [P, S, T, V, V, V, V, V, V, V]
     lib.tabx_global_state.argtypes = [P, S, T, V, V]
+    lib.tabx_heuristic_actions.argtypes = [P, S, T, C.POINTER(TabxPolicy),
+                                           C.POINTER(TabxPolicyMemory), V, V, V]
     lib.tabx_strerror.argtypes = [C.c_int]
     lib.tabx_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -146,6 +157,14 @@ def tabx_global_state(params, scenario, state, out, stream=None):
                                   _stream_ptr(stream)), "tabx_global_state")
 
 
+def tabx_heuristic_actions(params, scenario, state, policy, memory, controlled, actions,
+                           stream=None):
+    _check(_lib.tabx_heuristic_actions(C.byref(params), C.byref(scenario), C.byref(state),
+                                       C.byref(policy), C.byref(memory), _ptr(controlled),
+                                       _ptr(actions), _stream_ptr(stream)),
+           "tabx_heuristic_actions")
+
+
 class TabxEnv:
     """Device buffers of one batch of environments plus the calls on them."""
 
@@ -185,6 +204,7 @@ class TabxEnv:
             self.metrics = {n: torch.zeros(E, dtype=dt, device=dev) for n, _, dt in METRICS}
         self.state = self._state_struct(self.st, self.metrics)
         self.gstate = None
+        self.memory = None
 
         self.rewards = torch.zeros(E, N, dtype=torch.float32, device=dev)
         self.dones = torch.zeros(E, dtype=torch.uint8, device=dev)
@@ -208,6 +228,20 @@ class TabxEnv:
                                       dtype=torch.float32, device=self.device)
         tabx_global_state(self.params, self.scenario, self.state, self.gstate, stream)
         return self.gstate
+
+    def heuristic_actions(self, policy: dict, controlled, actions, stream=None):
+        """Fills `actions` (uint8 [E, N] on the device, in place) for the controlled units."""
+        if self.memory is None:
+            n = self.E * self.N
+            self.mem = {"mem_x": torch.zeros(n, dtype=torch.float32, device=self.device),
+                        "mem_y": torch.zeros(n, dtype=torch.float32, device=self.device),
+                        "mem_valid": torch.zeros(n, dtype=torch.uint8, device=self.device)}
+            self.memory = TabxPolicyMemory(mem_x=_cast(self.mem["mem_x"], _F),
+                                           mem_y=_cast(self.mem["mem_y"], _F),
+                                           mem_valid=_cast(self.mem["mem_valid"], _U8))
+        tabx_heuristic_actions(self.params, self.scenario, self.state, TabxPolicy(**policy),
+                               self.memory, controlled, actions, stream)
+        return actions
 
     def reset(self, env_mask=None, stream=None):
         tabx_reset(self.params, self.scenario, self.state, env_mask, stream)

@@ -969,6 +969,216 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
     }
 }
 
+// ------------------------------------------------------------------ heuristic policy
+//
+// Role-appropriate heuristic policy (Sec. 4.2; App. A "Role-Appropriate Heuristic Policy
+// Mechanism" and the table of tier parameters).  Lane = deciding unit; the units of its env
+// are scanned through records in LDS.  Visibility and reach are the tests of the observation
+// (fan-shaped field of view, bush rule, hurtbox, role filter), from the observer's side.
+
+struct PolicyArgs {
+    TabxPolicy       pol;
+    TabxPolicyMemory mem;
+    const uint8_t   *controlled;
+    uint8_t         *actions_out;
+};
+
+template <int WAVES>
+struct PolicyShared {
+    static constexpr int L = 64 * WAVES;
+    float4 pose[L];       // x, y, cos(theta), sin(theta)
+    float4 body[L];       // radius, max health, health, -
+    int    flags[L];      // alive | team<<1 | concealable<<2 | bush key<<8
+};
+
+// Counter-based random numbers: two multiply / xor-shift rounds over the draw's coordinates.
+__device__ __forceinline__ uint32_t policy_hash(uint32_t seed, uint32_t env, uint32_t unit,
+                                                uint32_t tick, uint32_t draw)
+{
+    uint32_t x = seed;
+    x ^= env * 0x9E3779B9u;
+    x ^= unit * 0x85EBCA6Bu;
+    x ^= tick * 0xC2B2AE35u;
+    x ^= draw * 0x27D4EB2Fu;
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// The cardinal move that closes most of the offset (gx, gy); idle if there is none.
+__device__ __forceinline__ int move_along(float gx, float gy)
+{
+    const float ax = __builtin_fabsf(gx), ay = __builtin_fabsf(gy);
+    if (ax >= ay) return gx > 0.0f ? TABX_ACT_MOVE_XP : (gx < 0.0f ? TABX_ACT_MOVE_XM : TABX_ACT_NOOP);
+    return gy > 0.0f ? TABX_ACT_MOVE_YP : TABX_ACT_MOVE_YM;
+}
+
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void tabx_policy_kernel(const KArgs a, const PolicyArgs pa)
+{
+    __shared__ PolicyShared<WAVES> sh;
+    const Place P = locate<WAVES>(a);
+    const int N = a.p.num_units;
+    Unit U = {};
+    int code_u = 0;
+    float cu = 1.0f, su = 0.0f;
+    if (P.has) {
+        load_spec(a, P.k, U);
+        load_state(a, P.k, U);
+        float zeff = 0.0f;
+        code_u = zone_at(a, a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones, P.e, U.x, U.y, zeff);
+        heading_sincos(U.theta, su, cu);
+    }
+    const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
+    const int my_key = in_bush ? (code_u & 0xff) : 0x100;          // 0x100 matches no cell code
+    const bool concealable = in_bush && !(U.reveal > 0.0f);
+    sh.pose[P.l] = make_float4(U.x, U.y, cu, su);
+    sh.body[P.l] = make_float4(U.radius, U.hmax, U.hp, 0.0f);
+    sh.flags[P.l] = (P.has ? U.alive : 0) | (U.team << 1) | (concealable ? 4 : 0) | (my_key << 8);
+    lds_barrier<WAVES>();
+
+    const bool decide = P.has && U.enabled && U.alive && (!pa.controlled || pa.controlled[P.k]);
+    if (!decide) return;
+
+    const bool healer = U.dmg < 0.0f;
+    const bool assassin = U.speed >= pa.pol.assassin_speed;
+    const bool ranger = U.range >= pa.pol.ranger_range;
+    const float sight2 = U.sight_range * U.sight_range;
+    const float neg_hw = -U.hurt_hw;
+
+    // target selection among the visible units; nearest visible enemy; anything worth a strike
+    int tgt = -1, near_enemy = -1;
+    float tgt_d2 = 0.0f, tgt_h = 0.0f, near_d2 = 0.0f, near_dx = 0.0f, near_dy = 0.0f;
+    bool tgt_injured = false, can_hit = false, tgt_in_box = false;
+    for (int j = 0; j < N; ++j) {
+        const int fj = sh.flags[P.base + j];
+        if (j == P.u || !(fj & 1)) continue;
+        const float4 A = sh.pose[P.base + j];
+        const float4 B = sh.body[P.base + j];
+        const float dx = A.x - U.x;
+        const float dy = A.y - U.y;
+        float dot;
+        const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, dot);
+        const float d2 = (dx * dx) + (dy * dy);
+        const bool in_range = d2 <= sight2;
+        const bool in_cone = (d2 == 0.0f) || (dot >= U.cos_half * __builtin_sqrtf(d2));
+        const bool same_team = ((fj >> 1) & 1) == U.team;
+        const bool same_bush = (fj >> 8) == my_key;
+        const bool concealed = (fj & 4) && !same_team && !same_bush;
+        if (!(in_range && in_cone && !concealed)) continue;
+        const bool attackable = (healer == same_team) && (g2 <= B.x * B.x);
+        const bool injured = B.z < B.y;
+        if (attackable && (!healer || injured)) can_hit = true;
+        if (!same_team && (near_enemy < 0 || d2 < near_d2)) {
+            near_enemy = j;
+            near_d2 = d2;
+            near_dx = dx;
+            near_dy = dy;
+        }
+        bool better = false;
+        if (healer) {                // nearest injured ally, else nearest ally
+            if (same_team) {
+                better = tgt < 0 || (injured && !tgt_injured) || (injured == tgt_injured && d2 < tgt_d2);
+                if (better) tgt_injured = injured;
+            }
+        } else if (assassin) {       // lowest maximum health, then nearest
+            if (!same_team) better = tgt < 0 || B.y < tgt_h || (B.y == tgt_h && d2 < tgt_d2);
+        } else {                     // nearest enemy
+            if (!same_team) better = tgt < 0 || d2 < tgt_d2;
+        }
+        if (better) {
+            tgt = j;
+            tgt_d2 = d2;
+            tgt_h = B.y;
+            tgt_in_box = attackable;
+        }
+    }
+
+    const uint32_t tick = (uint32_t)a.st.t[P.e];
+    const uint32_t coin = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 2u) & 1u;
+    const int search_turn = coin ? TABX_ACT_ROT_LEFT : TABX_ACT_ROT_RIGHT;
+    int act = TABX_ACT_NOOP;
+    if (tgt >= 0) {
+        const float4 T = sh.pose[P.base + tgt];
+        const float tr = sh.body[P.base + tgt].x;
+        pa.mem.mem_x[P.k] = T.x;
+        pa.mem.mem_y[P.k] = T.y;
+        pa.mem.mem_valid[P.k] = 1;
+        const float tdx = T.x - U.x;
+        const float tdy = T.y - U.y;
+        const float reach = U.range + tr;
+        const bool within = tgt_d2 <= reach * reach;
+        const float kite = pa.pol.xi * U.range;
+        if (can_hit && U.cd <= 0.0f) {
+            act = TABX_ACT_ATTACK;
+        } else if (within && !tgt_in_box) {
+            // turn towards the side the target is on
+            const float lx = (tdx * cu) + (tdy * su);
+            const float ly = (tdy * cu) - (tdx * su);
+            act = ly > 0.0f ? TABX_ACT_ROT_LEFT
+                            : (ly < 0.0f ? TABX_ACT_ROT_RIGHT : (lx < 0.0f ? TABX_ACT_ROT_LEFT : TABX_ACT_NOOP));
+        } else if (ranger && near_enemy >= 0 && near_d2 < kite * kite) {
+            act = move_along(-near_dx, -near_dy);
+        } else if (tgt_in_box) {
+            act = TABX_ACT_NOOP;     // aligned, waiting for the cooldown
+        } else {
+            // Assassins go behind the target, Healers to it, the rest in front of it
+            const float standoff = 0.5f * U.range;
+            float gx = T.x, gy = T.y;
+            if (!healer) {
+                if (assassin) {
+                    gx = gx - (T.z * standoff);
+                    gy = gy - (T.w * standoff);
+                } else {
+                    gx = gx + (T.z * standoff);
+                    gy = gy + (T.w * standoff);
+                }
+            }
+            act = move_along(gx - U.x, gy - U.y);
+        }
+    } else if (pa.mem.mem_valid[P.k]) {
+        const float gx = pa.mem.mem_x[P.k] - U.x;
+        const float gy = pa.mem.mem_y[P.k] - U.y;
+        if ((gx * gx) + (gy * gy) <= 1.0f) {
+            pa.mem.mem_valid[P.k] = 0;
+            act = search_turn;
+        } else {
+            act = move_along(gx, gy);
+        }
+    } else {
+        // Rangers outside a bush walk to the nearest bush zone they know of, then search
+        int bush = -1;
+        float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
+        if (ranger && !in_bush && a.sc.zone_desc) {
+            const float *zd = a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones;
+            for (int z = 0; z < a.p.max_zones; ++z) {
+                const float *d = zd + 6 * z;
+                if ((int)d[0] != TABX_ZONE_BUSH) continue;
+                const float zx = d[1] - U.x;
+                const float zy = d[2] - U.y;
+                const float d2 = (zx * zx) + (zy * zy);
+                if (bush < 0 || d2 < bush_d2) {
+                    bush = z;
+                    bush_d2 = d2;
+                    bx = zx;
+                    by = zy;
+                }
+            }
+        }
+        act = bush >= 0 ? move_along(bx, by) : search_turn;
+    }
+
+    // epsilon-greedy override
+    const uint32_t h0 = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 0u);
+    const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
+    if (u0 < pa.pol.epsilon)
+        act = (int)(policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 1u) & 7u);
+    pa.actions_out[P.k] = (uint8_t)act;
+}
+
 // ------------------------------------------------------------------ host side
 
 enum Mode { MODE_RESET, MODE_STEP, MODE_OBSERVE, MODE_STEP_OBSERVE };
@@ -1205,6 +1415,50 @@ int tabx_global_state(const TabxParams *p, const TabxScenario *sc, const TabxSta
     (void)hipGetLastError();
     hipLaunchKernelGGL(tabx::tabx_global_state_kernel, dim3((unsigned)((threads + 255) / 256)),
                        dim3(256), 0, (hipStream_t)stream, a, out);
+    return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
+}
+
+int tabx_heuristic_actions(const TabxParams *p, const TabxScenario *sc, const TabxState *st,
+                           const TabxPolicy *policy, const TabxPolicyMemory *memory,
+                           const uint8_t *controlled, uint8_t *actions, void *stream)
+{
+    int rc = tabx::check_params(p);
+    if (rc) return rc;
+    if (p->num_envs == 0) return TABX_OK;
+    if ((rc = tabx::check_scenario(p, sc))) return rc;
+    if ((rc = tabx::check_state(st))) return rc;
+    if (!policy || !memory || !actions) return TABX_ERR_NULL;
+    if (!memory->mem_x || !memory->mem_y || !memory->mem_valid) return TABX_ERR_NULL;
+    if (!tabx::aligned(memory->mem_x, 4) || !tabx::aligned(memory->mem_y, 4)) return TABX_ERR_ALIGN;
+    const float fin[] = {policy->epsilon, policy->xi, policy->assassin_speed, policy->ranger_range};
+    for (float v : fin)
+        if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
+    tabx::KArgs a = {};
+    a.p = *p;
+    a.sc = *sc;
+    a.st = *st;
+    {
+        int ex = 0;
+        const float mant = frexpf(p->cell_size, &ex);
+        a.cell_pow2 = (mant == 0.5f && ex > -100 && ex < 100) ? 1 : 0;
+        a.inv_cell = 1.0f / p->cell_size;
+    }
+    const int N = p->num_units;
+    const int waves = N <= 64 ? 1 : 2;
+    a.envs_per_block = waves == 1 ? 64 / N : 1;
+    a.num_groups = (p->num_envs + a.envs_per_block - 1) / a.envs_per_block;
+    a.groups_per_xcd = (a.num_groups + 7) / 8;
+    tabx::PolicyArgs pa;
+    pa.pol = *policy;
+    pa.mem = *memory;
+    pa.controlled = controlled;
+    pa.actions_out = actions;
+    const dim3 grid((unsigned)(8 * a.groups_per_xcd)), block(64 * waves);
+    (void)hipGetLastError();
+    if (waves == 1)
+        hipLaunchKernelGGL((tabx::tabx_policy_kernel<1>), grid, block, 0, (hipStream_t)stream, a, pa);
+    else
+        hipLaunchKernelGGL((tabx::tabx_policy_kernel<2>), grid, block, 0, (hipStream_t)stream, a, pa);
     return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
 }
 

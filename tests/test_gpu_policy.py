@@ -1,0 +1,161 @@
+"""Heuristic policy: HIP library vs CPU checker through the C ABI (needs an MI355X).
+
+Actions and the memory-valid flags are bit-exact, remembered positions equal as floats;
+the rollouts feed each side its own actions, so a single differing action would also show
+as a state mismatch on the following tick.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2602_01665_amd import inputs as I
+from tests.parity import compare_state
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _policy_rollout(w, E, steps, tier, who, scenario=None, seed=5, **override):
+    """who: "adversaries" (allies act at random), "both", or "allies"."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    p = I.make_params(w, E, **override)
+    sc = I.make_scenario(w, E) if scenario is None else scenario
+    N = p["num_units"]
+    ref = RefEnv(p, sc)
+    gpu = TabxEnv(p, sc, want_metrics=True)
+    ref.reset()
+    gpu.reset()
+    team = np.asarray(sc["team"]).reshape(E, N)
+    ctl = {"adversaries": team == 1, "allies": team == 0,
+           "both": np.ones_like(team, bool)}[who].astype(np.uint8)
+    ctl_d = None if who == "both" else torch.from_numpy(ctl).to(gpu.device)
+    pol = I.policy(tier, seed)
+    hist = np.zeros(8, np.int64)
+    dones = 0
+    for s in range(steps):
+        a = I.actions_for_step(w.seed, s, E, N)
+        ad = torch.from_numpy(a).to(gpu.device)
+        ref.heuristic_actions(pol, ctl, a)
+        gpu.heuristic_actions(pol, ctl_d, ad)
+        torch.cuda.synchronize()
+        where = f"{w.name} E={E} {tier}/{who} step {s}: "
+        got = ad.cpu().numpy()
+        bad = np.argwhere(got != a)
+        assert bad.size == 0, where + f"actions differ at {bad[:5].tolist()}: " \
+            f"{got[tuple(bad[0])]} vs {a[tuple(bad[0])]}"
+        valid = gpu.mem["mem_valid"].cpu().numpy().reshape(E, N)
+        assert np.array_equal(valid, ref.mem["mem_valid"]), where + "mem_valid"
+        for k in ("mem_x", "mem_y"):
+            g = gpu.mem[k].cpu().numpy().reshape(E, N)
+            assert np.array_equal(g[valid == 1], ref.mem[k][valid == 1]), where + k
+        hist += np.bincount(a[ctl == 1], minlength=8)
+        ref.step(a)
+        gpu.step(ad)
+        torch.cuda.synchronize()
+        compare_state(gpu.state_numpy(), ref.st, where)
+        assert np.array_equal(gpu.dones.cpu().numpy(), ref.dones), where + "dones"
+        done = ref.dones.astype(bool)
+        if done.any():                       # a new episode starts with an empty memory
+            ref.mem["mem_valid"][done] = 0
+            gpu.mem["mem_valid"].view(E, N)[torch.from_numpy(done).to(gpu.device)] = 0
+            dones += int(done.sum())
+    return hist, dones
+
+
+TIERS = ["random", "novice", "medium", "advanced", "expert"]
+
+
+@pytest.mark.parametrize("tier", TIERS)
+def test_adversaries_under_every_tier(tier):
+    _say(f"[gpu] policy c3 subset, adversaries, tier {tier}")
+    hist, dones = _policy_rollout(I.WORKLOADS["c3_16384env_10v10"], 48, 120, tier, "adversaries",
+                                  max_steps=96)
+    _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
+    assert hist.sum() > 0
+
+
+@pytest.mark.parametrize("name,E,steps,over", [
+    ("c1_16env_3v3", 16, 256, dict()),
+    ("c2_4096env_5v5", 200, 200, dict(max_steps=128)),
+    ("c3_16384env_10v10", 70, 200, dict(max_steps=128)),
+    ("c3e_16384env_10v10_ellipses", 70, 200, dict(max_steps=128)),
+    ("c5_1024env_64v64", 3, 80, dict(max_steps=60)),
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_self_play_rollouts(name, E, steps, over):
+    _say(f"[gpu] policy self-play {name} E={E} steps={steps}")
+    hist, dones = _policy_rollout(I.WORKLOADS[name], E, steps, "expert", "both", **over)
+    _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
+    # seek-and-approach, combat, turning and search all occur
+    assert hist[5] > 0 and hist[1:5].sum() > 0 and hist[6:].sum() > 0
+    assert dones > 0
+
+
+def test_every_roster_unit_and_role_mix():
+    """All nine roster units on both teams (Healers, Assassin, Rangers, plain units), terrain
+    with bushes, greedy and noisy tiers."""
+    names = list(I.ROSTER)
+    E, N = 40, 2 * len(names)
+    w = I.Workload("roster_policy", E, len(names), 48.0, 24, "iid", 0.5, "iid", steps=150,
+                   seed=777)
+    sc = I.make_scenario(w, E)
+    for u in range(N):
+        row = I.ROSTER[names[u % len(names)]]
+        for k, v in zip(("hmax", "radius", "mass", "speed", "dmg", "range", "cooldown"), row):
+            sc[k][:, u] = np.float32(v)
+        sc["hurt_halfwidth"][:, u] = np.float32(row[1])
+    for tier in ("expert", "medium"):
+        _say(f"[gpu] policy roster mix, tier {tier}")
+        hist, dones = _policy_rollout(w, E, 150, tier, "both", scenario=sc, max_steps=120)
+        _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
+        assert hist[5] > 0
+
+
+def test_ragged_and_padded_units():
+    for team_size, disabled in [(1, 0), (7, 2), (33, 4), (50, 9)]:
+        w = I.Workload(f"ragged_policy_{team_size}", 5, team_size, 40.0, 20, "iid", 0.6, "iid",
+                       steps=60, seed=5252 + team_size)
+        sc = I.make_scenario(w, 5)
+        rng = np.random.default_rng(team_size)
+        for e in range(5):
+            off = rng.choice(w.num_units, size=min(disabled, w.num_units - 2), replace=False)
+            off = [u for u in off if u not in (0, w.num_units - 1)]
+            sc["enabled"][e, off] = 0
+        _say(f"[gpu] policy ragged N={w.num_units} disabled={disabled}")
+        _policy_rollout(w, 5, 60, "advanced", "both", scenario=sc, max_steps=40)
+
+
+def test_uncontrolled_entries_are_left_alone_and_errors():
+    import torch
+    from paper_2602_01665_amd import binding as B
+    w = I.WORKLOADS["c2_4096env_5v5"]
+    E = 64
+    p, sc = I.make_params(w, E), I.make_scenario(w, E)
+    gpu = B.TabxEnv(p, sc)
+    gpu.reset()
+    N = p["num_units"]
+    ctl = torch.zeros(E, N, dtype=torch.uint8, device=gpu.device)
+    ctl[:, N // 2:] = 1
+    a = torch.full((E, N), 99, dtype=torch.uint8, device=gpu.device)
+    gpu.heuristic_actions(I.policy("expert", 1), ctl, a)
+    torch.cuda.synchronize()
+    got = a.cpu().numpy()
+    assert (got[:, :N // 2] == 99).all() and (got[:, N // 2:] < 8).all()
+    # NULL outputs / memory and a non-finite coefficient are refused on the host
+    with pytest.raises(B.TabxError):
+        B.tabx_heuristic_actions(gpu.params, gpu.scenario, gpu.state,
+                                 B.TabxPolicy(**I.policy("expert", 1)), gpu.memory, None, None)
+    with pytest.raises(B.TabxError):
+        B.tabx_heuristic_actions(gpu.params, gpu.scenario, gpu.state,
+                                 B.TabxPolicy(**I.policy("expert", 1)), B.TabxPolicyMemory(),
+                                 None, a)
+    with pytest.raises(B.TabxError):
+        B.tabx_heuristic_actions(gpu.params, gpu.scenario, gpu.state,
+                                 B.TabxPolicy(**dict(I.policy("expert", 1), xi=float("nan"))),
+                                 gpu.memory, None, a)
