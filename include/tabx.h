@@ -229,6 +229,18 @@ int tabx_heuristic_actions(const TabxParams *params, const TabxScenario *scenari
                            const TabxPolicyMemory *memory, const uint8_t *controlled,
                            uint8_t *actions, void *stream);
 
+/* tabx_heuristic_actions followed by tabx_step_observe in one launch: the scripted units'
+ * actions are chosen from the state at entry, written into `actions` (in / out: the entries
+ * of the other units are read) and applied in the same tick.  An env that finishes also has
+ * the mem_valid flags of its units cleared, so the new episode starts without memories (the
+ * separate calls leave that to the caller, who sees `dones`).  Otherwise the results are
+ * identical to the two calls. */
+int tabx_policy_step_observe(const TabxParams *params, const TabxScenario *scenario,
+                             const TabxState *state, const TabxPolicy *policy,
+                             const TabxPolicyMemory *memory, const uint8_t *controlled,
+                             uint8_t *actions, float *rewards, uint8_t *dones, float *obs,
+                             uint64_t *vis_mask, uint8_t *action_mask, void *stream);
+
 const char *tabx_strerror(int code);
 
 #ifdef __cplusplus

@@ -231,3 +231,11 @@ class RefEnv:
                                          C.byref(pol), C.byref(self.cmem), _ptr(ctl, _B),
                                          _ptr(actions, _B))
         return actions
+
+    def policy_step(self, policy: dict, controlled, actions):
+        """heuristic_actions, then step, then the units of finished envs forget their targets:
+        what the library's fused policy tick computes."""
+        self.heuristic_actions(policy, controlled, actions)
+        out = self.step(actions)
+        self.mem["mem_valid"][self.dones.astype(bool)] = 0
+        return out

@@ -24,7 +24,8 @@ SCENARIO_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "s
 STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
 
 EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
-           "tabx_step_observe", "tabx_global_state", "tabx_heuristic_actions", "tabx_strerror")
+           "tabx_step_observe", "tabx_global_state", "tabx_heuristic_actions",
+           "tabx_policy_step_observe", "tabx_strerror")
 
 _I8 = C.POINTER(C.c_int8)
 _I32 = C.POINTER(C.c_int32)
@@ -84,6 +85,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
     lib.tabx_global_state.argtypes = [P, S, T, V, V]
     lib.tabx_heuristic_actions.argtypes = [P, S, T, C.POINTER(TabxPolicy),
                                            C.POINTER(TabxPolicyMemory), V, V, V]
+    lib.tabx_policy_step_observe.argtypes = [P, S, T, C.POINTER(TabxPolicy),
+                                             C.POINTER(TabxPolicyMemory)] + [V] * 8
     lib.tabx_strerror.argtypes = [C.c_int]
     lib.tabx_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -165,6 +168,15 @@ def tabx_heuristic_actions(params, scenario, state, policy, memory, controlled, 
            "tabx_heuristic_actions")
 
 
+def tabx_policy_step_observe(params, scenario, state, policy, memory, controlled, actions,
+                             rewards, dones, obs, vis_mask=None, action_mask=None, stream=None):
+    _check(_lib.tabx_policy_step_observe(C.byref(params), C.byref(scenario), C.byref(state),
+                                         C.byref(policy), C.byref(memory), _ptr(controlled),
+                                         _ptr(actions), _ptr(rewards), _ptr(dones), _ptr(obs),
+                                         _ptr(vis_mask), _ptr(action_mask), _stream_ptr(stream)),
+           "tabx_policy_step_observe")
+
+
 class TabxEnv:
     """Device buffers of one batch of environments plus the calls on them."""
 
@@ -229,8 +241,7 @@ class TabxEnv:
         tabx_global_state(self.params, self.scenario, self.state, self.gstate, stream)
         return self.gstate
 
-    def heuristic_actions(self, policy: dict, controlled, actions, stream=None):
-        """Fills `actions` (uint8 [E, N] on the device, in place) for the controlled units."""
+    def _policy_memory(self):
         if self.memory is None:
             n = self.E * self.N
             self.mem = {"mem_x": torch.zeros(n, dtype=torch.float32, device=self.device),
@@ -239,9 +250,19 @@ class TabxEnv:
             self.memory = TabxPolicyMemory(mem_x=_cast(self.mem["mem_x"], _F),
                                            mem_y=_cast(self.mem["mem_y"], _F),
                                            mem_valid=_cast(self.mem["mem_valid"], _U8))
+        return self.memory
+
+    def heuristic_actions(self, policy: dict, controlled, actions, stream=None):
+        """Fills `actions` (uint8 [E, N] on the device, in place) for the controlled units."""
+        self._policy_memory()
         tabx_heuristic_actions(self.params, self.scenario, self.state, TabxPolicy(**policy),
                                self.memory, controlled, actions, stream)
         return actions
+
+    def policy_step_observe(self, policy: dict, controlled, actions, stream=None):
+        tabx_policy_step_observe(self.params, self.scenario, self.state, TabxPolicy(**policy),
+                                 self._policy_memory(), controlled, actions, self.rewards,
+                                 self.dones, self.obs, self.vis, self.amask, stream)
 
     def reset(self, env_mask=None, stream=None):
         tabx_reset(self.params, self.scenario, self.state, env_mask, stream)

@@ -32,6 +32,13 @@ namespace tabx {
 
 constexpr int kMaxPasses = 10;     // store passes that stream one set of staged rows
 
+struct PolicyArgs {
+    TabxPolicy       pol;
+    TabxPolicyMemory mem;          // mem_valid == nullptr: no policy in this launch
+    const uint8_t   *controlled;
+    uint8_t         *actions_out;
+};
+
 struct KArgs {
     TabxParams   p;
     TabxScenario sc;
@@ -53,6 +60,7 @@ struct KArgs {
     int       groups_per_xcd;      // ceil(num_groups / 8)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
     int       cell_pow2;
+    PolicyArgs pa;
 };
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte store, 4-byte aligned
@@ -132,12 +140,17 @@ struct Shared {
             int2   hitrec[L];     // {designated victim (local index) or -1, damage bits}
             float2 share[L];      // this unit's term in the team-0 / team-1 ratio sums
         } st;
+        struct {                  // policy stage: what a deciding unit needs of the others
+            float4 pose[L];       // x, y, cos(theta), sin(theta)
+            float4 body[L];       // radius, max health, health, -
+        } po;
         struct {                  // observe stage: what an observer's row needs
             float4 pose[L];       // x, y, cos(theta), sin(theta)
             float4 reach[L];      // attack range, hurtbox half-width, sight range^2, cos(cone / 2)
         } ob;
     };
     int      seer[L];             // observer flags: alive | team<<1 | heals<<2 | enabled<<3 | bush key<<8
+                                  // (policy stage: alive | team<<1 | concealable<<2 | bush key<<8)
     uint64_t rowbits[WAVES == 1 ? 1 : L][WAVES];   // two-wave workgroups: ballots of "observer i sees lane"
     uint64_t ballots[WAVES][4];
 };
@@ -347,16 +360,191 @@ __device__ __forceinline__ float hurtbox_gap2(float dx, float dy, float ci, floa
     return (ex * ex) + (ey * ey);
 }
 
+// ------------------------------------------------------------------ heuristic policy
+//
+// Role-appropriate heuristic policy (Sec. 4.2; App. A "Role-Appropriate Heuristic Policy
+// Mechanism" and the table of tier parameters).  Lane = deciding unit; the units of its env
+// are scanned through records in LDS.  Visibility and reach are the tests of the observation
+// (fan-shaped field of view, bush rule, hurtbox, role filter), from the observer's side.
+
+// Counter-based random numbers: two multiply / xor-shift rounds over the draw's coordinates.
+__device__ __forceinline__ uint32_t policy_hash(uint32_t seed, uint32_t env, uint32_t unit,
+                                                uint32_t tick, uint32_t draw)
+{
+    uint32_t x = seed;
+    x ^= env * 0x9E3779B9u;
+    x ^= unit * 0x85EBCA6Bu;
+    x ^= tick * 0xC2B2AE35u;
+    x ^= draw * 0x27D4EB2Fu;
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// The cardinal move that closes most of the offset (gx, gy); idle if there is none.
+__device__ __forceinline__ int move_along(float gx, float gy)
+{
+    const float ax = __builtin_fabsf(gx), ay = __builtin_fabsf(gy);
+    const int along_x = gx > 0.0f ? TABX_ACT_MOVE_XP : (gx < 0.0f ? TABX_ACT_MOVE_XM : TABX_ACT_NOOP);
+    const int along_y = gy > 0.0f ? TABX_ACT_MOVE_YP : TABX_ACT_MOVE_YM;
+    return ax >= ay ? along_x : along_y;
+}
+
+// Decides for the lane's unit from the state in U (heading cosine / sine cu, su, zone code
+// code_u under it); returns the action, or -1 if the unit is not the policy's to move.  Writes
+// the action and the remembered target position.  All lanes of the workgroup call it.
+template <int WAVES>
+__device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, const Place &P,
+                                          const Unit &U, int code_u, float cu, float su)
+{
+    const PolicyArgs &pa = a.pa;
+    const int N = a.p.num_units;
+    const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
+    const int my_key = in_bush ? (code_u & 0xff) : 0x100;          // 0x100 matches no cell code
+    const bool concealable = in_bush && !(U.reveal > 0.0f);
+    sh.po.pose[P.l] = make_float4(U.x, U.y, cu, su);
+    sh.po.body[P.l] = make_float4(U.radius, U.hmax, U.hp, 0.0f);
+    sh.seer[P.l] = (P.has ? U.alive : 0) | (U.team << 1) | (concealable ? 4 : 0) | (my_key << 8);
+    // per-env tick counter and the unit's memory, requested before the scan
+    const bool decide = P.has && U.enabled && U.alive && (!pa.controlled || pa.controlled[P.k]);
+    const uint32_t tick = decide ? (uint32_t)a.st.t[P.e] : 0u;
+    const int remembered = decide ? pa.mem.mem_valid[P.k] : 0;
+    const float mx = decide ? pa.mem.mem_x[P.k] : 0.0f;
+    const float my = decide ? pa.mem.mem_y[P.k] : 0.0f;
+    lds_barrier<WAVES>();
+
+    const bool healer = U.dmg < 0.0f;
+    const bool assassin = U.speed >= pa.pol.assassin_speed;
+    const bool ranger = U.range >= pa.pol.ranger_range;
+    const float sight2 = U.sight_range * U.sight_range;
+    const float neg_hw = -U.hurt_hw;
+
+    // One scan, no divergent branches: the target by role (Healer: injured allies first, then
+    // nearest; Assassin: lowest maximum health, then nearest; others: nearest enemy; a strict
+    // "better" keeps the lower index on ties), the nearest visible enemy, and whether
+    // anything worth a strike is in the hurtbox.
+    int tgt = -1;
+    bool any_enemy = false, can_hit = false, tgt_in_box = false;
+    float tgt_d2 = 0.0f, tgt_key = 0.0f, near_d2 = 0.0f, near_dx = 0.0f, near_dy = 0.0f;
+    for (int j = 0; j < N; ++j) {
+        const int fj = sh.seer[P.base + j];
+        const float4 A = sh.po.pose[P.base + j];
+        const float4 B = sh.po.body[P.base + j];
+        const float dx = A.x - U.x;
+        const float dy = A.y - U.y;
+        float dot;
+        const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, dot);
+        const float d2 = (dx * dx) + (dy * dy);
+        const bool in_range = d2 <= sight2;
+        const bool in_cone = (d2 == 0.0f) || (dot >= U.cos_half * __builtin_sqrtf(d2));
+        const bool same_team = ((fj >> 1) & 1) == U.team;
+        const bool same_bush = (fj >> 8) == my_key;
+        const bool concealed = (fj & 4) && !same_team && !same_bush;
+        const bool seen = (j != P.u) && (fj & 1) && in_range && in_cone && !concealed;
+        const bool attackable = seen && (healer == same_team) && (g2 <= B.x * B.x);
+        const bool injured = B.z < B.y;
+        can_hit = can_hit || (attackable && (!healer || injured));
+        const bool enemy = seen && !same_team;
+        const bool nearer = enemy && (!any_enemy || d2 < near_d2);
+        any_enemy = any_enemy || enemy;
+        near_d2 = nearer ? d2 : near_d2;
+        near_dx = nearer ? dx : near_dx;
+        near_dy = nearer ? dy : near_dy;
+        const bool candidate = seen && (healer == same_team);
+        const float key = healer ? (injured ? 0.0f : 1.0f) : (assassin ? B.y : 0.0f);
+        const bool better = candidate && (tgt < 0 || key < tgt_key || (key == tgt_key && d2 < tgt_d2));
+        tgt = better ? j : tgt;
+        tgt_d2 = better ? d2 : tgt_d2;
+        tgt_key = better ? key : tgt_key;
+        tgt_in_box = better ? attackable : tgt_in_box;
+    }
+
+    int act = -1;
+    if (decide) {
+        const uint32_t coin = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 2u) & 1u;
+        const int search_turn = coin ? TABX_ACT_ROT_LEFT : TABX_ACT_ROT_RIGHT;
+        if (tgt >= 0) {
+            const float4 T = sh.po.pose[P.base + tgt];
+            const float tr = sh.po.body[P.base + tgt].x;
+            pa.mem.mem_x[P.k] = T.x;
+            pa.mem.mem_y[P.k] = T.y;
+            if (!remembered) pa.mem.mem_valid[P.k] = 1;
+            const float tdx = T.x - U.x;
+            const float tdy = T.y - U.y;
+            const float reach = U.range + tr;
+            const bool within = tgt_d2 <= reach * reach;
+            const float kite = pa.pol.xi * U.range;
+            // turning towards the side the target is on
+            const float lx = (tdx * cu) + (tdy * su);
+            const float ly = (tdy * cu) - (tdx * su);
+            const int turn = ly > 0.0f ? TABX_ACT_ROT_LEFT
+                                       : (ly < 0.0f ? TABX_ACT_ROT_RIGHT
+                                                    : (lx < 0.0f ? TABX_ACT_ROT_LEFT : TABX_ACT_NOOP));
+            // Assassins go behind the target, Healers to it, the rest in front of it
+            const float standoff = 0.5f * U.range;
+            const float ox = T.z * standoff, oy = T.w * standoff;
+            const float gx = healer ? T.x : (assassin ? T.x - ox : T.x + ox);
+            const float gy = healer ? T.y : (assassin ? T.y - oy : T.y + oy);
+            const int approach = move_along(gx - U.x, gy - U.y);
+            const int retreat = move_along(-near_dx, -near_dy);
+            act = (can_hit && U.cd <= 0.0f) ? (int)TABX_ACT_ATTACK
+                  : (within && !tgt_in_box) ? turn
+                  : (ranger && any_enemy && near_d2 < kite * kite) ? retreat
+                  : tgt_in_box ? (int)TABX_ACT_NOOP            // aligned, waiting for the cooldown
+                               : approach;
+        } else if (remembered) {
+            const float gx = mx - U.x;
+            const float gy = my - U.y;
+            const bool arrived = (gx * gx) + (gy * gy) <= 1.0f;
+            if (arrived) pa.mem.mem_valid[P.k] = 0;
+            act = arrived ? search_turn : move_along(gx, gy);
+        } else {
+            // Rangers outside a bush walk to the nearest bush zone they know of, then search
+            int bush = -1;
+            float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
+            if (ranger && !in_bush && a.sc.zone_desc) {
+                const float *zd = a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones;
+                for (int z = 0; z < a.p.max_zones; ++z) {
+                    const float *d = zd + 6 * z;
+                    if ((int)d[0] != TABX_ZONE_BUSH) continue;
+                    const float zx = d[1] - U.x;
+                    const float zy = d[2] - U.y;
+                    const float d2 = (zx * zx) + (zy * zy);
+                    if (bush < 0 || d2 < bush_d2) {
+                        bush = z;
+                        bush_d2 = d2;
+                        bx = zx;
+                        by = zy;
+                    }
+                }
+            }
+            act = bush >= 0 ? move_along(bx, by) : search_turn;
+        }
+        // epsilon-greedy override
+        const uint32_t h0 = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 0u);
+        const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
+        if (u0 < pa.pol.epsilon)
+            act = (int)(policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 1u) & 7u);
+        pa.actions_out[P.k] = (uint8_t)act;
+    }
+    lds_barrier<WAVES>();          // the records may be overwritten by the next stage
+    return act;
+}
+
+// `forced` >= 0 replaces the unit's entry of the action array (the policy stage chose it).
 template <int WAVES>
 __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, const float *zd,
-                                         const Place &P, Unit &U, int &code_u, Carry &C)
+                                         const Place &P, Unit &U, int &code_u, Carry &C, int forced)
 {
     float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
     const int N = a.p.num_units;
     const float dt = a.p.dt;
     const bool has = P.has;
     const int alive0 = has ? U.alive : 0;
-    const int act = has ? (int)a.actions[P.k] : 0;
+    const int act = forced >= 0 ? forced : (has ? (int)a.actions[P.k] : 0);
     // per-env scalars, requested early: they are needed only after three LDS exchanges
     const int t_new = has ? a.st.t[P.e] + 1 : 0;
     const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
@@ -551,6 +739,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
     lds_barrier<WAVES>();          // everyone has read the ratio terms of the finished tick
     if (any_done) {
         if (done) {
+            if (a.pa.mem.mem_valid) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
             code_u = spawn_unit(a, zd, P.e, P.k, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
@@ -857,7 +1046,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     }
 }
 
-template <int WAVES, bool DO_STEP, bool DO_OBS>
+template <int WAVES, bool DO_POLICY, bool DO_STEP, bool DO_OBS>
 __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
 {
     __shared__ Shared<WAVES> sh;
@@ -885,8 +1074,17 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
     const float *zd = zdesc + (P.has ? P.g : 0) * zlen;
     Carry C = {1.0f, 0.0f, 0.0f};
     float zeff_unused = 0.0f;
-    if (DO_STEP) step_env<WAVES>(a, sh, zd, P, U, code_u, C);
-    else if (P.has) code_u = zone_at(a, zd, P.e, U.x, U.y, zeff_unused);
+    int forced = -1;
+    if (DO_POLICY) {
+        float cu = 1.0f, su = 0.0f;
+        if (P.has) {
+            code_u = zone_at(a, zd, P.e, U.x, U.y, zeff_unused);
+            heading_sincos(U.theta, su, cu);
+        }
+        forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su);
+    }
+    if (DO_STEP) step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
+    else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.e, U.x, U.y, zeff_unused);
     if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C, Zr);
 }
 
@@ -969,219 +1167,10 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
     }
 }
 
-// ------------------------------------------------------------------ heuristic policy
-//
-// Role-appropriate heuristic policy (Sec. 4.2; App. A "Role-Appropriate Heuristic Policy
-// Mechanism" and the table of tier parameters).  Lane = deciding unit; the units of its env
-// are scanned through records in LDS.  Visibility and reach are the tests of the observation
-// (fan-shaped field of view, bush rule, hurtbox, role filter), from the observer's side.
-
-struct PolicyArgs {
-    TabxPolicy       pol;
-    TabxPolicyMemory mem;
-    const uint8_t   *controlled;
-    uint8_t         *actions_out;
-};
-
-template <int WAVES>
-struct PolicyShared {
-    static constexpr int L = 64 * WAVES;
-    float4 pose[L];       // x, y, cos(theta), sin(theta)
-    float4 body[L];       // radius, max health, health, -
-    int    flags[L];      // alive | team<<1 | concealable<<2 | bush key<<8
-};
-
-// Counter-based random numbers: two multiply / xor-shift rounds over the draw's coordinates.
-__device__ __forceinline__ uint32_t policy_hash(uint32_t seed, uint32_t env, uint32_t unit,
-                                                uint32_t tick, uint32_t draw)
-{
-    uint32_t x = seed;
-    x ^= env * 0x9E3779B9u;
-    x ^= unit * 0x85EBCA6Bu;
-    x ^= tick * 0xC2B2AE35u;
-    x ^= draw * 0x27D4EB2Fu;
-    x ^= x >> 16;
-    x *= 0x7FEB352Du;
-    x ^= x >> 15;
-    x *= 0x846CA68Bu;
-    x ^= x >> 16;
-    return x;
-}
-
-// The cardinal move that closes most of the offset (gx, gy); idle if there is none.
-__device__ __forceinline__ int move_along(float gx, float gy)
-{
-    const float ax = __builtin_fabsf(gx), ay = __builtin_fabsf(gy);
-    if (ax >= ay) return gx > 0.0f ? TABX_ACT_MOVE_XP : (gx < 0.0f ? TABX_ACT_MOVE_XM : TABX_ACT_NOOP);
-    return gy > 0.0f ? TABX_ACT_MOVE_YP : TABX_ACT_MOVE_YM;
-}
-
-template <int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void tabx_policy_kernel(const KArgs a, const PolicyArgs pa)
-{
-    __shared__ PolicyShared<WAVES> sh;
-    const Place P = locate<WAVES>(a);
-    const int N = a.p.num_units;
-    Unit U = {};
-    int code_u = 0;
-    float cu = 1.0f, su = 0.0f;
-    if (P.has) {
-        load_spec(a, P.k, U);
-        load_state(a, P.k, U);
-        float zeff = 0.0f;
-        code_u = zone_at(a, a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones, P.e, U.x, U.y, zeff);
-        heading_sincos(U.theta, su, cu);
-    }
-    const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
-    const int my_key = in_bush ? (code_u & 0xff) : 0x100;          // 0x100 matches no cell code
-    const bool concealable = in_bush && !(U.reveal > 0.0f);
-    sh.pose[P.l] = make_float4(U.x, U.y, cu, su);
-    sh.body[P.l] = make_float4(U.radius, U.hmax, U.hp, 0.0f);
-    sh.flags[P.l] = (P.has ? U.alive : 0) | (U.team << 1) | (concealable ? 4 : 0) | (my_key << 8);
-    lds_barrier<WAVES>();
-
-    const bool decide = P.has && U.enabled && U.alive && (!pa.controlled || pa.controlled[P.k]);
-    if (!decide) return;
-
-    const bool healer = U.dmg < 0.0f;
-    const bool assassin = U.speed >= pa.pol.assassin_speed;
-    const bool ranger = U.range >= pa.pol.ranger_range;
-    const float sight2 = U.sight_range * U.sight_range;
-    const float neg_hw = -U.hurt_hw;
-
-    // target selection among the visible units; nearest visible enemy; anything worth a strike
-    int tgt = -1, near_enemy = -1;
-    float tgt_d2 = 0.0f, tgt_h = 0.0f, near_d2 = 0.0f, near_dx = 0.0f, near_dy = 0.0f;
-    bool tgt_injured = false, can_hit = false, tgt_in_box = false;
-    for (int j = 0; j < N; ++j) {
-        const int fj = sh.flags[P.base + j];
-        if (j == P.u || !(fj & 1)) continue;
-        const float4 A = sh.pose[P.base + j];
-        const float4 B = sh.body[P.base + j];
-        const float dx = A.x - U.x;
-        const float dy = A.y - U.y;
-        float dot;
-        const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, dot);
-        const float d2 = (dx * dx) + (dy * dy);
-        const bool in_range = d2 <= sight2;
-        const bool in_cone = (d2 == 0.0f) || (dot >= U.cos_half * __builtin_sqrtf(d2));
-        const bool same_team = ((fj >> 1) & 1) == U.team;
-        const bool same_bush = (fj >> 8) == my_key;
-        const bool concealed = (fj & 4) && !same_team && !same_bush;
-        if (!(in_range && in_cone && !concealed)) continue;
-        const bool attackable = (healer == same_team) && (g2 <= B.x * B.x);
-        const bool injured = B.z < B.y;
-        if (attackable && (!healer || injured)) can_hit = true;
-        if (!same_team && (near_enemy < 0 || d2 < near_d2)) {
-            near_enemy = j;
-            near_d2 = d2;
-            near_dx = dx;
-            near_dy = dy;
-        }
-        bool better = false;
-        if (healer) {                // nearest injured ally, else nearest ally
-            if (same_team) {
-                better = tgt < 0 || (injured && !tgt_injured) || (injured == tgt_injured && d2 < tgt_d2);
-                if (better) tgt_injured = injured;
-            }
-        } else if (assassin) {       // lowest maximum health, then nearest
-            if (!same_team) better = tgt < 0 || B.y < tgt_h || (B.y == tgt_h && d2 < tgt_d2);
-        } else {                     // nearest enemy
-            if (!same_team) better = tgt < 0 || d2 < tgt_d2;
-        }
-        if (better) {
-            tgt = j;
-            tgt_d2 = d2;
-            tgt_h = B.y;
-            tgt_in_box = attackable;
-        }
-    }
-
-    const uint32_t tick = (uint32_t)a.st.t[P.e];
-    const uint32_t coin = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 2u) & 1u;
-    const int search_turn = coin ? TABX_ACT_ROT_LEFT : TABX_ACT_ROT_RIGHT;
-    int act = TABX_ACT_NOOP;
-    if (tgt >= 0) {
-        const float4 T = sh.pose[P.base + tgt];
-        const float tr = sh.body[P.base + tgt].x;
-        pa.mem.mem_x[P.k] = T.x;
-        pa.mem.mem_y[P.k] = T.y;
-        pa.mem.mem_valid[P.k] = 1;
-        const float tdx = T.x - U.x;
-        const float tdy = T.y - U.y;
-        const float reach = U.range + tr;
-        const bool within = tgt_d2 <= reach * reach;
-        const float kite = pa.pol.xi * U.range;
-        if (can_hit && U.cd <= 0.0f) {
-            act = TABX_ACT_ATTACK;
-        } else if (within && !tgt_in_box) {
-            // turn towards the side the target is on
-            const float lx = (tdx * cu) + (tdy * su);
-            const float ly = (tdy * cu) - (tdx * su);
-            act = ly > 0.0f ? TABX_ACT_ROT_LEFT
-                            : (ly < 0.0f ? TABX_ACT_ROT_RIGHT : (lx < 0.0f ? TABX_ACT_ROT_LEFT : TABX_ACT_NOOP));
-        } else if (ranger && near_enemy >= 0 && near_d2 < kite * kite) {
-            act = move_along(-near_dx, -near_dy);
-        } else if (tgt_in_box) {
-            act = TABX_ACT_NOOP;     // aligned, waiting for the cooldown
-        } else {
-            // Assassins go behind the target, Healers to it, the rest in front of it
-            const float standoff = 0.5f * U.range;
-            float gx = T.x, gy = T.y;
-            if (!healer) {
-                if (assassin) {
-                    gx = gx - (T.z * standoff);
-                    gy = gy - (T.w * standoff);
-                } else {
-                    gx = gx + (T.z * standoff);
-                    gy = gy + (T.w * standoff);
-                }
-            }
-            act = move_along(gx - U.x, gy - U.y);
-        }
-    } else if (pa.mem.mem_valid[P.k]) {
-        const float gx = pa.mem.mem_x[P.k] - U.x;
-        const float gy = pa.mem.mem_y[P.k] - U.y;
-        if ((gx * gx) + (gy * gy) <= 1.0f) {
-            pa.mem.mem_valid[P.k] = 0;
-            act = search_turn;
-        } else {
-            act = move_along(gx, gy);
-        }
-    } else {
-        // Rangers outside a bush walk to the nearest bush zone they know of, then search
-        int bush = -1;
-        float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
-        if (ranger && !in_bush && a.sc.zone_desc) {
-            const float *zd = a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones;
-            for (int z = 0; z < a.p.max_zones; ++z) {
-                const float *d = zd + 6 * z;
-                if ((int)d[0] != TABX_ZONE_BUSH) continue;
-                const float zx = d[1] - U.x;
-                const float zy = d[2] - U.y;
-                const float d2 = (zx * zx) + (zy * zy);
-                if (bush < 0 || d2 < bush_d2) {
-                    bush = z;
-                    bush_d2 = d2;
-                    bx = zx;
-                    by = zy;
-                }
-            }
-        }
-        act = bush >= 0 ? move_along(bx, by) : search_turn;
-    }
-
-    // epsilon-greedy override
-    const uint32_t h0 = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 0u);
-    const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
-    if (u0 < pa.pol.epsilon)
-        act = (int)(policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 1u) & 7u);
-    pa.actions_out[P.k] = (uint8_t)act;
-}
-
 // ------------------------------------------------------------------ host side
 
-enum Mode { MODE_RESET, MODE_STEP, MODE_OBSERVE, MODE_STEP_OBSERVE };
+enum Mode { MODE_RESET, MODE_STEP, MODE_OBSERVE, MODE_STEP_OBSERVE, MODE_POLICY,
+            MODE_POLICY_STEP_OBSERVE };
 
 static bool aligned(const void *p, size_t n) { return ((uintptr_t)p % n) == 0; }
 
@@ -1255,20 +1244,29 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     const size_t zdesc_floats = a.p.zone_shapes == 1 ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
     const size_t dyn_bytes = (dyn_floats + zdesc_floats) * sizeof(float);
     const size_t step_bytes = zdesc_floats * sizeof(float);
-    a.zdesc_offset = mode == MODE_STEP ? 0 : (int)dyn_floats;
+    a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0 : (int)dyn_floats;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
         break;
     case MODE_STEP:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false>), grid, block, step_bytes, stream, a);
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, false>), grid, block, step_bytes,
+                           stream, a);
         break;
     case MODE_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true>), grid, block, dyn_bytes,
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, false, true>), grid, block, dyn_bytes,
                            stream, a);
         break;
     case MODE_STEP_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, true>), grid, block, dyn_bytes,
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true>), grid, block, dyn_bytes,
+                           stream, a);
+        break;
+    case MODE_POLICY:
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false, false>), grid, block, step_bytes,
+                           stream, a);
+        break;
+    case MODE_POLICY_STEP_OBSERVE:
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, true, true>), grid, block, dyn_bytes,
                            stream, a);
         break;
     }
@@ -1277,15 +1275,28 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
 static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const TabxState *st,
                const uint8_t *actions, const uint8_t *env_mask, float *rewards,
                uint8_t *dones, float *obs, uint64_t *vis_mask, uint8_t *action_mask,
-               void *stream)
+               void *stream, const TabxPolicy *policy = nullptr,
+               const TabxPolicyMemory *memory = nullptr, const uint8_t *controlled = nullptr,
+               uint8_t *actions_out = nullptr)
 {
     int rc = check_params(p);
     if (rc) return rc;
     if (p->num_envs == 0) return TABX_OK;          // empty batch: nothing to validate or do
     if ((rc = check_scenario(p, sc))) return rc;
     if ((rc = check_state(st))) return rc;
-    const bool stepping = mode == MODE_STEP || mode == MODE_STEP_OBSERVE;
-    const bool observing = mode == MODE_OBSERVE || mode == MODE_STEP_OBSERVE;
+    const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE;
+    const bool stepping = mode == MODE_STEP || mode == MODE_STEP_OBSERVE ||
+                          mode == MODE_POLICY_STEP_OBSERVE;
+    const bool observing = mode == MODE_OBSERVE || mode == MODE_STEP_OBSERVE ||
+                           mode == MODE_POLICY_STEP_OBSERVE;
+    if (deciding) {
+        if (!policy || !memory || !actions_out) return TABX_ERR_NULL;
+        if (!memory->mem_x || !memory->mem_y || !memory->mem_valid) return TABX_ERR_NULL;
+        if (!aligned(memory->mem_x, 4) || !aligned(memory->mem_y, 4)) return TABX_ERR_ALIGN;
+        const float fin[] = {policy->epsilon, policy->xi, policy->assassin_speed, policy->ranger_range};
+        for (float v : fin)
+            if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
+    }
     if (stepping) {
         if (!actions || !rewards || !dones) return TABX_ERR_NULL;
         if (!aligned(rewards, 4)) return TABX_ERR_ALIGN;
@@ -1306,6 +1317,13 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     a.vis_mask = vis_mask;
     a.action_mask = action_mask;
     a.obs_dim = 16 * p->num_units + 6 * p->max_zones;
+    a.pa = {};
+    if (deciding) {
+        a.pa.pol = *policy;
+        a.pa.mem = *memory;
+        a.pa.controlled = controlled;
+        a.pa.actions_out = actions_out;
+    }
 
     hipStream_t s = (hipStream_t)stream;
     (void)hipGetLastError();
@@ -1422,44 +1440,18 @@ int tabx_heuristic_actions(const TabxParams *p, const TabxScenario *sc, const Ta
                            const TabxPolicy *policy, const TabxPolicyMemory *memory,
                            const uint8_t *controlled, uint8_t *actions, void *stream)
 {
-    int rc = tabx::check_params(p);
-    if (rc) return rc;
-    if (p->num_envs == 0) return TABX_OK;
-    if ((rc = tabx::check_scenario(p, sc))) return rc;
-    if ((rc = tabx::check_state(st))) return rc;
-    if (!policy || !memory || !actions) return TABX_ERR_NULL;
-    if (!memory->mem_x || !memory->mem_y || !memory->mem_valid) return TABX_ERR_NULL;
-    if (!tabx::aligned(memory->mem_x, 4) || !tabx::aligned(memory->mem_y, 4)) return TABX_ERR_ALIGN;
-    const float fin[] = {policy->epsilon, policy->xi, policy->assassin_speed, policy->ranger_range};
-    for (float v : fin)
-        if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
-    tabx::KArgs a = {};
-    a.p = *p;
-    a.sc = *sc;
-    a.st = *st;
-    {
-        int ex = 0;
-        const float mant = frexpf(p->cell_size, &ex);
-        a.cell_pow2 = (mant == 0.5f && ex > -100 && ex < 100) ? 1 : 0;
-        a.inv_cell = 1.0f / p->cell_size;
-    }
-    const int N = p->num_units;
-    const int waves = N <= 64 ? 1 : 2;
-    a.envs_per_block = waves == 1 ? 64 / N : 1;
-    a.num_groups = (p->num_envs + a.envs_per_block - 1) / a.envs_per_block;
-    a.groups_per_xcd = (a.num_groups + 7) / 8;
-    tabx::PolicyArgs pa;
-    pa.pol = *policy;
-    pa.mem = *memory;
-    pa.controlled = controlled;
-    pa.actions_out = actions;
-    const dim3 grid((unsigned)(8 * a.groups_per_xcd)), block(64 * waves);
-    (void)hipGetLastError();
-    if (waves == 1)
-        hipLaunchKernelGGL((tabx::tabx_policy_kernel<1>), grid, block, 0, (hipStream_t)stream, a, pa);
-    else
-        hipLaunchKernelGGL((tabx::tabx_policy_kernel<2>), grid, block, 0, (hipStream_t)stream, a, pa);
-    return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
+    return tabx::run(tabx::MODE_POLICY, p, sc, st, nullptr, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, stream, policy, memory, controlled, actions);
+}
+
+int tabx_policy_step_observe(const TabxParams *p, const TabxScenario *sc, const TabxState *st,
+                             const TabxPolicy *policy, const TabxPolicyMemory *memory,
+                             const uint8_t *controlled, uint8_t *actions, float *rewards,
+                             uint8_t *dones, float *obs, uint64_t *vis_mask,
+                             uint8_t *action_mask, void *stream)
+{
+    return tabx::run(tabx::MODE_POLICY_STEP_OBSERVE, p, sc, st, actions, nullptr, rewards, dones,
+                     obs, vis_mask, action_mask, stream, policy, memory, controlled, actions);
 }
 
 const char *tabx_strerror(int code)

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from paper_2602_01665_amd import inputs as I
-from tests.parity import compare_state
+from tests.parity import compare_outputs, compare_state
 
 pytestmark = pytest.mark.gpu
 
@@ -20,8 +20,17 @@ def _say(msg):
     sys.stdout.flush()
 
 
-def _policy_rollout(w, E, steps, tier, who, scenario=None, seed=5, **override):
-    """who: "adversaries" (allies act at random), "both", or "allies"."""
+def _check_memory(gpu, ref, E, N, where):
+    valid = gpu.mem["mem_valid"].cpu().numpy().reshape(E, N)
+    assert np.array_equal(valid, ref.mem["mem_valid"]), where + "mem_valid"
+    for k in ("mem_x", "mem_y"):
+        g = gpu.mem[k].cpu().numpy().reshape(E, N)
+        assert np.array_equal(g[valid == 1], ref.mem[k][valid == 1]), where + k
+
+
+def _policy_rollout(w, E, steps, tier, who, scenario=None, seed=5, fused=False, **override):
+    """who: "adversaries" (allies act at random), "both", or "allies".  fused: the policy runs
+    inside the tick launch (tabx_policy_step_observe)."""
     import torch
     from oracle.ref import RefEnv
     from paper_2602_01665_amd.binding import TabxEnv
@@ -42,19 +51,29 @@ def _policy_rollout(w, E, steps, tier, who, scenario=None, seed=5, **override):
     for s in range(steps):
         a = I.actions_for_step(w.seed, s, E, N)
         ad = torch.from_numpy(a).to(gpu.device)
+        where = f"{w.name} E={E} {tier}/{who} step {s}: "
+        if fused:
+            ref.policy_step(pol, ctl, a)
+            ref.observe()
+            gpu.policy_step_observe(pol, ctl_d, ad)
+            torch.cuda.synchronize()
+            got = ad.cpu().numpy()
+            bad = np.argwhere(got != a)
+            assert bad.size == 0, where + f"actions differ at {bad[:5].tolist()}"
+            _check_memory(gpu, ref, E, N, where)
+            compare_state(gpu.state_numpy(), ref.st, where)
+            compare_outputs(gpu, ref, where, check_obs=True)
+            hist += np.bincount(a[ctl == 1], minlength=8)
+            dones += int(ref.dones.sum())
+            continue
         ref.heuristic_actions(pol, ctl, a)
         gpu.heuristic_actions(pol, ctl_d, ad)
         torch.cuda.synchronize()
-        where = f"{w.name} E={E} {tier}/{who} step {s}: "
         got = ad.cpu().numpy()
         bad = np.argwhere(got != a)
         assert bad.size == 0, where + f"actions differ at {bad[:5].tolist()}: " \
             f"{got[tuple(bad[0])]} vs {a[tuple(bad[0])]}"
-        valid = gpu.mem["mem_valid"].cpu().numpy().reshape(E, N)
-        assert np.array_equal(valid, ref.mem["mem_valid"]), where + "mem_valid"
-        for k in ("mem_x", "mem_y"):
-            g = gpu.mem[k].cpu().numpy().reshape(E, N)
-            assert np.array_equal(g[valid == 1], ref.mem[k][valid == 1]), where + k
+        _check_memory(gpu, ref, E, N, where)
         hist += np.bincount(a[ctl == 1], minlength=8)
         ref.step(a)
         gpu.step(ad)
@@ -72,11 +91,12 @@ def _policy_rollout(w, E, steps, tier, who, scenario=None, seed=5, **override):
 TIERS = ["random", "novice", "medium", "advanced", "expert"]
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
 @pytest.mark.parametrize("tier", TIERS)
-def test_adversaries_under_every_tier(tier):
-    _say(f"[gpu] policy c3 subset, adversaries, tier {tier}")
+def test_adversaries_under_every_tier(tier, fused):
+    _say(f"[gpu] policy c3 subset, adversaries, tier {tier}, fused={fused}")
     hist, dones = _policy_rollout(I.WORKLOADS["c3_16384env_10v10"], 48, 120, tier, "adversaries",
-                                  max_steps=96)
+                                  fused=fused, max_steps=96)
     _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
     assert hist.sum() > 0
 
@@ -88,9 +108,11 @@ def test_adversaries_under_every_tier(tier):
     ("c3e_16384env_10v10_ellipses", 70, 200, dict(max_steps=128)),
     ("c5_1024env_64v64", 3, 80, dict(max_steps=60)),
 ], ids=lambda v: v if isinstance(v, str) else None)
-def test_self_play_rollouts(name, E, steps, over):
-    _say(f"[gpu] policy self-play {name} E={E} steps={steps}")
-    hist, dones = _policy_rollout(I.WORKLOADS[name], E, steps, "expert", "both", **over)
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_self_play_rollouts(name, E, steps, over, fused):
+    _say(f"[gpu] policy self-play {name} E={E} steps={steps} fused={fused}")
+    hist, dones = _policy_rollout(I.WORKLOADS[name], E, steps, "expert", "both", fused=fused,
+                                  **over)
     _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
     # seek-and-approach, combat, turning and search all occur
     assert hist[5] > 0 and hist[1:5].sum() > 0 and hist[6:].sum() > 0
@@ -112,7 +134,8 @@ def test_every_roster_unit_and_role_mix():
         sc["hurt_halfwidth"][:, u] = np.float32(row[1])
     for tier in ("expert", "medium"):
         _say(f"[gpu] policy roster mix, tier {tier}")
-        hist, dones = _policy_rollout(w, E, 150, tier, "both", scenario=sc, max_steps=120)
+        hist, dones = _policy_rollout(w, E, 150, tier, "both", scenario=sc,
+                                      fused=tier == "medium", max_steps=120)
         _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
         assert hist[5] > 0
 
@@ -129,6 +152,8 @@ def test_ragged_and_padded_units():
             sc["enabled"][e, off] = 0
         _say(f"[gpu] policy ragged N={w.num_units} disabled={disabled}")
         _policy_rollout(w, 5, 60, "advanced", "both", scenario=sc, max_steps=40)
+        _policy_rollout(w, 5, 60, "advanced", "adversaries", scenario=sc, fused=True,
+                        max_steps=40)
 
 
 def test_uncontrolled_entries_are_left_alone_and_errors():
