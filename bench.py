@@ -70,6 +70,9 @@ def main() -> int:
                          "not part of the headline tick")
     ap.add_argument("--separate", action="store_true",
                     help="time tabx_step + tabx_observe as two launches instead of the fused one")
+    ap.add_argument("--policy", default=None, metavar="TIER",
+                    help="the adversaries are moved by the heuristic policy of this tier inside "
+                         "the tick launch (tabx_policy_step_observe); not the headline tick")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (environments are independent; more GPUs "
@@ -98,10 +101,19 @@ def main() -> int:
     acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, N)).to("cuda:0")
             for s in range(n_act)]
     stream = torch.cuda.current_stream()
+    scripted = policy = None
+    if args.policy:
+        policy = I.policy(args.policy, seed=w.seed)
+        scripted = torch.from_numpy(np.ascontiguousarray(scenario["team"], np.uint8)).to("cuda:0")
 
     def tick(s):
         a = acts[s % n_act]
-        if args.separate:
+        if policy and args.separate:
+            env.heuristic_actions(policy, scripted, a, stream)
+            env.step_observe(a, stream)
+        elif policy:
+            env.policy_step_observe(policy, scripted, a, stream)
+        elif args.separate:
             env.step(a, stream)
             env.observe(stream)
         else:
@@ -135,6 +147,7 @@ def main() -> int:
         "config": {"workload": name, "num_envs": E, "units_per_env": N, "obs_dim": env.D,
                    "launch": "separate step+observe" if args.separate else "fused step_observe",
                    "body_collisions": bool(args.collisions),
+                   "scripted_adversaries": args.policy,
                    "actions": f"{n_act} pre-generated seeded uniform action batches, cycled"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
