@@ -828,6 +828,9 @@ __device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &
     return Z;
 }
 
+// Where 16-byte chunk c of the staged row images lives in LDS.
+__device__ __forceinline__ int staged_chunk(int c) { return c + (c >> 4); }
+
 template <int WAVES, bool CARRIED>
 __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *stg,
                                             const Place &P, const Unit &U, int code_u,
@@ -845,6 +848,11 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int wv = P.l >> 6;
     const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
     const int envs_here = envs_left < G ? envs_left : G;
+
+    // Blocks of 16 floats written by neighbouring lanes are 64 bytes apart, which would put every
+    // fourth lane on the same LDS banks; one spare 16-byte chunk after every 16 spreads them.
+    float4 *stage = reinterpret_cast<float4 *>(stg);
+    const bool blocks_aligned = (Dp & 15) == 0;  // every block then lies within one group of 16 chunks
 
     lds_barrier<WAVES>();                        // the step stage is done with the LDS union
 
@@ -954,23 +962,35 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             const float c13 = self ? U.cur_speed : (same_team ? 1.0f : 0.0f);
             const float c14 = self ? own_zone : (hit ? 1.0f : 0.0f);
             const float c15 = self ? own_team : U.cur_speed;
-            float4 *d = reinterpret_cast<float4 *>(stg + buf + blk_row0 + 16 * blk);
-            d[0] = make_float4(__int_as_float(__float_as_int(U.hp) & m),
-                               __int_as_float(__float_as_int(ratio) & m),
-                               __int_as_float(__float_as_int(c2) & m),
-                               __int_as_float(__float_as_int(c3) & m));
-            d[1] = make_float4(__int_as_float(__float_as_int(U.theta) & m),
-                               __int_as_float(__float_as_int(U.range) & m),
-                               __int_as_float(__float_as_int(U.dmg) & m),
-                               __int_as_float(__float_as_int(U.cd) & m));
-            d[2] = make_float4(__int_as_float(__float_as_int(cd_ratio) & m),
-                               __int_as_float(__float_as_int(U.radius) & m),
-                               __int_as_float(__float_as_int(U.mass) & m),
-                               __int_as_float(__float_as_int(U.sight_angle) & m));
-            d[3] = make_float4(__int_as_float(__float_as_int(c12) & m),
-                               __int_as_float(__float_as_int(c13) & m),
-                               __int_as_float(__float_as_int(c14) & m),
-                               __int_as_float(__float_as_int(c15) & m));
+            const float4 q0 = make_float4(__int_as_float(__float_as_int(U.hp) & m),
+                                          __int_as_float(__float_as_int(ratio) & m),
+                                          __int_as_float(__float_as_int(c2) & m),
+                                          __int_as_float(__float_as_int(c3) & m));
+            const float4 q1 = make_float4(__int_as_float(__float_as_int(U.theta) & m),
+                                          __int_as_float(__float_as_int(U.range) & m),
+                                          __int_as_float(__float_as_int(U.dmg) & m),
+                                          __int_as_float(__float_as_int(U.cd) & m));
+            const float4 q2 = make_float4(__int_as_float(__float_as_int(cd_ratio) & m),
+                                          __int_as_float(__float_as_int(U.radius) & m),
+                                          __int_as_float(__float_as_int(U.mass) & m),
+                                          __int_as_float(__float_as_int(U.sight_angle) & m));
+            const float4 q3 = make_float4(__int_as_float(__float_as_int(c12) & m),
+                                          __int_as_float(__float_as_int(c13) & m),
+                                          __int_as_float(__float_as_int(c14) & m),
+                                          __int_as_float(__float_as_int(c15) & m));
+            const int cb = (buf + blk_row0 + 16 * blk) >> 2;       // first 16-byte chunk of the block
+            if (blocks_aligned) {
+                float4 *d = stage + staged_chunk(cb);
+                d[0] = q0;
+                d[1] = q1;
+                d[2] = q2;
+                d[3] = q3;
+            } else {
+                stage[staged_chunk(cb)] = q0;
+                stage[staged_chunk(cb + 1)] = q1;
+                stage[staged_chunk(cb + 2)] = q2;
+                stage[staged_chunk(cb + 3)] = q3;
+            }
         }
         if (zone_lane) {
             const float4 Z = sh.ob.pose[zone_seer0 + i];
@@ -982,7 +1002,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 const float shift = __int_as_float((xb & zsx[k]) | (yb & zsy[k]));
                 zo[k] = __int_as_float(__float_as_int(zval[k] - shift) & en);
             }
-            *reinterpret_cast<float4 *>(stg + buf + zone_dst0) = make_float4(zo[0], zo[1], zo[2], zo[3]);
+            stage[staged_chunk((buf + zone_dst0) >> 2)] = make_float4(zo[0], zo[1], zo[2], zo[3]);
         }
     }
         lds_barrier<WAVES>();
@@ -990,13 +1010,17 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
         const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
         float *row = out + i0 * D;
+        // chunk t = p * LANES + lane of the staged rows sits at staged_chunk(t): LANES is a
+        // multiple of 16, so the passes are a constant stride apart
+        const float4 *src = stage + staged_chunk((buf >> 2) + P.l);
+        constexpr int PASS_STRIDE = LANES + LANES / 16;
         if (D == Dp) {
             // every chunk is whole: fetch all passes from LDS first, then issue the stores
             float4 v[kMaxPasses];
 #pragma unroll
             for (int p = 0; p < kMaxPasses; ++p)
                 if (p < a.copy_passes)
-                    v[p] = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
+                    v[p] = src[p * PASS_STRIDE];
 #pragma unroll
             for (int p = 0; p < kMaxPasses; ++p) {
                 if (p < a.copy_passes && valid[p] != 0) {
@@ -1015,7 +1039,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             for (int p = 0; p < kMaxPasses; ++p) {
                 const int vm = valid[p];
                 if (p < a.copy_passes && vm != 0) {
-                    const float4 v = *reinterpret_cast<const float4 *>(stg + buf + 4 * (p * LANES + P.l));
+                    const float4 v = src[p * PASS_STRIDE];
                     float *dp = row + dst_off[p];
                     if (vm == 15) {
                         f4u o = {v.x, v.y, v.z, v.w};
@@ -1240,6 +1264,8 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     size_t dyn_floats = rows_staged * a.row_pitch;
     const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
     if (dyn_floats < pass_floats) dyn_floats = pass_floats;
+    // ... with one spare 16-byte chunk after every 16 (see staged_chunk)
+    dyn_floats = 4 * ((dyn_floats + 3) / 4 + (dyn_floats + 3) / 64 + 1);
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
     const size_t zdesc_floats = a.p.zone_shapes == 1 ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
     const size_t dyn_bytes = (dyn_floats + zdesc_floats) * sizeof(float);
