@@ -25,7 +25,7 @@ class RefParams(C.Structure):
                [(n, C.c_float) for n in
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
-               [("zone_shapes", C.c_int)]
+               [("zone_shapes", C.c_int), ("num_levels", C.c_int), ("level_seed", C.c_uint)]
 
 
 _SC_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",
@@ -47,10 +47,14 @@ _METRICS = (("ret_run", _F, np.float32), ("kill_run", _I8, np.int8), ("ep_count"
             ("ep_first_kill", _I8, np.int8))
 
 
+_LEVELS = ("level", "next_level", "level_draws")
+
+
 class RefState(C.Structure):
     _fields_ = [(n, _F) for n in _ST_FLOAT] + [("alive", _B), ("t", C.POINTER(C.c_int)),
                                                 ("phi_prev", _F)] + \
-               [(n, t) for n, t, _ in _METRICS]
+               [(n, t) for n, t, _ in _METRICS] + \
+               [(n, _I32) for n in _LEVELS]
 
 
 class RefPolicy(C.Structure):
@@ -120,24 +124,26 @@ class RefEnv:
         self.metrics = metrics
         E, N = self.p["num_envs"], self.p["num_units"]
         self.E, self.N = E, N
+        L = self.p.get("num_levels", 0)
+        rows = L if L > 0 else E            # scenario rows: a bank of levels, or one per env
         self.sc = {}
         for k in _SC_FLOAT:
             a = np.ascontiguousarray(scenario[k], np.float32)
-            assert a.shape == (E, N), (k, a.shape)
+            assert a.shape == (rows, N), (k, a.shape)
             self.sc[k] = a
         for k in ("team", "enabled"):
             a = np.ascontiguousarray(scenario[k], np.uint8)
-            assert a.shape == (E, N)
+            assert a.shape == (rows, N)
             self.sc[k] = a
         ter = scenario.get("terrain")
         if ter is not None:
             ter = np.ascontiguousarray(ter, np.int8)
-            assert ter.shape == (E, self.p["grid_h"], self.p["grid_w"])
+            assert ter.shape == (rows, self.p["grid_h"], self.p["grid_w"])
         self.sc["terrain"] = ter
         zd = scenario.get("zone_desc")
         if zd is not None and self.p["max_zones"] > 0:
             zd = np.ascontiguousarray(zd, np.float32)
-            assert zd.shape == (E, self.p["max_zones"], 6)
+            assert zd.shape == (rows, self.p["max_zones"], 6)
         else:
             zd = None
         self.sc["zone_desc"] = zd
@@ -157,6 +163,10 @@ class RefEnv:
         if metrics:
             for n, _, dt in _METRICS:
                 self.st[n] = np.zeros(E, dt)
+        if L > 0:
+            self.st["level"] = np.zeros(E, np.int32)
+            self.st["next_level"] = (np.arange(E) % L).astype(np.int32)   # first episodes
+            self.st["level_draws"] = np.zeros(E, np.int32)
         self._bind_state()
         self.gstate = np.zeros((E, 16 * N + 6 * self.p["max_zones"]), np.float32)
         self.rewards = np.zeros((E, N), np.float32)
@@ -173,7 +183,9 @@ class RefEnv:
                             t=_ptr(self.st["t"], C.POINTER(C.c_int)),
                             phi_prev=_ptr(self.st["phi_prev"], _F),
                             **({n: _ptr(self.st[n], t) for n, t, _ in _METRICS}
-                               if self.metrics else {}))
+                               if self.metrics else {}),
+                            **({n: _ptr(self.st[n], _I32) for n in _LEVELS}
+                               if "level" in self.st else {}))
 
     def set_state(self, **arrays):
         """Overwrites state fields in place (hand-worked cases)."""

@@ -71,17 +71,58 @@ inline float clampf(float v, float lo, float hi)
     return v < lo ? lo : (v > hi ? hi : v);
 }
 
+/* Which row of the scenario arrays configures env e: its own (no level bank) or the level it
+ * currently plays (the configuration is applied at reset, Sec. 4.1; App. A "Environment
+ * Parameters"). */
+int level_of(const RefParams &P, const RefState &st, int e)
+{
+    return P.num_levels > 0 ? st.level[e] : e;
+}
+
+/* The scenario as env e sees it: every pointer moved to the row of its level, so that the
+ * per-env code below indexes unit arrays by unit, `terrain` by cell and `zone_desc` by slot. */
+RefScenario level_slice(const RefParams &P, const RefScenario &bank, const RefState &st, int e)
+{
+    const long row = level_of(P, st, e);
+    const long N = P.num_units;
+    RefScenario S = bank;
+    S.init_x += row * N;       S.init_y += row * N;       S.init_theta += row * N;
+    S.hmax += row * N;         S.radius += row * N;       S.mass += row * N;
+    S.speed += row * N;        S.dmg += row * N;          S.range += row * N;
+    S.cooldown += row * N;     S.sight_angle += row * N;  S.sight_cos_half += row * N;
+    S.sight_range += row * N;  S.hurt_halfwidth += row * N;
+    S.team += row * N;         S.enabled += row * N;
+    if (S.terrain) S.terrain += row * P.grid_h * P.grid_w;
+    if (S.zone_desc) S.zone_desc += row * P.max_zones * 6;
+    return S;
+}
+
+/* An episode of env e is about to start: it takes the level queued in next_level (any int is
+ * folded into [0, num_levels)), and the queue is refilled with a uniform draw, the
+ * counter-based hash of (level_seed, env, number of draws so far); the caller may overwrite
+ * the queued level at any time before the episode ends. */
+unsigned hash32(unsigned seed, unsigned env, unsigned unit, unsigned tick, unsigned draw);
+void advance_level(const RefParams &P, RefState &st, int e)
+{
+    if (P.num_levels <= 0) return;
+    const unsigned L = (unsigned)P.num_levels;
+    st.level[e] = (int)((unsigned)st.next_level[e] % L);
+    const unsigned n = (unsigned)st.level_draws[e];
+    st.next_level[e] = (int)(hash32(P.level_seed, (unsigned)e, 0u, n, 3u) % L);
+    st.level_draws[e] = (int)(n + 1u);
+}
+
 /* Zone code under a position: low two bits = zone type, upper bits = zone identity; 0 = open.
  * Cell-grid zones: the code stored in the cell.  Elliptical zones (App. A "Zones": type,
  * centre, two axes, effect magnitude): the last listed active zone whose ellipse
  * (x-cx)^2/hx^2 + (y-cy)^2/hy^2 <= 1 holds the point, tested without division as
  * (dx^2)*hy^2 + (dy^2)*hx^2 <= hx^2*hy^2; identity = slot index + 1. */
-int cell_code(const RefParams &P, const RefScenario &S, int e, float x, float y)
+int cell_code(const RefParams &P, const RefScenario &S, float x, float y)
 {
     if (P.zone_shapes == 1) {
         int code = 0;
         for (int z = 0; z < P.max_zones && S.zone_desc; ++z) {
-            const float *d = S.zone_desc + ((long)e * P.max_zones + z) * 6;
+            const float *d = S.zone_desc + (long)z * 6;
             if (d[0] == 0.0f) continue;
             float dx = x - d[1];
             float dy = y - d[2];
@@ -99,15 +140,15 @@ int cell_code(const RefParams &P, const RefScenario &S, int e, float x, float y)
     if (cy > P.grid_h - 1) cy = P.grid_h - 1;
     if (cx < 0) cx = 0;
     if (cy < 0) cy = 0;
-    return (int)S.terrain[((long)e * P.grid_h + cy) * P.grid_w + cx];
+    return (int)S.terrain[(long)cy * P.grid_w + cx];
 }
 
 /* Effect magnitude of the zone a code names: the zone's own (elliptical zones) or the
  * global parameter (cell grid). */
-float zone_effect(const RefParams &P, const RefScenario &S, int e, int code, float global_value)
+float zone_effect(const RefParams &P, const RefScenario &S, int code, float global_value)
 {
     if (P.zone_shapes == 1 && (code >> 2) > 0)
-        return S.zone_desc[((long)e * P.max_zones + ((code >> 2) - 1)) * 6 + 5];
+        return S.zone_desc[(long)((code >> 2) - 1) * 6 + 5];
     return global_value;
 }
 
@@ -120,8 +161,8 @@ float team_ratio(const RefParams &P, const RefScenario &S, const RefState &st,
     float sum = 0.0f;
     int   cnt = 0;
     for (int u = 0; u < N; ++u) {
-        if (!S.enabled[b + u] || S.team[b + u] != team) continue;
-        sum = sum + st.hp[b + u] / S.hmax[b + u];
+        if (!S.enabled[u] || S.team[u] != team) continue;
+        sum = sum + st.hp[b + u] / S.hmax[u];
         cnt += 1;
     }
     return cnt > 0 ? sum / (float)cnt : 0.0f;
@@ -132,18 +173,18 @@ void reset_env(const RefParams &P, const RefScenario &S, RefState &st, int e)
     const int N = P.num_units, b = e * N;
     for (int u = 0; u < N; ++u) {
         const int k = b + u;
-        st.x[k] = S.init_x[k];
-        st.y[k] = S.init_y[k];
-        st.theta[k] = S.init_theta[k];
+        st.x[k] = S.init_x[u];
+        st.y[k] = S.init_y[u];
+        st.theta[k] = S.init_theta[u];
         st.vx[k] = 0.0f;
         st.vy[k] = 0.0f;
-        st.hp[k] = S.enabled[k] ? S.hmax[k] : 0.0f;
+        st.hp[k] = S.enabled[u] ? S.hmax[u] : 0.0f;
         st.cd[k] = 0.0f;
         st.reveal[k] = 0.0f;
-        st.alive[k] = S.enabled[k] ? 1 : 0;
-        const int code = cell_code(P, S, e, st.x[k], st.y[k]);
+        st.alive[k] = S.enabled[u] ? 1 : 0;
+        const int code = cell_code(P, S, st.x[k], st.y[k]);
         st.cur_speed[k] = ((code & 3) == ZONE_SWAMP)
-                              ? S.speed[k] * zone_effect(P, S, e, code, P.swamp_mult) : S.speed[k];
+                              ? S.speed[u] * zone_effect(P, S, code, P.swamp_mult) : S.speed[u];
     }
     st.t[e] = 0;
     st.phi_prev[e] = team_ratio(P, S, st, e, 0) - team_ratio(P, S, st, e, 1);
@@ -177,10 +218,11 @@ inline bool role_allows(float dmg_i, int team_i, int team_j)
     return dmg_i < 0.0f ? (team_i == team_j) : (team_i != team_j);
 }
 
-void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
+void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
               const unsigned char *act, float *rewards, unsigned char *dones,
               double *min_margin)
 {
+    const RefScenario S = level_slice(P, bank, st, e);
     const int N = P.num_units, b = e * N;
     std::vector<unsigned char> alive0(N);
     std::vector<float> bdmg(N, 0.0f), c(N), s(N);
@@ -192,7 +234,7 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
     /* ---- stage 1: physics --------------------------------------------------- */
     for (int u = 0; u < N; ++u) {
         const int k = b + u;
-        if (!S.enabled[k]) continue;
+        if (!S.enabled[u]) continue;
         float v = st.cd[k] - P.dt;
         st.cd[k] = v > 0.0f ? v : 0.0f;
         v = st.reveal[k] - P.dt;
@@ -201,7 +243,7 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
         float x = st.x[k] + st.vx[k] * P.dt;
         float y = st.y[k] + st.vy[k] * P.dt;
         bool oob = (x < 0.0f) || (x > P.map_w) || (y < 0.0f) || (y > P.map_h);
-        if (oob) bdmg[u] = (P.boundary_frac * S.hmax[k]) * P.dt;
+        if (oob) bdmg[u] = (P.boundary_frac * S.hmax[u]) * P.dt;
         st.x[k] = clampf(x, 0.0f, P.map_w);
         st.y[k] = clampf(y, 0.0f, P.map_h);
     }
@@ -223,13 +265,13 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
             py[u] = st.y[b + u];
         }
         for (int i = 0; i < N; ++i) {
-            if (!S.enabled[b + i]) continue;
+            if (!S.enabled[i]) continue;
             for (int j = 0; j < N; ++j) {
-                if (j == i || !S.enabled[b + j]) continue;
+                if (j == i || !S.enabled[j]) continue;
                 float dx = px[j] - px[i];
                 float dy = py[j] - py[i];
                 float dist = std::sqrt((dx * dx) + (dy * dy));
-                float pen = (S.radius[b + i] + S.radius[b + j]) - dist;
+                float pen = (S.radius[i] + S.radius[j]) - dist;
                 if (!(pen > P.collision_slop)) continue;
                 float nx, ny;
                 if (dist > 0.0f) {
@@ -239,14 +281,14 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
                     nx = (i < j) ? 1.0f : -1.0f;
                     ny = 0.0f;
                 }
-                float share = S.mass[b + j] / (S.mass[b + i] + S.mass[b + j]);
+                float share = S.mass[j] / (S.mass[i] + S.mass[j]);
                 float c = ((pen - P.collision_slop) * P.collision_alpha) * share;
                 ax[i] = ax[i] - (c * nx);
                 ay[i] = ay[i] - (c * ny);
             }
         }
         for (int u = 0; u < N; ++u) {
-            if (!S.enabled[b + u]) continue;
+            if (!S.enabled[u]) continue;
             st.x[b + u] = clampf(px[u] + ax[u], 0.0f, P.map_w);
             st.y[b + u] = clampf(py[u] + ay[u], 0.0f, P.map_h);
         }
@@ -286,12 +328,12 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
         for (int j = 0; j < N; ++j) {
             if (j == i || !alive0[j]) continue;
             const int kj = b + j;
-            if (!role_allows(S.dmg[ki], S.team[ki], S.team[kj])) continue;
+            if (!role_allows(S.dmg[i], S.team[i], S.team[j])) continue;
             float d2;
             double m;
-            bool hit = hurtbox_hit(st.x[ki], st.y[ki], c[i], s[i], S.range[ki],
-                                   S.hurt_halfwidth[ki], st.x[kj], st.y[kj],
-                                   S.radius[kj], &d2, min_margin ? &m : nullptr);
+            bool hit = hurtbox_hit(st.x[ki], st.y[ki], c[i], s[i], S.range[i],
+                                   S.hurt_halfwidth[i], st.x[kj], st.y[kj],
+                                   S.radius[j], &d2, min_margin ? &m : nullptr);
             if (min_margin && m < min_margin[e]) min_margin[e] = m;
             if (hit && (target[i] < 0 || d2 < best)) {
                 target[i] = j;
@@ -305,7 +347,7 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
     for (int i = 0; i < N; ++i) {
         const int ki = b + i;
         bool elig = alive0[i] && act[ki] == ACT_ATTACK && st.cd[ki] <= 0.0f;
-        if (elig) st.cd[ki] = S.cooldown[ki];
+        if (elig) st.cd[ki] = S.cooldown[i];
         landed[i] = (elig && target[i] >= 0) ? 1 : 0;
     }
 
@@ -317,13 +359,13 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
         const int kj = b + j;
         float acc = 0.0f;
         for (int i = 0; i < N; ++i)
-            if (landed[i] && target[i] == j) acc = acc + S.dmg[b + i];
+            if (landed[i] && target[i] == j) acc = acc + S.dmg[i];
         float h = (st.hp[kj] - acc) - bdmg[j];
-        st.hp[kj] = clampf(h, 0.0f, S.hmax[kj]);
+        st.hp[kj] = clampf(h, 0.0f, S.hmax[j]);
     }
     /* combat reveal (bush rule): a landed damaging attack exposes both ends */
     for (int i = 0; i < N; ++i) {
-        if (landed[i] && S.dmg[b + i] > 0.0f) {
+        if (landed[i] && S.dmg[i] > 0.0f) {
             st.reveal[b + i] = P.reveal_time;
             st.reveal[b + target[i]] = P.reveal_time;
         }
@@ -332,15 +374,15 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
     /* ---- stage 3: zone effects, alive flags, reward, termination -------------- */
     for (int u = 0; u < N; ++u) {
         const int k = b + u;
-        if (!S.enabled[k]) { st.alive[k] = 0; continue; }
-        const int code = cell_code(P, S, e, st.x[k], st.y[k]);
+        if (!S.enabled[u]) { st.alive[k] = 0; continue; }
+        const int code = cell_code(P, S, st.x[k], st.y[k]);
         const int zone = code & 3;
         if (alive0[u] && zone == ZONE_LAVA) {
-            float h = st.hp[k] - (zone_effect(P, S, e, code, P.lava_dps) * P.dt);
+            float h = st.hp[k] - (zone_effect(P, S, code, P.lava_dps) * P.dt);
             st.hp[k] = h > 0.0f ? h : 0.0f;
         }
         st.cur_speed[k] = (zone == ZONE_SWAMP)
-                              ? S.speed[k] * zone_effect(P, S, e, code, P.swamp_mult) : S.speed[k];
+                              ? S.speed[u] * zone_effect(P, S, code, P.swamp_mult) : S.speed[u];
         st.alive[k] = st.hp[k] > 0.0f ? 1 : 0;
     }
     st.t[e] += 1;
@@ -353,8 +395,8 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
 
     int alive_cnt[2] = {0, 0}, before_cnt[2] = {0, 0};
     for (int u = 0; u < N; ++u) {
-        if (st.alive[b + u]) alive_cnt[S.team[b + u] ? 1 : 0] += 1;
-        if (alive0[u]) before_cnt[S.team[b + u] ? 1 : 0] += 1;
+        if (st.alive[b + u]) alive_cnt[S.team[u] ? 1 : 0] += 1;
+        if (alive0[u]) before_cnt[S.team[u] ? 1 : 0] += 1;
     }
     const bool done = alive_cnt[0] == 0 || alive_cnt[1] == 0 || st.t[e] >= P.max_steps;
     if (done) {
@@ -366,7 +408,7 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
     }
     for (int u = 0; u < N; ++u) {
         const int k = b + u;
-        rewards[k] = S.enabled[k] ? (S.team[k] ? r1 : r0) : 0.0f;
+        rewards[k] = S.enabled[u] ? (S.team[u] ? r1 : r0) : 0.0f;
     }
     dones[e] = done ? 1 : 0;
 
@@ -384,7 +426,10 @@ void step_env(const RefParams &P, const RefScenario &S, RefState &st, int e,
         if (st.ep_win) st.ep_win[e] = (ratio0 > ratio1) ? 1 : 0;
         if (st.ep_first_kill && st.kill_run) st.ep_first_kill[e] = st.kill_run[e];
     }
-    if (done) reset_env(P, S, st, e);
+    if (done) {
+        advance_level(P, st, e);
+        reset_env(P, level_slice(P, bank, st, e), st, e);
+    }
     else st.phi_prev[e] = phi;
 }
 
@@ -394,21 +439,21 @@ void own_block(const RefParams &P, const RefScenario &S, const RefState &st, int
 {
     const int k = e * P.num_units + u;
     row[0] = st.hp[k];
-    row[1] = st.hp[k] / S.hmax[k];
+    row[1] = st.hp[k] / S.hmax[u];
     row[2] = st.x[k];
     row[3] = st.y[k];
     row[4] = st.theta[k];
-    row[5] = S.range[k];
-    row[6] = S.dmg[k];
+    row[5] = S.range[u];
+    row[6] = S.dmg[u];
     row[7] = st.cd[k];
-    row[8] = S.cooldown[k] != 0.0f ? st.cd[k] / S.cooldown[k] : 0.0f;
-    row[9] = S.radius[k];
-    row[10] = S.mass[k];
-    row[11] = S.sight_angle[k];
+    row[8] = S.cooldown[u] != 0.0f ? st.cd[k] / S.cooldown[u] : 0.0f;
+    row[9] = S.radius[u];
+    row[10] = S.mass[u];
+    row[11] = S.sight_angle[u];
     row[12] = st.alive[k] ? 1.0f : 0.0f;
     row[13] = st.cur_speed[k];
     row[14] = (float)(code & 3);
-    row[15] = (float)S.team[k];
+    row[15] = (float)S.team[u];
 }
 
 void global_state_env(const RefParams &P, const RefScenario &S, const RefState &st, int e,
@@ -418,11 +463,11 @@ void global_state_env(const RefParams &P, const RefScenario &S, const RefState &
     for (int o = 0; o < 16 * N + 6 * Z; ++o) out[o] = 0.0f;
     for (int u = 0; u < N; ++u) {
         const int k = e * N + u;
-        if (!S.enabled[k]) continue;
-        own_block(P, S, st, e, u, cell_code(P, S, e, st.x[k], st.y[k]), out + 16 * u);
+        if (!S.enabled[u]) continue;
+        own_block(P, S, st, e, u, cell_code(P, S, st.x[k], st.y[k]), out + 16 * u);
     }
     for (int z = 0; z < Z && S.zone_desc; ++z) {
-        const float *d = S.zone_desc + ((long)e * Z + z) * 6;
+        const float *d = S.zone_desc + (long)z * 6;
         if (d[0] == 0.0f) continue;
         for (int c = 0; c < 6; ++c) out[16 * N + 6 * z + c] = d[c];
     }
@@ -446,11 +491,11 @@ PairView pair_view(const RefParams &P, const RefScenario &S, const RefState &st,
     V.dx = st.x[kj] - st.x[ki];
     V.dy = st.y[kj] - st.y[ki];
     V.d2 = (V.dx * V.dx) + (V.dy * V.dy);
-    float R = S.sight_range[ki];
+    float R = S.sight_range[i];
     bool in_range = V.d2 <= R * R;
     float dot = (V.dx * ci) + (V.dy * si);
     float dist = std::sqrt(V.d2);
-    bool in_cone = (V.d2 == 0.0f) || (dot >= S.sight_cos_half[ki] * dist);
+    bool in_cone = (V.d2 == 0.0f) || (dot >= S.sight_cos_half[i] * dist);
     if (margin) {
         double m = std::fabs((double)dist - (double)R);
         if (m < *margin) *margin = m;
@@ -458,12 +503,12 @@ PairView pair_view(const RefParams &P, const RefScenario &S, const RefState &st,
             double cosang = (double)dot / (double)dist;
             if (cosang > 1.0) cosang = 1.0;
             if (cosang < -1.0) cosang = -1.0;
-            double half = std::acos((double)S.sight_cos_half[ki]);
+            double half = std::acos((double)S.sight_cos_half[i]);
             m = std::fabs(std::acos(cosang) - half);
             if (in_range && m < *margin) *margin = m;
         }
     }
-    V.same_team = S.team[ki] == S.team[kj];
+    V.same_team = S.team[i] == S.team[j];
     bool bush_j = (code_j & 3) == ZONE_BUSH;
     bool same_bush = bush_j && (code_i & 3) == ZONE_BUSH && code_i == code_j;
     bool concealed = bush_j && !V.same_team && !same_bush && !(st.reveal[kj] > 0.0f);
@@ -471,9 +516,9 @@ PairView pair_view(const RefParams &P, const RefScenario &S, const RefState &st,
 
     float d2h;
     double mh;
-    bool overlap = hurtbox_hit(st.x[ki], st.y[ki], ci, si, S.range[ki], S.hurt_halfwidth[ki],
-                               st.x[kj], st.y[kj], S.radius[kj], &d2h, margin ? &mh : nullptr);
-    bool allowed = role_allows(S.dmg[ki], S.team[ki], S.team[kj]);
+    bool overlap = hurtbox_hit(st.x[ki], st.y[ki], ci, si, S.range[i], S.hurt_halfwidth[i],
+                               st.x[kj], st.y[kj], S.radius[j], &d2h, margin ? &mh : nullptr);
+    bool allowed = role_allows(S.dmg[i], S.team[i], S.team[j]);
     if (margin && allowed && mh < *margin) *margin = mh;
     V.attackable = overlap && allowed;
     return V;
@@ -490,7 +535,7 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
     std::vector<int> code(N);
     for (int u = 0; u < N; ++u) {
         sincos_spec(st.theta[b + u], &s[u], &c[u]);
-        code[u] = cell_code(P, S, e, st.x[b + u], st.y[b + u]);
+        code[u] = cell_code(P, S, st.x[b + u], st.y[b + u]);
     }
 
     for (int i = 0; i < N; ++i) {
@@ -501,7 +546,7 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
             for (int w = 0; w < words; ++w) vis_mask[(long)ki * words + w] = 0ull;
         if (action_mask)
             action_mask[ki] = (st.alive[ki] && st.cd[ki] <= 0.0f) ? 1 : 0;
-        if (!S.enabled[ki]) continue;
+        if (!S.enabled[i]) continue;
 
         /* own block */
         own_block(P, S, st, e, i, code[i], row);
@@ -523,17 +568,17 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
             if (!visible) continue;
             if (vis_mask) vis_mask[(long)ki * words + (j >> 6)] |= 1ull << (j & 63);
             o[0] = st.hp[kj];
-            o[1] = st.hp[kj] / S.hmax[kj];
+            o[1] = st.hp[kj] / S.hmax[j];
             o[2] = dx;
             o[3] = dy;
             o[4] = st.theta[kj];
-            o[5] = S.range[kj];
-            o[6] = S.dmg[kj];
+            o[5] = S.range[j];
+            o[6] = S.dmg[j];
             o[7] = st.cd[kj];
-            o[8] = S.cooldown[kj] != 0.0f ? st.cd[kj] / S.cooldown[kj] : 0.0f;
-            o[9] = S.radius[kj];
-            o[10] = S.mass[kj];
-            o[11] = S.sight_angle[kj];
+            o[8] = S.cooldown[j] != 0.0f ? st.cd[kj] / S.cooldown[j] : 0.0f;
+            o[9] = S.radius[j];
+            o[10] = S.mass[j];
+            o[11] = S.sight_angle[j];
             o[12] = 1.0f;
             o[13] = same_team ? 1.0f : 0.0f;
             o[14] = attackable ? 1.0f : 0.0f;
@@ -543,7 +588,7 @@ void observe_env(const RefParams &P, const RefScenario &S, const RefState &st, i
         /* zone descriptor slots; an inactive slot (type 0) stays zero */
         for (int z = 0; z < Z; ++z) {
             if (!S.zone_desc) break;
-            const float *d = S.zone_desc + ((long)e * Z + z) * 6;
+            const float *d = S.zone_desc + (long)z * 6;
             float *o = row + 16 * N + 6 * z;
             if (d[0] == 0.0f) continue;
             o[0] = d[0];
@@ -593,9 +638,9 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
                 const std::vector<int> &code)
 {
     const int N = P.num_units, b = e * N, ki = b + i;
-    const bool healer = S.dmg[ki] < 0.0f;
-    const bool assassin = S.speed[ki] >= pol.assassin_speed;
-    const bool ranger = S.range[ki] >= pol.ranger_range;
+    const bool healer = S.dmg[i] < 0.0f;
+    const bool assassin = S.speed[i] >= pol.assassin_speed;
+    const bool ranger = S.range[i] >= pol.ranger_range;
 
     /* target selection among the visible units; nearest visible enemy; anything in reach */
     int tgt = -1, near_enemy = -1;
@@ -607,7 +652,7 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
         if (!V.visible) continue;
         /* the combat action is worth taking: an enemy in the hurtbox, or for a healer an
          * ally there that is below its maximum health */
-        if (V.attackable && (!healer || st.hp[b + j] < S.hmax[b + j])) can_hit = true;
+        if (V.attackable && (!healer || st.hp[b + j] < S.hmax[j])) can_hit = true;
         if (!V.same_team && (near_enemy < 0 || V.d2 < near_d2)) {
             near_enemy = j;
             near_d2 = V.d2;
@@ -615,22 +660,22 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
         bool better = false;
         if (healer) {          /* nearest injured ally, else nearest ally */
             if (V.same_team) {
-                const bool injured = st.hp[b + j] < S.hmax[b + j];
+                const bool injured = st.hp[b + j] < S.hmax[j];
                 better = tgt < 0 || (injured && !tgt_injured) ||
                          (injured == tgt_injured && V.d2 < tgt_d2);
                 if (better) tgt_injured = injured;
             }
         } else if (assassin) { /* lowest maximum health, then nearest */
             if (!V.same_team)
-                better = tgt < 0 || S.hmax[b + j] < tgt_h ||
-                         (S.hmax[b + j] == tgt_h && V.d2 < tgt_d2);
+                better = tgt < 0 || S.hmax[j] < tgt_h ||
+                         (S.hmax[j] == tgt_h && V.d2 < tgt_d2);
         } else {               /* nearest enemy */
             if (!V.same_team) better = tgt < 0 || V.d2 < tgt_d2;
         }
         if (better) {
             tgt = j;
             tgt_d2 = V.d2;
-            tgt_h = S.hmax[b + j];
+            tgt_h = S.hmax[j];
             tgt_in_box = V.attackable;
         }
     }
@@ -646,9 +691,9 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
         mem.mem_valid[ki] = 1;
         const float tdx = st.x[kt] - st.x[ki];
         const float tdy = st.y[kt] - st.y[ki];
-        const float reach = S.range[ki] + S.radius[kt];
+        const float reach = S.range[i] + S.radius[tgt];
         const bool within = tgt_d2 <= reach * reach;
-        const float kite = pol.xi * S.range[ki];
+        const float kite = pol.xi * S.range[i];
         if (can_hit && st.cd[ki] <= 0.0f) {
             act = ACT_ATTACK;
         } else if (within && !tgt_in_box) {
@@ -664,7 +709,7 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
             /* Assassins go behind the target, Healers to it, the rest in front of it */
             float ct, st_;
             sincos_spec(st.theta[kt], &st_, &ct);
-            const float standoff = 0.5f * S.range[ki];
+            const float standoff = 0.5f * S.range[i];
             float gx = st.x[kt], gy = st.y[kt];
             if (!healer) {
                 if (assassin) {
@@ -692,7 +737,7 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
         float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
         if (ranger && (code[i] & 3) != ZONE_BUSH && S.zone_desc) {
             for (int z = 0; z < P.max_zones; ++z) {
-                const float *d = S.zone_desc + ((long)e * P.max_zones + z) * 6;
+                const float *d = S.zone_desc + (long)z * 6;
                 if ((int)d[0] != ZONE_BUSH) continue;
                 const float zx = d[1] - st.x[ki];
                 const float zy = d[2] - st.y[ki];
@@ -724,11 +769,11 @@ void policy_env(const RefParams &P, const RefScenario &S, const RefState &st,
     std::vector<int> code(N);
     for (int u = 0; u < N; ++u) {
         sincos_spec(st.theta[b + u], &s[u], &c[u]);
-        code[u] = cell_code(P, S, e, st.x[b + u], st.y[b + u]);
+        code[u] = cell_code(P, S, st.x[b + u], st.y[b + u]);
     }
     for (int i = 0; i < N; ++i) {
         const int ki = b + i;
-        if (!controlled[ki] || !S.enabled[ki] || !st.alive[ki]) continue;
+        if (!controlled[ki] || !S.enabled[i] || !st.alive[ki]) continue;
         actions[ki] = (unsigned char)policy_unit(P, S, st, pol, mem, e, i, c, s, code);
     }
 }
@@ -747,7 +792,7 @@ void tabx_ref_heuristic_actions(const RefParams *p, const RefScenario *sc, const
                                 const unsigned char *controlled, unsigned char *actions)
 {
     for (int e = 0; e < p->num_envs; ++e)
-        policy_env(*p, *sc, *st, *pol, *mem, e, controlled, actions);
+        policy_env(*p, level_slice(*p, *sc, *st, e), *st, *pol, *mem, e, controlled, actions);
 }
 
 
@@ -767,7 +812,10 @@ void tabx_ref_reset(const RefParams *p, const RefScenario *sc, RefState *st,
                     const unsigned char *env_mask)
 {
     for (int e = 0; e < p->num_envs; ++e)
-        if (!env_mask || env_mask[e]) reset_env(*p, *sc, *st, e);
+        if (!env_mask || env_mask[e]) {
+            advance_level(*p, *st, e);
+            reset_env(*p, level_slice(*p, *sc, *st, e), *st, e);
+        }
 }
 
 void tabx_ref_step(const RefParams *p, const RefScenario *sc, RefState *st,
@@ -783,14 +831,14 @@ void tabx_ref_observe(const RefParams *p, const RefScenario *sc, const RefState 
                       unsigned char *action_mask, double *min_margin)
 {
     for (int e = 0; e < p->num_envs; ++e)
-        observe_env(*p, *sc, *st, e, obs, vis_mask, action_mask, min_margin);
+        observe_env(*p, level_slice(*p, *sc, *st, e), *st, e, obs, vis_mask, action_mask, min_margin);
 }
 
 void tabx_ref_global_state(const RefParams *p, const RefScenario *sc, const RefState *st,
                            float *out)
 {
     const long Dg = 16 * p->num_units + 6 * p->max_zones;
-    for (int e = 0; e < p->num_envs; ++e) global_state_env(*p, *sc, *st, e, out + e * Dg);
+    for (int e = 0; e < p->num_envs; ++e) global_state_env(*p, level_slice(*p, *sc, *st, e), *st, e, out + e * Dg);
 }
 
 } /* extern "C" */

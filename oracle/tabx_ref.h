@@ -42,6 +42,10 @@ typedef struct RefParams {
     float collision_slop;       /* overlap tolerated without correction */
     int   zone_shapes;          /* 0: zones are the cells of `terrain`; 1: zones are the ellipses of
                                    zone_desc (centre, semi-axes, own effect magnitude)           */
+    int   num_levels;           /* 0: row e of the scenario arrays configures env e.  L > 0: the
+                                   scenario arrays are a bank of L levels and env e plays row
+                                   level[e], re-drawn whenever one of its episodes starts        */
+    unsigned level_seed;        /* of the uniform level draws                                    */
 } RefParams;
 
 typedef struct RefScenario {
@@ -49,8 +53,8 @@ typedef struct RefScenario {
     const float *hmax, *radius, *mass, *speed, *dmg, *range, *cooldown;
     const float *sight_angle, *sight_cos_half, *sight_range, *hurt_halfwidth;
     const unsigned char *team, *enabled;
-    const signed char   *terrain;    /* [E][grid_h][grid_w] or NULL */
-    const float         *zone_desc;  /* [E][max_zones][6] or NULL   */
+    const signed char   *terrain;    /* [rows][grid_h][grid_w] or NULL */
+    const float         *zone_desc;  /* [rows][max_zones][6] or NULL   */
 } RefScenario;
 
 typedef struct RefState {
@@ -68,6 +72,10 @@ typedef struct RefState {
     float *ep_return;        /* allied return of the last finished episode             */
     signed char *ep_win;     /* 1 if the allies won it                                 */
     signed char *ep_first_kill; /* kill_run at its end                                 */
+    /* level bank (num_levels > 0), all [E]: the level being played, the level the next
+     * episode will take (refilled with a uniform draw when it is taken; the caller may
+     * overwrite it), and how many draws the env has made */
+    int   *level, *next_level, *level_draws;
 } RefState;
 
 int  tabx_ref_obs_dim(const RefParams *p);
