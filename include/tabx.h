@@ -16,7 +16,8 @@
  *    frees nothing and keeps no global state; it borrows the pointers until the
  *    enqueued work has finished on `stream`.
  *  - Per-unit arrays are struct-of-arrays, one array per field, indexed
- *    [e * N + u].  float arrays must be 4-byte aligned, `obs` and `vis_mask`
+ *    [e * N + u] (scenario arrays: [row * N + u] with row = e, or the env's level when a
+ *    level bank is used, see TabxParams.num_levels).  float arrays must be 4-byte aligned, `obs` and `vis_mask`
  *    16-byte aligned.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls validate their arguments on the host, enqueue kernels and return
@@ -89,6 +90,17 @@ typedef struct TabxParams {
      * belongs to the last listed active zone with (dx^2)*hy^2 + (dy^2)*hx^2 <= hx^2*hy^2, and
      * two units share a bush iff they are in the same slot. */
     int32_t zone_shapes;
+    /* Per-episode reconfiguration (Sec. 4.1, App. A "Environment Parameters": the configuration
+     * is applied when an episode starts, without rebuilding anything).  0: row e of the scenario
+     * arrays configures env e for good.  L > 0: the scenario arrays are a bank of L levels
+     * ([L * N] per unit field, terrain [L][grid_h][grid_w], zone_desc [L][max_zones][6]) and env e
+     * plays row state->level[e].  Whenever an episode of env e starts (tabx_reset, or the
+     * auto-reset inside a step) it takes level (uint32) next_level[e] mod L, and next_level[e]
+     * is refilled with a uniform draw: hash32(level_seed, e, 0, level_draws[e]++, 3) mod L, the
+     * hash of tabx_heuristic_actions.  The caller may overwrite next_level between calls (a
+     * curriculum) or leave the draws alone (domain randomisation). */
+    int32_t  num_levels;
+    uint32_t level_seed;
 } TabxParams;
 
 /* The scenario: unit specifications and zones (the unit and zone axes of the
@@ -127,6 +139,12 @@ typedef struct TabxState {
     float   *ep_return;      /* allied return of the last finished episode              */
     int8_t  *ep_win;         /* 1 if the allies won it                                  */
     int8_t  *ep_first_kill;  /* kill_run at its end                                     */
+    /* Level bank, required iff params->num_levels > 0, all [E] (see TabxParams.num_levels).
+     * The caller initialises next_level (and level_draws, normally to 0) before the first
+     * tabx_reset; `level` is written by the library. */
+    int32_t *level;          /* the level the env is playing                            */
+    int32_t *next_level;     /* the level its next episode will take                    */
+    int32_t *level_draws;    /* how many uniform draws the env has made                 */
 } TabxState;
 
 /* Floats per agent observation: 16 * N + 6 * max_zones.

@@ -35,13 +35,16 @@ METRICS = (("ret_run", _F, torch.float32), ("kill_run", _I8, torch.int8),
            ("ep_first_kill", _I8, torch.int8))
 
 
+LEVELS = ("level", "next_level", "level_draws")
+
+
 class TabxParams(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("num_envs", "num_units", "grid_w", "grid_h", "max_zones", "max_steps")] + \
                [(n, C.c_float) for n in
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
-               [("zone_shapes", C.c_int32)]
+               [("zone_shapes", C.c_int32), ("num_levels", C.c_int32), ("level_seed", C.c_uint32)]
 
 
 class TabxScenario(C.Structure):
@@ -53,7 +56,8 @@ class TabxScenario(C.Structure):
 class TabxState(C.Structure):
     _fields_ = [(n, _F) for n in STATE_FLOAT] + \
                [("alive", _U8), ("t", C.POINTER(C.c_int32)), ("phi_prev", _F)] + \
-               [(n, t) for n, t, _ in METRICS]
+               [(n, t) for n, t, _ in METRICS] + \
+               [(n, _I32) for n in LEVELS]
 
 
 class TabxError(RuntimeError):
@@ -187,6 +191,8 @@ class TabxEnv:
         self.params = make_params(self.p)
         E, N = self.p["num_envs"], self.p["num_units"]
         self.E, self.N = E, N
+        L = self.p.get("num_levels", 0)
+        rows = L if L > 0 else E           # scenario rows: a bank of levels, or one per env
         self.D = tabx_obs_dim(self.params)
         self.words = (N + 63) // 64
         dev = self.device
@@ -194,9 +200,9 @@ class TabxEnv:
         def up(a, dtype):
             return torch.as_tensor(a, dtype=dtype).contiguous().to(dev)
 
-        self.sc = {k: up(scenario[k], torch.float32).reshape(E * N) for k in SCENARIO_FLOAT}
-        self.sc["team"] = up(scenario["team"], torch.uint8).reshape(E * N)
-        self.sc["enabled"] = up(scenario["enabled"], torch.uint8).reshape(E * N)
+        self.sc = {k: up(scenario[k], torch.float32).reshape(rows * N) for k in SCENARIO_FLOAT}
+        self.sc["team"] = up(scenario["team"], torch.uint8).reshape(rows * N)
+        self.sc["enabled"] = up(scenario["enabled"], torch.uint8).reshape(rows * N)
         ter = scenario.get("terrain")
         self.sc["terrain"] = None if ter is None else up(ter, torch.int8)
         zd = scenario.get("zone_desc") if self.p["max_zones"] > 0 else None
@@ -214,6 +220,10 @@ class TabxEnv:
         self.metrics = {}
         if want_metrics:
             self.metrics = {n: torch.zeros(E, dtype=dt, device=dev) for n, _, dt in METRICS}
+        if L > 0:
+            self.st["level"] = torch.zeros(E, dtype=torch.int32, device=dev)
+            self.st["next_level"] = (torch.arange(E, device=dev) % L).to(torch.int32)
+            self.st["level_draws"] = torch.zeros(E, dtype=torch.int32, device=dev)
         self.state = self._state_struct(self.st, self.metrics)
         self.gstate = None
         self.memory = None
@@ -232,7 +242,8 @@ class TabxEnv:
                          alive=_cast(st["alive"], _U8),
                          t=_cast(st["t"], C.POINTER(C.c_int32)),
                          phi_prev=_cast(st["phi_prev"], _F),
-                         **{n: _cast(metrics[n], t) for n, t, _ in METRICS if n in metrics})
+                         **{n: _cast(metrics[n], t) for n, t, _ in METRICS if n in metrics},
+                         **{n: _cast(st[n], _I32) for n in LEVELS if n in st})
 
     def global_state(self, stream=None):
         if self.gstate is None:
@@ -290,5 +301,6 @@ class TabxEnv:
         out = {}
         for k, v in self.st.items():
             a = v.cpu().numpy()
-            out[k] = a if k in ("t", "phi_prev") else a.reshape(self.E, self.N)
+            per_env = k in ("t", "phi_prev") or k in LEVELS
+            out[k] = a if per_env else a.reshape(self.E, self.N)
         return out

@@ -129,6 +129,8 @@ struct Place {
     int l, g, u, base, e;
     bool has;
     size_t k;
+    int row;           // row of the scenario arrays that configures env e (its level, or e itself)
+    size_t ks;         // row * N + u
 };
 
 template <int WAVES>
@@ -153,6 +155,7 @@ struct Shared {
                                   // (policy stage: alive | team<<1 | concealable<<2 | bush key<<8)
     uint64_t rowbits[WAVES == 1 ? 1 : L][WAVES];   // two-wave workgroups: ballots of "observer i sees lane"
     uint64_t ballots[WAVES][4];
+    int      rows[WAVES == 1 ? 64 : 1];   // level bank: the row an env slot has just switched to, or -1
 };
 
 // Orders LDS traffic between the lanes of a workgroup without waiting for global
@@ -176,8 +179,9 @@ __device__ __forceinline__ void lds_barrier()
 // Cell-grid zones: the code stored in the cell.  Elliptical zones (App. A "Zones"): the last
 // listed active zone whose ellipse holds the point, tested without division as
 // (dx^2)*hy^2 + (dy^2)*hx^2 <= hx^2*hy^2; identity = slot index + 1, and `own_effect` returns
-// that zone's effect magnitude.  `zd` = the env's zone descriptors (LDS or global).
-__device__ __forceinline__ int zone_at(const KArgs &a, const float *zd, int e, float x, float y,
+// that zone's effect magnitude.  `zd` = the env's zone descriptors (LDS or global), `row` = its
+// row of the scenario arrays.
+__device__ __forceinline__ int zone_at(const KArgs &a, const float *zd, int row, float x, float y,
                                        float &own_effect)
 {
     if (a.p.zone_shapes == 1) {
@@ -203,7 +207,7 @@ __device__ __forceinline__ int zone_at(const KArgs &a, const float *zd, int e, f
     cy = cy > a.p.grid_h - 1 ? a.p.grid_h - 1 : cy;
     cx = cx < 0 ? 0 : cx;
     cy = cy < 0 ? 0 : cy;
-    return (int)a.sc.terrain[((size_t)e * a.p.grid_h + cy) * a.p.grid_w + cx];
+    return (int)a.sc.terrain[((size_t)row * a.p.grid_h + cy) * a.p.grid_w + cx];
 }
 
 // Effect magnitude that applies in the zone just found: its own (elliptical zones) or the
@@ -260,19 +264,19 @@ __device__ __forceinline__ void store_state(const KArgs &a, size_t k, const Unit
 
 // Episode start for one unit: spawn pose, full health, timers cleared.  Returns
 // the terrain cell code under the spawn point.
-__device__ __forceinline__ int spawn_unit(const KArgs &a, const float *zd, int e, size_t k,
+__device__ __forceinline__ int spawn_unit(const KArgs &a, const float *zd, int row, size_t ks,
                                           Unit &U, float &zeff)
 {
-    U.x = a.sc.init_x[k];
-    U.y = a.sc.init_y[k];
-    U.theta = a.sc.init_theta[k];
+    U.x = a.sc.init_x[ks];
+    U.y = a.sc.init_y[ks];
+    U.theta = a.sc.init_theta[ks];
     U.vx = 0.0f;
     U.vy = 0.0f;
     U.hp = U.enabled ? U.hmax : 0.0f;
     U.cd = 0.0f;
     U.reveal = 0.0f;
     U.alive = U.enabled ? 1 : 0;
-    const int code = zone_at(a, zd, e, U.x, U.y, zeff);
+    const int code = zone_at(a, zd, row, U.x, U.y, zeff);
     U.cur_speed = (code & 3) == TABX_ZONE_SWAMP
                       ? U.speed * zone_magnitude(a, zeff, a.p.swamp_mult) : U.speed;
     return code;
@@ -299,6 +303,12 @@ __device__ __forceinline__ Place locate(const KArgs &a)
     P.has = P.grp < a.num_groups && P.g < a.envs_per_block && P.u < N && P.e < a.p.num_envs;
     P.base = P.has ? P.l - P.u : 0;
     P.k = (size_t)P.e * N + P.u;
+    P.row = P.e;
+    if (a.p.num_levels > 0) {      // folded into the bank whatever the array holds
+        const int lv = P.has ? a.st.level[P.e] : 0;
+        P.row = lv < 0 ? 0 : (lv >= a.p.num_levels ? a.p.num_levels - 1 : lv);
+    }
+    P.ks = (size_t)P.row * N + P.u;
     return P;
 }
 
@@ -506,7 +516,7 @@ __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, con
             int bush = -1;
             float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
             if (ranger && !in_bush && a.sc.zone_desc) {
-                const float *zd = a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones;
+                const float *zd = a.sc.zone_desc + (size_t)P.row * 6 * a.p.max_zones;
                 for (int z = 0; z < a.p.max_zones; ++z) {
                     const float *d = zd + 6 * z;
                     if ((int)d[0] != TABX_ZONE_BUSH) continue;
@@ -534,10 +544,36 @@ __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, con
     return act;
 }
 
-// `forced` >= 0 replaces the unit's entry of the action array (the policy stage chose it).
+// Level bank: an episode of the lane's env is about to start (`take`, uniform over the env's
+// lanes).  Unit 0 takes the queued level (folded into [0, num_levels)), refills the queue with
+// a uniform draw, the hash of (level_seed, env, draws so far), and tells the env's other lanes
+// through LDS.  Returns the env's new row, or -1 if it keeps its level.  All lanes call it.
 template <int WAVES>
-__device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, const float *zd,
-                                         const Place &P, Unit &U, int &code_u, Carry &C, int forced)
+__device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, const Place &P,
+                                             bool take)
+{
+    if (P.has && P.u == 0) {
+        int row = -1;
+        if (take) {
+            const uint32_t L = (uint32_t)a.p.num_levels;
+            row = (int)((uint32_t)a.st.next_level[P.e] % L);
+            const uint32_t n = (uint32_t)a.st.level_draws[P.e];
+            a.st.level[P.e] = row;
+            a.st.next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)P.e, 0u, n, 3u) % L);
+            a.st.level_draws[P.e] = (int)(n + 1u);
+        }
+        sh.rows[P.g] = row;
+    }
+    lds_barrier<WAVES>();
+    return P.has ? sh.rows[P.g] : -1;
+}
+
+// `forced` >= 0 replaces the unit's entry of the action array (the policy stage chose it).
+// `zd`: the env's zone descriptors in LDS (elliptical zones), rewritten when the env changes
+// level.  Returns whether any env of the workgroup restarted.
+template <int WAVES>
+__device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, float *zd,
+                                         Place &P, Unit &U, int &code_u, Carry &C, int forced)
 {
     float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
     const int N = a.p.num_units;
@@ -601,7 +637,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
 
     // the position is final for this tick: fetch the terrain cell under it now, the zone
     // effects of stage 3 use it after the combat exchange
-    if (has && U.enabled) code_u = zone_at(a, zd, P.e, U.x, U.y, zeff);
+    if (has && U.enabled) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff);
 
     // stage 2a: movement sets next tick's velocity, rotation turns the heading now
     float cu = 1.0f, su = 0.0f;
@@ -738,17 +774,42 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
     float phi_next = phi;
     lds_barrier<WAVES>();          // everyone has read the ratio terms of the finished tick
     if (any_done) {
+        bool en_next = en;
+        if (a.p.num_levels > 0) {
+            // the finished envs move to their queued level: new specifications, new zones
+            const int row = advance_level<WAVES>(a, sh, P, done);
+            if (row >= 0) {
+                P.row = row;
+                P.ks = (size_t)row * N + P.u;
+                load_spec(a, P.ks, U);
+                en_next = U.enabled != 0;
+                if (a.p.zone_shapes == 1) {
+                    const int zlen = 6 * a.p.max_zones;
+                    for (int q = P.u; q < zlen; q += N) zd[q] = a.sc.zone_desc[(size_t)row * zlen + q];
+                }
+            }
+            if (a.p.zone_shapes == 1) lds_barrier<WAVES>();
+        }
         if (done) {
             if (a.pa.mem.mem_valid) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
-            code_u = spawn_unit(a, zd, P.e, P.k, U, zeff);
+            code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
         }
-        sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
-                                    (en && U.team != 0) ? ratio : 0.0f);
+        int c0 = cnt[0], c1 = cnt[1];
+        if (a.p.num_levels > 0) {
+            // teams and placeholders may differ in the new level
+            const bool pred1[4] = {en_next && U.team == 0, en_next && U.team != 0, false, false};
+            int fresh[4];
+            env_counts(sh, P, N, pred1, fresh);
+            c0 = fresh[0];
+            c1 = fresh[1];
+        }
+        sh.st.share[P.l] = make_float2((en_next && U.team == 0) ? ratio : 0.0f,
+                                    (en_next && U.team != 0) ? ratio : 0.0f);
         lds_barrier<WAVES>();
         float f0, f1;
-        team_means(sh, P, N, cnt[0], cnt[1], f0, f1);
+        team_means(sh, P, N, c0, c1, f0, f1);
         if (done) phi_next = f0 - f1;
     }
     if (has && P.u == 0) {
@@ -779,6 +840,7 @@ __device__ __forceinline__ void step_env(const KArgs &a, Shared<WAVES> &sh, cons
     C.cu = cu;
     C.su = su;
     C.ratio = ratio;
+    return any_done;
 }
 
 // Observation rows of every unit of the workgroup's envs, visibility masks, action masks.
@@ -800,8 +862,16 @@ struct ZoneRegs {
 
 // Issued at the top of the kernel so that the descriptor loads are long done when the
 // observe stage needs them.
+// Row of the scenario arrays that configures env `env`.
+__device__ __forceinline__ int row_of(const KArgs &a, int env)
+{
+    if (a.p.num_levels <= 0) return env;
+    const int lv = a.st.level[env];
+    return lv < 0 ? 0 : (lv >= a.p.num_levels ? a.p.num_levels - 1 : lv);
+}
+
 template <int WAVES>
-__device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &P)
+__device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &P, int row_override = -1)
 {
     ZoneRegs Z = {};
     const int G = a.envs_per_block;
@@ -812,7 +882,8 @@ __device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &
     Z.zc = P.l - Z.zg * ZC;
     Z.lane = ZC > 0 && Z.zg < (envs_left < G ? envs_left : G);
     if (Z.lane) {
-        const float *d = a.sc.zone_desc + (size_t)(P.grp * G + Z.zg) * zlen;
+        const int row = row_override >= 0 ? row_override : row_of(a, P.grp * G + Z.zg);
+        const float *d = a.sc.zone_desc + (size_t)row * zlen;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int zz = 4 * Z.zc + k;
@@ -1075,11 +1146,11 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
 {
     __shared__ Shared<WAVES> sh;
     extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
-    const Place P = locate<WAVES>(a);
+    Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
     if (P.has) {
-        load_spec(a, P.k, U);
+        load_spec(a, P.ks, U);
         load_state(a, P.k, U);
     }
     ZoneRegs Zr = {};
@@ -1089,26 +1160,34 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
     float *zdesc = dyn_lds + a.zdesc_offset;
     if (a.p.zone_shapes == 1) {
         const int G = a.envs_per_block;
-        const size_t first = (size_t)P.grp * G * zlen;
-        const size_t total = (size_t)a.p.num_envs * zlen;
-        for (int q = P.l; q < G * zlen; q += 64 * WAVES)
-            zdesc[q] = (P.grp < a.num_groups && first + q < total) ? a.sc.zone_desc[first + q] : 0.0f;
+        for (int q = P.l; q < G * zlen; q += 64 * WAVES) {
+            const int g = q / zlen;
+            const int env = P.grp * G + g;
+            const bool live = P.grp < a.num_groups && env < a.p.num_envs;
+            zdesc[q] = live ? a.sc.zone_desc[(size_t)row_of(a, env) * zlen + (q - g * zlen)] : 0.0f;
+        }
         lds_barrier<WAVES>();
     }
-    const float *zd = zdesc + (P.has ? P.g : 0) * zlen;
+    float *zd = zdesc + (P.has ? P.g : 0) * zlen;
     Carry C = {1.0f, 0.0f, 0.0f};
     float zeff_unused = 0.0f;
     int forced = -1;
     if (DO_POLICY) {
         float cu = 1.0f, su = 0.0f;
         if (P.has) {
-            code_u = zone_at(a, zd, P.e, U.x, U.y, zeff_unused);
+            code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
             heading_sincos(U.theta, su, cu);
         }
         forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su);
     }
-    if (DO_STEP) step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
-    else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.e, U.x, U.y, zeff_unused);
+    bool restarted = false;
+    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
+    else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
+    if (DO_STEP && DO_OBS && a.p.num_levels > 0 && restarted) {
+        // zone slots of the envs that changed level
+        const int row = Zr.lane ? sh.rows[Zr.zg] : -1;
+        if (row >= 0) Zr = load_zone_regs<WAVES>(a, P, row);
+    }
     if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C, Zr);
 }
 
@@ -1116,15 +1195,22 @@ template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
 {
     __shared__ Shared<WAVES> sh;
-    const Place P = locate<WAVES>(a);
+    Place P = locate<WAVES>(a);
     const int N = a.p.num_units;
     const bool go = P.has && !(a.env_mask && a.env_mask[P.e] == 0);
+    if (a.p.num_levels > 0) {
+        const int row = advance_level<WAVES>(a, sh, P, go);
+        if (row >= 0) {
+            P.row = row;
+            P.ks = (size_t)row * N + P.u;
+        }
+    }
     Unit U = {};
     float ratio = 0.0f;
     if (go) {
-        load_spec(a, P.k, U);
+        load_spec(a, P.ks, U);
         float zeff = 0.0f;
-        spawn_unit(a, a.sc.zone_desc + (size_t)P.e * 6 * a.p.max_zones, P.e, P.k, U, zeff);
+        spawn_unit(a, a.sc.zone_desc + (size_t)P.row * 6 * a.p.max_zones, P.row, P.ks, U, zeff);
         ratio = U.enabled ? U.hp / U.hmax : 0.0f;
         store_state(a, P.k, U);
     }
@@ -1157,13 +1243,14 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
     if (tid < units) {
         const int e = (int)(tid / N);
         const int u = (int)(tid - (size_t)e * N);
+        const int row = row_of(a, e);
         Unit U = {};
-        load_spec(a, tid, U);
+        load_spec(a, (size_t)row * N + u, U);
         load_state(a, tid, U);
         float4 q[4];
         if (U.enabled) {
             float zeff = 0.0f;
-            const int code = zone_at(a, a.sc.zone_desc + (size_t)e * zlen, e, U.x, U.y, zeff);
+            const int code = zone_at(a, a.sc.zone_desc + (size_t)row * zlen, row, U.x, U.y, zeff);
             q[0] = make_float4(U.hp, U.hp / U.hmax, U.x, U.y);
             q[1] = make_float4(U.theta, U.range, U.dmg, U.cd);
             q[2] = make_float4(U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f, U.radius, U.mass,
@@ -1185,7 +1272,7 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
     if (zlen > 0 && zt < zones) {
         const int e = (int)(zt / zlen);
         const int zz = (int)(zt - (size_t)e * zlen);
-        const float *d = a.sc.zone_desc + (size_t)e * zlen;
+        const float *d = a.sc.zone_desc + (size_t)row_of(a, e) * zlen;
         const int comp = zz % 6;
         out[(size_t)e * Dg + 16 * N + zz] = d[zz - comp] != 0.0f ? d[zz] : 0.0f;
     }
@@ -1208,6 +1295,8 @@ static int check_params(const TabxParams *p)
     if (p->max_steps < 1) return TABX_ERR_SHAPE;
     if (p->zone_shapes != 0 && p->zone_shapes != 1) return TABX_ERR_SHAPE;
     if (p->zone_shapes == 1 && (p->grid_w != 0 || p->max_zones < 1)) return TABX_ERR_SHAPE;
+    if (p->num_levels < 0) return TABX_ERR_SHAPE;
+    if ((int64_t)p->num_levels * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     if ((int64_t)p->num_envs * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     const float pos[] = {p->map_w, p->map_h, p->cell_size, p->dt};
     for (float v : pos)
@@ -1236,9 +1325,16 @@ static int check_scenario(const TabxParams *p, const TabxScenario *s)
     return TABX_OK;
 }
 
-static int check_state(const TabxState *s)
+static int check_state(const TabxParams *p, const TabxState *s)
 {
     if (!s) return TABX_ERR_NULL;
+    if (p->num_levels > 0) {
+        const void *lv[] = {s->level, s->next_level, s->level_draws};
+        for (const void *q : lv) {
+            if (!q) return TABX_ERR_NULL;
+            if (!aligned(q, 4)) return TABX_ERR_ALIGN;
+        }
+    }
     const float *f[] = {s->x, s->y, s->vx, s->vy, s->theta, s->hp, s->cd, s->reveal,
                         s->cur_speed, s->phi_prev};
     for (const float *q : f) {
@@ -1309,7 +1405,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     if (rc) return rc;
     if (p->num_envs == 0) return TABX_OK;          // empty batch: nothing to validate or do
     if ((rc = check_scenario(p, sc))) return rc;
-    if ((rc = check_state(st))) return rc;
+    if ((rc = check_state(p, st))) return rc;
     const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE;
     const bool stepping = mode == MODE_STEP || mode == MODE_STEP_OBSERVE ||
                           mode == MODE_POLICY_STEP_OBSERVE;
@@ -1440,7 +1536,7 @@ int tabx_global_state(const TabxParams *p, const TabxScenario *sc, const TabxSta
     if (rc) return rc;
     if (p->num_envs == 0) return TABX_OK;
     if ((rc = tabx::check_scenario(p, sc))) return rc;
-    if ((rc = tabx::check_state(st))) return rc;
+    if ((rc = tabx::check_state(p, st))) return rc;
     if (!out) return TABX_ERR_NULL;
     if (!tabx::aligned(out, 16)) return TABX_ERR_ALIGN;
     tabx::KArgs a = {};

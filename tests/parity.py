@@ -3,6 +3,7 @@ import numpy as np
 
 FLOAT_STATE = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed", "phi_prev")
 INT_STATE = ("alive", "t")
+LEVEL_STATE = ("level", "next_level", "level_draws")
 FLOAT_TOL = 1e-5          # absolute, float32 fields (positions, headings, HP, rewards, obs)
 
 
@@ -36,7 +37,7 @@ def compare_state(gpu_state: dict, ref_state: dict, where="", rows=None):
     for k in FLOAT_STATE:
         g = gpu_state[k] if rows is None else gpu_state[k][rows]
         inexact += _cmp_float(k, g, ref_state[k], where)
-    for k in INT_STATE:
+    for k in INT_STATE + tuple(k for k in LEVEL_STATE if k in ref_state):
         g = gpu_state[k] if rows is None else gpu_state[k][rows]
         _cmp_int(k, g, ref_state[k], where)
     return inexact
