@@ -25,7 +25,8 @@ class RefParams(C.Structure):
                [(n, C.c_float) for n in
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
-               [("zone_shapes", C.c_int), ("num_levels", C.c_int), ("level_seed", C.c_uint)]
+               [("zone_shapes", C.c_int), ("num_levels", C.c_int), ("level_seed", C.c_uint),
+                ("hurtbox_cone", C.c_int), ("hit_all", C.c_int)]
 
 
 _SC_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",

@@ -211,6 +211,15 @@ bool hurtbox_hit(float xi, float yi, float ci, float si, float L, float hw,
     return g2 <= rj * rj;
 }
 
+/* Angular part of the field of view: the offset (dx, dy) lies within the cone of half-angle
+ * acos(cos_half) around the heading (ci, si); a zero offset counts as inside. */
+bool within_cone_angle(float dx, float dy, float ci, float si, float cos_half)
+{
+    float d2 = (dx * dx) + (dy * dy);
+    float dot = (dx * ci) + (dy * si);
+    return (d2 == 0.0f) || (dot >= cos_half * std::sqrt(d2));
+}
+
 /* Role filter: damage dealers reach enemies only, healers (negative damage)
  * allies only. */
 inline bool role_allows(float dmg_i, int team_i, int team_j)
@@ -228,6 +237,7 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
     std::vector<float> bdmg(N, 0.0f), c(N), s(N);
     std::vector<int> target(N, -1);
     std::vector<unsigned char> landed(N, 0);
+    std::vector<unsigned char> inbox((size_t)N * N, 0);   /* attackable matrix: i may strike j */
 
     for (int u = 0; u < N; ++u) alive0[u] = st.alive[b + u];
 
@@ -335,6 +345,10 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
                                    S.hurt_halfwidth[i], st.x[kj], st.y[kj],
                                    S.radius[j], &d2, min_margin ? &m : nullptr);
             if (min_margin && m < min_margin[e]) min_margin[e] = m;
+            if (hit && P.hurtbox_cone)
+                hit = within_cone_angle(st.x[kj] - st.x[ki], st.y[kj] - st.y[ki], c[i], s[i],
+                                        S.sight_cos_half[i]);
+            if (hit) inbox[i * N + j] = 1;
             if (hit && (target[i] < 0 || d2 < best)) {
                 target[i] = j;
                 best = d2;
@@ -358,8 +372,10 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
         if (!alive0[j]) continue;
         const int kj = b + j;
         float acc = 0.0f;
-        for (int i = 0; i < N; ++i)
-            if (landed[i] && target[i] == j) acc = acc + S.dmg[i];
+        for (int i = 0; i < N; ++i) {
+            const bool strikes_j = P.hit_all ? inbox[i * N + j] != 0 : target[i] == j;
+            if (landed[i] && strikes_j) acc = acc + S.dmg[i];
+        }
         float h = (st.hp[kj] - acc) - bdmg[j];
         st.hp[kj] = clampf(h, 0.0f, S.hmax[j]);
     }
@@ -367,7 +383,10 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
     for (int i = 0; i < N; ++i) {
         if (landed[i] && S.dmg[i] > 0.0f) {
             st.reveal[b + i] = P.reveal_time;
-            st.reveal[b + target[i]] = P.reveal_time;
+            for (int j = 0; j < N; ++j) {
+                const bool strikes_j = P.hit_all ? inbox[i * N + j] != 0 : target[i] == j;
+                if (strikes_j) st.reveal[b + j] = P.reveal_time;
+            }
         }
     }
 
@@ -485,7 +504,6 @@ struct PairView {
 PairView pair_view(const RefParams &P, const RefScenario &S, const RefState &st, int e, int i,
                    int j, float ci, float si, int code_i, int code_j, double *margin)
 {
-    (void)P;
     const int N = P.num_units, ki = e * N + i, kj = e * N + j;
     PairView V;
     V.dx = st.x[kj] - st.x[ki];
@@ -520,6 +538,7 @@ PairView pair_view(const RefParams &P, const RefScenario &S, const RefState &st,
                                st.x[kj], st.y[kj], S.radius[j], &d2h, margin ? &mh : nullptr);
     bool allowed = role_allows(S.dmg[i], S.team[i], S.team[j]);
     if (margin && allowed && mh < *margin) *margin = mh;
+    if (P.hurtbox_cone) overlap = overlap && in_cone;
     V.attackable = overlap && allowed;
     return V;
 }

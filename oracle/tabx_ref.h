@@ -46,6 +46,11 @@ typedef struct RefParams {
                                    scenario arrays are a bank of L levels and env e plays row
                                    level[e], re-drawn whenever one of its episodes starts        */
     unsigned level_seed;        /* of the uniform level draws                                    */
+    int   hurtbox_cone;         /* 1: the hurtbox is also bounded by the unit's field of view: a
+                                   body in the rectangle counts only if its centre lies within
+                                   the sight cone's angle (any distance)                         */
+    int   hit_all;              /* 0: a strike lands on the closest valid body in the hurtbox;
+                                   1: on every valid body in it                                  */
 } RefParams;
 
 typedef struct RefScenario {

@@ -131,6 +131,7 @@ def step_health(p, terrain_e, sc_e, st_e, act):
             continue
         best, best_d = -1, np.inf
         hit_d = []
+        struck = []
         for j in range(n):
             if j == i or not alive[j]:
                 continue
@@ -139,11 +140,23 @@ def step_health(p, terrain_e, sc_e, st_e, act):
                 continue
             min_margin = min(min_margin, margin[i, j])
             d = math.hypot(x[j] - x[i], y[j] - y[i])
-            if hit[i, j]:
+            inside = bool(hit[i, j])
+            if inside and p.get("hurtbox_cone", 0) and d > 0.0:
+                # the body's centre must also lie within the angle of the sight cone
+                off = math.atan2(y[j] - y[i], x[j] - x[i]) - th[i]
+                off = abs((off + math.pi) % (2 * math.pi) - math.pi)
+                half = float(sc_e["sight_angle"][i]) / 2.0
+                min_margin = min(min_margin, abs(off - half) * d)
+                inside = off <= half
+            if inside:
                 hit_d.append(d)
-            if hit[i, j] and d < best_d:
+                struck.append(j)
+            if inside and d < best_d:
                 best, best_d = j, d
-        if best >= 0:
+        if p.get("hit_all", 0):
+            for j in struck:            # every valid body in the hurtbox
+                delta[j] += float(sc_e["dmg"][i])
+        elif best >= 0:
             delta[best] += float(sc_e["dmg"][i])
             hit_d.sort()
             if len(hit_d) > 1:          # a near tie for "closest" may flip in float32

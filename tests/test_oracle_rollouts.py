@@ -146,10 +146,13 @@ def test_visibility_and_attackable_vs_bruteforce(name):
     assert checked > 500 and flagged > 50
 
 
-@pytest.mark.parametrize("name", ["dense", "c1"])
-def test_one_tick_health_vs_bruteforce(name):
+@pytest.mark.parametrize("name,variant", [
+    ("dense", {}), ("c1", {}), ("dense", dict(hit_all=1)), ("dense", dict(hurtbox_cone=1)),
+    ("dense", dict(hit_all=1, hurtbox_cone=1))],
+    ids=["dense", "c1", "dense-hit_all", "dense-cone", "dense-hit_all-cone"])
+def test_one_tick_health_vs_bruteforce(name, variant):
     w, E, steps = SMALL[name]
-    p, sc, env = _env(w, E, max_steps=10_000)
+    p, sc, env = _env(w, E, max_steps=10_000, **variant)
     N = w.num_units
     compared = changed = 0
     for s in range(steps):
