@@ -101,6 +101,14 @@ typedef struct TabxParams {
      * curriculum) or leave the draws alone (domain randomisation). */
     int32_t  num_levels;
     uint32_t level_seed;
+    /* Hurtbox variants (App. A "Attack range geometry and target selection"; Sec. 4), both 0 or 1.
+     * hurtbox_cone = 1: the rectangle is also bounded by the unit's field of view: a body in it
+     * counts only if its centre lies within the angle of the sight cone (sight_cos_half), at any
+     * distance.  hit_all = 1: a strike lands on every valid body in the hurtbox instead of the
+     * closest one (each victim still sums its strikers in ascending index; every struck unit of
+     * a damaging strike is revealed). */
+    int32_t  hurtbox_cone;
+    int32_t  hit_all;
 } TabxParams;
 
 /* The scenario: unit specifications and zones (the unit and zone axes of the

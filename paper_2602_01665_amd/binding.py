@@ -44,7 +44,8 @@ class TabxParams(C.Structure):
                [(n, C.c_float) for n in
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
-               [("zone_shapes", C.c_int32), ("num_levels", C.c_int32), ("level_seed", C.c_uint32)]
+               [("zone_shapes", C.c_int32), ("num_levels", C.c_int32), ("level_seed", C.c_uint32),
+                ("hurtbox_cone", C.c_int32), ("hit_all", C.c_int32)]
 
 
 class TabxScenario(C.Structure):

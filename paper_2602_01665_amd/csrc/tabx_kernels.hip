@@ -57,6 +57,7 @@ struct KArgs {
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
     int       num_groups;          // workgroups that have envs to process
     int       zdesc_offset;        // elliptical zones: descriptor copy in dynamic LDS, floats
+    int       mask_offset;         // hit-all strikes: per-lane victim masks in dynamic LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
     int       cell_pow2;
@@ -454,6 +455,7 @@ __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, con
         const bool same_bush = (fj >> 8) == my_key;
         const bool concealed = (fj & 4) && !same_team && !same_bush;
         const bool seen = (j != P.u) && (fj & 1) && in_range && in_cone && !concealed;
+        // (a seen unit is inside the cone, so a cone-bounded hurtbox needs no further test)
         const bool attackable = seen && (healer == same_team) && (g2 <= B.x * B.x);
         const bool injured = B.z < B.y;
         can_hit = can_hit || (attackable && (!healer || injured));
@@ -573,7 +575,8 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
 // level.  Returns whether any env of the workgroup restarted.
 template <int WAVES>
 __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, float *zd,
-                                         Place &P, Unit &U, int &code_u, Carry &C, int forced)
+                                         uint64_t *masks, Place &P, Unit &U, int &code_u,
+                                         Carry &C, int forced)
 {
     float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
     const int N = a.p.num_units;
@@ -668,29 +671,58 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     lds_barrier<WAVES>();
 
     // stage 2b: attackable row of this unit over its env, closest valid target
-    // (strict "<" keeps the lowest index on ties)
+    // (strict "<" keeps the lowest index on ties).  Variants: the hurtbox also bounded by the
+    // sight cone's angle; the whole row kept as a bit mask when a strike lands on everybody.
+    const bool cone_bound = a.p.hurtbox_cone != 0;
+    const bool hit_all = a.p.hit_all != 0;
     int target = -1;
     {
         const int want = (U.dmg < 0.0f) ? U.team : 1 - U.team;   // healers reach allies only
         const float neg_hw = -U.hurt_hw;
         float best = kInf;
-        for (int jj = 0; jj < N; ++jj) {
-            const float4 J = sh.st.pj[P.base + jj];
-            const float dx = J.x - U.x;
-            const float dy = J.y - U.y;
-            float along;
-            const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
-            const float d2 = (dx * dx) + (dy * dy);
-            const bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
-            const bool take = ok && (d2 < best);
-            best = take ? d2 : best;
-            target = take ? jj : target;
+        if (!cone_bound && !hit_all) {
+            for (int jj = 0; jj < N; ++jj) {
+                const float4 J = sh.st.pj[P.base + jj];
+                const float dx = J.x - U.x;
+                const float dy = J.y - U.y;
+                float along;
+                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
+                const float d2 = (dx * dx) + (dy * dy);
+                const bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
+                const bool take = ok && (d2 < best);
+                best = take ? d2 : best;
+                target = take ? jj : target;
+            }
+        } else {
+            uint64_t row[WAVES] = {};
+            for (int jj = 0; jj < N; ++jj) {
+                const float4 J = sh.st.pj[P.base + jj];
+                const float dx = J.x - U.x;
+                const float dy = J.y - U.y;
+                float along;
+                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
+                const float d2 = (dx * dx) + (dy * dy);
+                bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
+                if (cone_bound)
+                    ok = ok && ((d2 == 0.0f) || (along >= U.cos_half * __builtin_sqrtf(d2)));
+                const bool take = ok && (d2 < best);
+                best = take ? d2 : best;
+                target = take ? jj : target;
+                const uint64_t bit = (uint64_t)(ok ? 1 : 0) << (jj & 63);
+                row[0] |= (WAVES == 1 || jj < 64) ? bit : 0ull;
+                if (WAVES == 2) row[WAVES - 1] |= jj >= 64 ? bit : 0ull;
+            }
+            if (hit_all) {
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) masks[P.l * WAVES + w] = row[w];
+            }
         }
     }
     const bool eligible = has && alive0 && act == TABX_ACT_ATTACK && U.cd <= 0.0f;
     if (eligible) U.cd = U.cooldown;
     const bool landed = eligible && target >= 0;
-    sh.st.hitrec[P.l] = make_int2(landed ? target : -1, __float_as_int(U.dmg));
+    // designated victim; -2: everybody in this unit's mask
+    sh.st.hitrec[P.l] = make_int2(landed ? (hit_all ? -2 : target) : -1, __float_as_int(U.dmg));
     lds_barrier<WAVES>();
 
     // stage 2c: victim side.  Sum what the attackers that designated this unit
@@ -698,12 +730,24 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     {
         float acc = 0.0f;
         bool struck = landed && U.dmg > 0.0f;
-        for (int ii = 0; ii < N; ++ii) {
-            const int2 h = sh.st.hitrec[P.base + ii];
-            const bool mine = h.x == P.u;
-            const float d = __int_as_float(h.y);
-            acc = acc + (mine ? d : 0.0f);
-            struck = struck || (mine && d > 0.0f);
+        if (!hit_all) {
+            for (int ii = 0; ii < N; ++ii) {
+                const int2 h = sh.st.hitrec[P.base + ii];
+                const bool mine = h.x == P.u;
+                const float d = __int_as_float(h.y);
+                acc = acc + (mine ? d : 0.0f);
+                struck = struck || (mine && d > 0.0f);
+            }
+        } else {
+            const int word = WAVES == 1 ? 0 : (P.u >> 6);
+            for (int ii = 0; ii < N; ++ii) {
+                const int2 h = sh.st.hitrec[P.base + ii];
+                const uint64_t row = masks[(P.base + ii) * WAVES + word];
+                const bool mine = h.x == -2 && ((row >> (P.u & 63)) & 1ull);
+                const float d = __int_as_float(h.y);
+                acc = acc + (mine ? d : 0.0f);
+                struck = struck || (mine && d > 0.0f);
+            }
         }
         if (has && alive0) {
             const float h = (U.hp - acc) - bdmg;
@@ -963,6 +1007,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int (&zsx)[4] = Zr.sx;
     const int (&zsy)[4] = Zr.sy;
     const int zone_seer0 = (WAVES == 1) ? zg * N : 0;     // lane of observer 0 of the zone lane's env
+    const bool cone_free = a.p.hurtbox_cone == 0;          // the hurtbox is the plain rectangle
     const int R = a.rows_per_flush;
     const int zone_dst0 = ((WAVES == 1) ? zg * R * Dp : 0) + 16 * N + 4 * zc;
 
@@ -1016,7 +1061,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const bool self = i == P.u;
         const bool pair = alive && (fi & 1) && !self;
         const bool seen = pair && in_range && in_cone && !concealed;
-        const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me);
+        const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me) &&
+                         (in_cone || cone_free);
         if (a.vis_mask) {
             // the ballot over the lanes is observer i's row; its own lane keeps it
             const uint64_t b = __ballot(seen);
@@ -1181,7 +1227,8 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su);
     }
     bool restarted = false;
-    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
+    uint64_t *masks = reinterpret_cast<uint64_t *>(dyn_lds + a.mask_offset);
+    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, masks, P, U, code_u, C, forced);
     else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
     if (DO_STEP && DO_OBS && a.p.num_levels > 0 && restarted) {
         // zone slots of the envs that changed level
@@ -1296,6 +1343,7 @@ static int check_params(const TabxParams *p)
     if (p->zone_shapes != 0 && p->zone_shapes != 1) return TABX_ERR_SHAPE;
     if (p->zone_shapes == 1 && (p->grid_w != 0 || p->max_zones < 1)) return TABX_ERR_SHAPE;
     if (p->num_levels < 0) return TABX_ERR_SHAPE;
+    if ((p->hurtbox_cone | p->hit_all) & ~1) return TABX_ERR_SHAPE;
     if ((int64_t)p->num_levels * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     if ((int64_t)p->num_envs * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     const float pos[] = {p->map_w, p->map_h, p->cell_size, p->dt};
@@ -1364,9 +1412,13 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     dyn_floats = 4 * ((dyn_floats + 3) / 4 + (dyn_floats + 3) / 64 + 1);
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
     const size_t zdesc_floats = a.p.zone_shapes == 1 ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
-    const size_t dyn_bytes = (dyn_floats + zdesc_floats) * sizeof(float);
-    const size_t step_bytes = zdesc_floats * sizeof(float);
+    // ... and, when a strike lands on everybody in the hurtbox, one victim mask per lane
+    const size_t zdesc_even = (zdesc_floats + 1) & ~(size_t)1;
+    const size_t mask_floats = a.p.hit_all ? (size_t)64 * WAVES * WAVES * 2 : 0;
+    const size_t dyn_bytes = (dyn_floats + zdesc_even + mask_floats) * sizeof(float);
+    const size_t step_bytes = (zdesc_even + mask_floats) * sizeof(float);
     a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0 : (int)dyn_floats;
+    a.mask_offset = a.zdesc_offset + (int)zdesc_even;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);

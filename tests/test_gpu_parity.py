@@ -98,6 +98,24 @@ def test_combat_heavy_rollout(fused):
     assert dones > 128
 
 
+VARIANTS = [dict(hit_all=1), dict(hurtbox_cone=1), dict(hit_all=1, hurtbox_cone=1)]
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+@pytest.mark.parametrize("variant", VARIANTS, ids=["hit_all", "cone", "hit_all+cone"])
+def test_hurtbox_variants(variant, fused):
+    """Strikes that land on every body in the hurtbox, and the hurtbox bounded by the sight
+    cone: crowded 4v4, the 10v10 workload, and 64v64 (two wavefronts per env, two mask words)."""
+    _say(f"[gpu] hurtbox variant {variant} fused={fused}")
+    inexact, dones = _rollout(DENSE, 128, 200, fused, max_steps=48, **variant)
+    assert dones > 64
+    wide = I.make_scenario(I.WORKLOADS["c3_16384env_10v10"], 48)
+    wide["hurt_halfwidth"] *= np.float32(3.0)            # boxes wider than the cone near the unit
+    _rollout(I.WORKLOADS["c3_16384env_10v10"], 48, 120, fused, scenario=wide, max_steps=64,
+             **variant)
+    _rollout(I.WORKLOADS["c5_1024env_64v64"], 2, 50, fused, max_steps=30, **variant)
+
+
 @pytest.mark.parametrize("team_size,disabled", [(1, 0), (3, 1), (7, 2), (16, 3), (17, 0),
                                                 (32, 5), (33, 4), (50, 9), (64, 0)])
 def test_ragged_unit_counts_and_padding(team_size, disabled):
