@@ -8,7 +8,9 @@ import sys
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 SOURCES = [os.path.join(_PKG, "csrc", "tabx_kernels.hip")]
-HEADERS = [os.path.join(_ROOT, "include", "tabx.h")]
+HEADERS = [os.path.join(_ROOT, "include", "tabx.h")] + [
+    os.path.join(_PKG, "csrc", h)
+    for h in ("tabx_device.h", "tabx_policy.h", "tabx_step.h", "tabx_observe.h")]
 LIB_PATH = os.path.join(_PKG, "libtabx.so")
 
 HIPCC_FLAGS = [

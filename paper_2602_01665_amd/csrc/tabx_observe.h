@@ -1,0 +1,308 @@
+// Observe stage of the TABX tick (App. A "Observation and Global State").
+#pragma once
+#include "tabx_device.h"
+
+#pragma clang fp contract(off)
+
+namespace tabx {
+
+// Observation rows of every unit of the workgroup's envs, visibility masks, action masks.
+//
+// A row is N blocks of 16 floats (the observer's own block first, then the other units in
+// ascending index) followed by the zone slots.  The rows of pass i (observer i of every env
+// packed in the workgroup) are assembled in LDS as exact images of the HBM rows, pitch
+// row_pitch = D rounded up to 4 floats, and then go out in 16-byte chunks, chunk t of the
+// staged rows handled by lane t % lanes of store pass t / lanes.
+// Zone slots of the observation rows: lane (env slot zg, 16-byte chunk zc of the zone part)
+// keeps its four zone floats in registers for the whole launch: the value (zero if the slot
+// is inactive) and which observer coordinate to subtract (centre x / y of an active slot).
+struct ZoneRegs {
+    bool  lane;
+    int   zg, zc;
+    float val[4];
+    int   sx[4], sy[4];
+};
+
+// Issued at the top of the kernel so that the descriptor loads are long done when the
+// observe stage needs them.
+// Row of the scenario arrays that configures env `env`.
+__device__ __forceinline__ int row_of(const KArgs &a, int env)
+{
+    if (a.p.num_levels <= 0) return env;
+    const int lv = a.st.level[env];
+    return lv < 0 ? 0 : (lv >= a.p.num_levels ? a.p.num_levels - 1 : lv);
+}
+
+template <int WAVES>
+__device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &P, int row_override = -1)
+{
+    ZoneRegs Z = {};
+    const int G = a.envs_per_block;
+    const int zlen = 6 * a.p.max_zones;
+    const int ZC = (zlen + 3) >> 2;
+    const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
+    Z.zg = ZC > 0 ? P.l / ZC : 0;
+    Z.zc = P.l - Z.zg * ZC;
+    Z.lane = ZC > 0 && Z.zg < (envs_left < G ? envs_left : G);
+    if (Z.lane) {
+        const int row = row_override >= 0 ? row_override : row_of(a, P.grp * G + Z.zg);
+        const float *d = a.sc.zone_desc + (size_t)row * zlen;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int zz = 4 * Z.zc + k;
+            if (zz < zlen) {
+                const int comp = zz % 6;
+                const bool active = d[zz - comp] != 0.0f;
+                Z.val[k] = active ? d[zz] : 0.0f;
+                Z.sx[k] = (active && comp == 1) ? -1 : 0;
+                Z.sy[k] = (active && comp == 2) ? -1 : 0;
+            }
+        }
+    }
+    return Z;
+}
+
+// Where 16-byte chunk c of the staged row images lives in LDS.
+__device__ __forceinline__ int staged_chunk(int c) { return c + (c >> 4); }
+
+template <int WAVES, bool CARRIED>
+__device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *stg,
+                                            const Place &P, const Unit &U, int code_u,
+                                            const Carry &C, const ZoneRegs &Zr)
+{
+    constexpr int LANES = 64 * WAVES;
+    const int N = a.p.num_units;
+    const int G = a.envs_per_block;
+    const int D = a.obs_dim;
+    const int Dp = a.row_pitch;
+    const int CPR = Dp >> 2;                     // 16-byte chunks per staged row
+    const bool has = P.has;
+    const int lane = P.l & 63;
+    const int wv = P.l >> 6;
+    const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
+    const int envs_here = envs_left < G ? envs_left : G;
+
+    // Blocks of 16 floats written by neighbouring lanes are 64 bytes apart, which would put every
+    // fourth lane on the same LDS banks; one spare 16-byte chunk after every 16 spreads them.
+    float4 *stage = reinterpret_cast<float4 *>(stg);
+    const bool blocks_aligned = (Dp & 15) == 0;  // every block then lies within one group of 16 chunks
+
+    lds_barrier<WAVES>();                        // the step stage is done with the LDS union
+
+    // ---- publish this unit as an observer
+    float cu = 1.0f, su = 0.0f;
+    const int alive = has ? U.alive : 0;
+    const bool enabled = has && U.enabled;
+    const bool in_bush = (code_u & 3) == TABX_ZONE_BUSH;
+    const int my_code = code_u & 0xff;
+    const bool hidden = in_bush && !(U.reveal > 0.0f);
+    const float ratio = CARRIED ? C.ratio : U.hp / U.hmax;   // disabled units: masked below
+    const float cd_ratio = U.cooldown != 0.0f ? U.cd / U.cooldown : 0.0f;
+    const float r2_me = U.radius * U.radius;
+    {
+        if (CARRIED) {
+            cu = C.cu;
+            su = C.su;
+        } else if (has) {
+            heading_sincos(U.theta, su, cu);
+        }
+        const int key = in_bush ? my_code : 0x100;         // 0x100 matches no cell code
+        sh.ob.pose[P.l] = make_float4(U.x, U.y, cu, su);
+        sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
+        sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | (key << 8);
+        if (has && a.action_mask) a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
+    }
+    // what differs between a unit's block in its own row and in another unit's row
+    const int own_mask = enabled ? -1 : 0;
+    const float own_alive = alive ? 1.0f : 0.0f;
+    const float own_zone = (float)(code_u & 3);
+    const float own_team = (float)U.team;
+
+    // ---- zone chunks: lane (env slot zg, chunk zc) holds its four zone floats in registers
+    const int zg = Zr.zg, zc = Zr.zc;
+    const bool zone_lane = Zr.lane;
+    const float (&zval)[4] = Zr.val;
+    const int (&zsx)[4] = Zr.sx;
+    const int (&zsy)[4] = Zr.sy;
+    const int zone_seer0 = (WAVES == 1) ? zg * N : 0;     // lane of observer 0 of the zone lane's env
+    const bool cone_free = a.p.hurtbox_cone == 0;          // the hurtbox is the plain rectangle
+    const int R = a.rows_per_flush;
+    const int zone_dst0 = ((WAVES == 1) ? zg * R * Dp : 0) + 16 * N + 4 * zc;
+
+    // ---- store passes: chunk t = p * LANES + l of the staged rows -> (row slot, chunk in row)
+    unsigned dst_off[kMaxPasses];
+    int valid[kMaxPasses];
+    {
+        const int RC = R * CPR;                    // chunks per env slot and flush
+        int tg = P.l / RC;                         // env slot of chunk t
+        int q = P.l - tg * RC;                     // chunk within the env's R staged rows
+#pragma unroll
+        for (int p = 0; p < kMaxPasses; ++p) {
+            int vm = 0;                            // R > 1 only when D is a multiple of 4
+#pragma unroll
+            for (int k = 0; k < 4; ++k) vm |= (R > 1 || 4 * q + k < D) ? (1 << k) : 0;
+            valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
+            dst_off[p] = (unsigned)(tg * N * D + 4 * q);
+            q += LANES;                            // chunk t + LANES of the next pass
+            while (q >= RC) {
+                q -= RC;
+                tg += 1;
+            }
+        }
+    }
+
+    lds_barrier<WAVES>();
+
+    // ---- one pass per observer index i: every lane's unit seen from observer i of its env
+    float *out = a.obs + (size_t)P.grp * G * N * D;
+    uint64_t my_row = 0;
+    const int blk_row0 = (WAVES == 1) ? P.g * R * Dp : 0;
+    for (int i0 = 0; i0 < N; i0 += R) {
+    for (int rr = 0; rr < R; ++rr) {
+        const int i = i0 + rr;
+        const int oi = P.base + i;
+        const float4 A = sh.ob.pose[oi];
+        const float4 B = sh.ob.reach[oi];
+        const int fi = sh.seer[oi];
+        const int buf = (WAVES == 1) ? rr * Dp : (i & 1) * Dp;
+        // offset of this unit from the observer; `dot` is its component along the heading
+        const float dx = U.x - A.x;
+        const float dy = U.y - A.y;
+        float dot;
+        const float g2 = hurtbox_gap2(dx, dy, A.z, A.w, B.x, B.y, -B.y, dot);
+        const float d2 = (dx * dx) + (dy * dy);
+        const bool in_range = d2 <= B.z;
+        const bool in_cone = (d2 == 0.0f) || (dot >= B.w * __builtin_sqrtf(d2));
+        const bool same_team = ((fi >> 1) & 1) == U.team;
+        const bool same_bush = (fi >> 8) == my_code;
+        const bool concealed = hidden && !same_team && !same_bush;
+        const bool self = i == P.u;
+        const bool pair = alive && (fi & 1) && !self;
+        const bool seen = pair && in_range && in_cone && !concealed;
+        const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me) &&
+                         (in_cone || cone_free);
+        if (a.vis_mask) {
+            // the ballot over the lanes is observer i's row; its own lane keeps it
+            const uint64_t b = __ballot(seen);
+            if (WAVES == 1) my_row = self ? b : my_row;
+            else if (lane == 0) sh.rowbits[i][wv] = b;
+        }
+        if (has) {
+            // block position in the row: own block first, then the others in index order
+            const int blk = self ? 0 : (P.u < i ? P.u + 1 : P.u);
+            const int m = self ? own_mask : (seen ? -1 : 0);
+            const float c2 = self ? U.x : dx;
+            const float c3 = self ? U.y : dy;
+            const float c12 = self ? own_alive : 1.0f;
+            const float c13 = self ? U.cur_speed : (same_team ? 1.0f : 0.0f);
+            const float c14 = self ? own_zone : (hit ? 1.0f : 0.0f);
+            const float c15 = self ? own_team : U.cur_speed;
+            const float4 q0 = make_float4(__int_as_float(__float_as_int(U.hp) & m),
+                                          __int_as_float(__float_as_int(ratio) & m),
+                                          __int_as_float(__float_as_int(c2) & m),
+                                          __int_as_float(__float_as_int(c3) & m));
+            const float4 q1 = make_float4(__int_as_float(__float_as_int(U.theta) & m),
+                                          __int_as_float(__float_as_int(U.range) & m),
+                                          __int_as_float(__float_as_int(U.dmg) & m),
+                                          __int_as_float(__float_as_int(U.cd) & m));
+            const float4 q2 = make_float4(__int_as_float(__float_as_int(cd_ratio) & m),
+                                          __int_as_float(__float_as_int(U.radius) & m),
+                                          __int_as_float(__float_as_int(U.mass) & m),
+                                          __int_as_float(__float_as_int(U.sight_angle) & m));
+            const float4 q3 = make_float4(__int_as_float(__float_as_int(c12) & m),
+                                          __int_as_float(__float_as_int(c13) & m),
+                                          __int_as_float(__float_as_int(c14) & m),
+                                          __int_as_float(__float_as_int(c15) & m));
+            const int cb = (buf + blk_row0 + 16 * blk) >> 2;       // first 16-byte chunk of the block
+            if (blocks_aligned) {
+                float4 *d = stage + staged_chunk(cb);
+                d[0] = q0;
+                d[1] = q1;
+                d[2] = q2;
+                d[3] = q3;
+            } else {
+                stage[staged_chunk(cb)] = q0;
+                stage[staged_chunk(cb + 1)] = q1;
+                stage[staged_chunk(cb + 2)] = q2;
+                stage[staged_chunk(cb + 3)] = q3;
+            }
+        }
+        if (zone_lane) {
+            const float4 Z = sh.ob.pose[zone_seer0 + i];
+            const int en = (sh.seer[zone_seer0 + i] & 8) ? -1 : 0;
+            const int xb = __float_as_int(Z.x), yb = __float_as_int(Z.y);
+            float zo[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float shift = __int_as_float((xb & zsx[k]) | (yb & zsy[k]));
+                zo[k] = __int_as_float(__float_as_int(zval[k] - shift) & en);
+            }
+            stage[staged_chunk((buf + zone_dst0) >> 2)] = make_float4(zo[0], zo[1], zo[2], zo[3]);
+        }
+    }
+        lds_barrier<WAVES>();
+
+        // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
+        const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
+        float *row = out + i0 * D;
+        // chunk t = p * LANES + lane of the staged rows sits at staged_chunk(t): LANES is a
+        // multiple of 16, so the passes are a constant stride apart
+        const float4 *src = stage + staged_chunk((buf >> 2) + P.l);
+        constexpr int PASS_STRIDE = LANES + LANES / 16;
+        if (D == Dp) {
+            // every chunk is whole: fetch all passes from LDS first, then issue the stores
+            float4 v[kMaxPasses];
+#pragma unroll
+            for (int p = 0; p < kMaxPasses; ++p)
+                if (p < a.copy_passes)
+                    v[p] = src[p * PASS_STRIDE];
+#pragma unroll
+            for (int p = 0; p < kMaxPasses; ++p) {
+                if (p < a.copy_passes && valid[p] != 0) {
+                    // single-wave workgroups stream with the non-temporal hint: the rows are
+                    // never read back by the kernel, and the hint measurably raises the store
+                    // rate there (it lowers it for the two-wave, 8 KB-row case)
+                    f4u o = {v[p].x, v[p].y, v[p].z, v[p].w};
+                    f4u *dp = reinterpret_cast<f4u *>(row + dst_off[p]);
+                    if (WAVES == 1) __builtin_nontemporal_store(o, dp);
+                    else *dp = o;
+                }
+            }
+        } else {
+            // rows that are not a multiple of 16 bytes end in a partial chunk
+#pragma unroll
+            for (int p = 0; p < kMaxPasses; ++p) {
+                const int vm = valid[p];
+                if (p < a.copy_passes && vm != 0) {
+                    const float4 v = src[p * PASS_STRIDE];
+                    float *dp = row + dst_off[p];
+                    if (vm == 15) {
+                        f4u o = {v.x, v.y, v.z, v.w};
+                        *reinterpret_cast<f4u *>(dp) = o;
+                    } else {
+                        if (vm & 1) dp[0] = v.x;
+                        if (vm & 2) dp[1] = v.y;
+                        if (vm & 4) dp[2] = v.z;
+                        if (vm & 8) dp[3] = v.w;
+                    }
+                }
+            }
+        }
+        if (WAVES == 1) lds_barrier<WAVES>();    // two waves alternate between two staging buffers
+    }
+
+    if (a.vis_mask) {
+        lds_barrier<WAVES>();
+        if (has) {
+            if (WAVES == 1) {
+                const uint64_t range = N >= 64 ? ~0ull : ((1ull << N) - 1ull);
+                a.vis_mask[P.k] = (my_row >> P.base) & range;
+            } else {
+                const int words = (N + 63) >> 6;
+                for (int w = 0; w < words; ++w) a.vis_mask[P.k * words + w] = sh.rowbits[P.u][w];
+            }
+        }
+    }
+}
+
+} // namespace tabx

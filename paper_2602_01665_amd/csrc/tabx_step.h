@@ -1,0 +1,352 @@
+// Step stage of the TABX tick (App. A "Interaction Dynamics", "Reward", "Zones"): timers,
+// kinematics, actions, hurtbox combat, zone effects, rewards, termination and auto-reset.
+#pragma once
+#include "tabx_device.h"
+#include "tabx_policy.h"   // policy_hash draws the levels
+
+#pragma clang fp contract(off)
+
+namespace tabx {
+
+// Level bank: an episode of the lane's env is about to start (`take`, uniform over the env's
+// lanes).  Unit 0 takes the queued level (folded into [0, num_levels)), refills the queue with
+// a uniform draw, the hash of (level_seed, env, draws so far), and tells the env's other lanes
+// through LDS.  Returns the env's new row, or -1 if it keeps its level.  All lanes call it.
+template <int WAVES>
+__device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, const Place &P,
+                                             bool take)
+{
+    if (P.has && P.u == 0) {
+        int row = -1;
+        if (take) {
+            const uint32_t L = (uint32_t)a.p.num_levels;
+            row = (int)((uint32_t)a.st.next_level[P.e] % L);
+            const uint32_t n = (uint32_t)a.st.level_draws[P.e];
+            a.st.level[P.e] = row;
+            a.st.next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)P.e, 0u, n, 3u) % L);
+            a.st.level_draws[P.e] = (int)(n + 1u);
+        }
+        sh.rows[P.g] = row;
+    }
+    lds_barrier<WAVES>();
+    return P.has ? sh.rows[P.g] : -1;
+}
+
+// `forced` >= 0 replaces the unit's entry of the action array (the policy stage chose it).
+// `zd`: the env's zone descriptors in LDS (elliptical zones), rewritten when the env changes
+// level.  Returns whether any env of the workgroup restarted.
+template <int WAVES>
+__device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, float *zd,
+                                         uint64_t *masks, Place &P, Unit &U, int &code_u,
+                                         Carry &C, int forced)
+{
+    float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
+    const int N = a.p.num_units;
+    const float dt = a.p.dt;
+    const bool has = P.has;
+    const int alive0 = has ? U.alive : 0;
+    const int act = forced >= 0 ? forced : (has ? (int)a.actions[P.k] : 0);
+    // per-env scalars, requested early: they are needed only after three LDS exchanges
+    const int t_new = has ? a.st.t[P.e] + 1 : 0;
+    const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
+    float bdmg = 0.0f;
+
+    // stage 1: cooldown / reveal timers, explicit Euler move, arena penalty + clip
+    if (has && U.enabled) {
+        float v = U.cd - dt;
+        U.cd = v > 0.0f ? v : 0.0f;
+        v = U.reveal - dt;
+        U.reveal = v > 0.0f ? v : 0.0f;
+        if (alive0) {
+            const float nx = U.x + U.vx * dt;
+            const float ny = U.y + U.vy * dt;
+            const bool oob = (nx < 0.0f) || (nx > a.p.map_w) || (ny < 0.0f) || (ny > a.p.map_h);
+            if (oob) bdmg = (a.p.boundary_frac * U.hmax) * dt;
+            U.x = clamp_between(nx, 0.0f, a.p.map_w);
+            U.y = clamp_between(ny, 0.0f, a.p.map_h);
+        }
+    }
+
+    // stage 1b: overlapping bodies are pushed apart.  Every unit sums, over its partners in
+    // ascending index, the share of each overlap it has to give way for; all pairs are taken
+    // on the positions after the kinematic update; then the unit is clipped again.
+    if (a.p.collision_alpha > 0.0f) {
+        // partner record: x, y, radius, mass (negative mass: not a body)
+        sh.st.pj[P.l] = make_float4(U.x, U.y, U.radius, (has && U.enabled) ? U.mass : -1.0f);
+        lds_barrier<WAVES>();
+        float ax = 0.0f, ay = 0.0f;
+        for (int jj = 0; jj < N; ++jj) {
+            const float4 J = sh.st.pj[P.base + jj];
+            const float dx = J.x - U.x;
+            const float dy = J.y - U.y;
+            const float dist = __builtin_sqrtf((dx * dx) + (dy * dy));
+            const float pen = (U.radius + J.z) - dist;
+            const bool apart = dist > 0.0f;
+            // coincident centres separate along x, the lower index to the left
+            const float nx = apart ? dx / dist : (P.u < jj ? 1.0f : -1.0f);
+            const float ny = apart ? dy / dist : 0.0f;
+            const float share = J.w / (U.mass + J.w);
+            const float c = ((pen - a.p.collision_slop) * a.p.collision_alpha) * share;
+            const bool push = (pen > a.p.collision_slop) && (jj != P.u) && (J.w >= 0.0f);
+            // subtracting a zero product leaves the finite sum unchanged
+            const float ce = push ? c : 0.0f;
+            ax = ax - (ce * nx);
+            ay = ay - (ce * ny);
+        }
+        if (has && U.enabled) {
+            U.x = clamp_between(U.x + ax, 0.0f, a.p.map_w);
+            U.y = clamp_between(U.y + ay, 0.0f, a.p.map_h);
+        }
+        lds_barrier<WAVES>();          // the partner records are rewritten for the combat stage
+    }
+
+    // the position is final for this tick: fetch the terrain cell under it now, the zone
+    // effects of stage 3 use it after the combat exchange
+    if (has && U.enabled) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff);
+
+    // stage 2a: movement sets next tick's velocity, rotation turns the heading now
+    float cu = 1.0f, su = 0.0f;
+    if (has) {
+        U.vx = 0.0f;
+        U.vy = 0.0f;
+        if (alive0) {
+            const float sp = U.cur_speed;
+            if (act == TABX_ACT_MOVE_XP) U.vx = sp;
+            else if (act == TABX_ACT_MOVE_YP) U.vy = sp;
+            else if (act == TABX_ACT_MOVE_XM) U.vx = -sp;
+            else if (act == TABX_ACT_MOVE_YM) U.vy = -sp;
+            else if (act == TABX_ACT_ROT_LEFT) {
+                float th = U.theta + (a.p.turn_rate * dt);
+                if (th >= kTwoPi) th = th - kTwoPi;
+                U.theta = th;
+            } else if (act == TABX_ACT_ROT_RIGHT) {
+                float th = U.theta - (a.p.turn_rate * dt);
+                if (th < 0.0f) th = th + kTwoPi;
+                U.theta = th;
+            }
+        }
+        heading_sincos(U.theta, su, cu);
+    }
+    // flags: team of a unit alive at entry, 2 for anything that cannot be a target
+    sh.st.pj[P.l] = make_float4(U.x, U.y, U.radius * U.radius,
+                             __int_as_float(alive0 ? U.team : 2));
+    lds_barrier<WAVES>();
+
+    // stage 2b: attackable row of this unit over its env, closest valid target
+    // (strict "<" keeps the lowest index on ties).  Variants: the hurtbox also bounded by the
+    // sight cone's angle; the whole row kept as a bit mask when a strike lands on everybody.
+    const bool cone_bound = a.p.hurtbox_cone != 0;
+    const bool hit_all = a.p.hit_all != 0;
+    int target = -1;
+    {
+        const int want = (U.dmg < 0.0f) ? U.team : 1 - U.team;   // healers reach allies only
+        const float neg_hw = -U.hurt_hw;
+        float best = kInf;
+        if (!cone_bound && !hit_all) {
+            for (int jj = 0; jj < N; ++jj) {
+                const float4 J = sh.st.pj[P.base + jj];
+                const float dx = J.x - U.x;
+                const float dy = J.y - U.y;
+                float along;
+                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
+                const float d2 = (dx * dx) + (dy * dy);
+                const bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
+                const bool take = ok && (d2 < best);
+                best = take ? d2 : best;
+                target = take ? jj : target;
+            }
+        } else {
+            uint64_t row[WAVES] = {};
+            for (int jj = 0; jj < N; ++jj) {
+                const float4 J = sh.st.pj[P.base + jj];
+                const float dx = J.x - U.x;
+                const float dy = J.y - U.y;
+                float along;
+                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
+                const float d2 = (dx * dx) + (dy * dy);
+                bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
+                if (cone_bound)
+                    ok = ok && ((d2 == 0.0f) || (along >= U.cos_half * __builtin_sqrtf(d2)));
+                const bool take = ok && (d2 < best);
+                best = take ? d2 : best;
+                target = take ? jj : target;
+                const uint64_t bit = (uint64_t)(ok ? 1 : 0) << (jj & 63);
+                row[0] |= (WAVES == 1 || jj < 64) ? bit : 0ull;
+                if (WAVES == 2) row[WAVES - 1] |= jj >= 64 ? bit : 0ull;
+            }
+            if (hit_all) {
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) masks[P.l * WAVES + w] = row[w];
+            }
+        }
+    }
+    const bool eligible = has && alive0 && act == TABX_ACT_ATTACK && U.cd <= 0.0f;
+    if (eligible) U.cd = U.cooldown;
+    const bool landed = eligible && target >= 0;
+    // designated victim; -2: everybody in this unit's mask
+    sh.st.hitrec[P.l] = make_int2(landed ? (hit_all ? -2 : target) : -1, __float_as_int(U.dmg));
+    lds_barrier<WAVES>();
+
+    // stage 2c: victim side.  Sum what the attackers that designated this unit
+    // deal, ascending attacker index; subtract once with the arena penalty; clamp.
+    {
+        float acc = 0.0f;
+        bool struck = landed && U.dmg > 0.0f;
+        if (!hit_all) {
+            for (int ii = 0; ii < N; ++ii) {
+                const int2 h = sh.st.hitrec[P.base + ii];
+                const bool mine = h.x == P.u;
+                const float d = __int_as_float(h.y);
+                acc = acc + (mine ? d : 0.0f);
+                struck = struck || (mine && d > 0.0f);
+            }
+        } else {
+            const int word = WAVES == 1 ? 0 : (P.u >> 6);
+            for (int ii = 0; ii < N; ++ii) {
+                const int2 h = sh.st.hitrec[P.base + ii];
+                const uint64_t row = masks[(P.base + ii) * WAVES + word];
+                const bool mine = h.x == -2 && ((row >> (P.u & 63)) & 1ull);
+                const float d = __int_as_float(h.y);
+                acc = acc + (mine ? d : 0.0f);
+                struck = struck || (mine && d > 0.0f);
+            }
+        }
+        if (has && alive0) {
+            const float h = (U.hp - acc) - bdmg;
+            U.hp = clamp_between(h, 0.0f, U.hmax);
+            if (struck) U.reveal = a.p.reveal_time;
+        }
+    }
+
+    // stage 3: zone effects at the new position, alive flag
+    float ratio = 0.0f;
+    if (has) {
+        if (U.enabled) {
+            const int zone = code_u & 3;
+            if (alive0 && zone == TABX_ZONE_LAVA) {
+                const float h = U.hp - (zone_magnitude(a, zeff, a.p.lava_dps) * dt);
+                U.hp = h > 0.0f ? h : 0.0f;
+            }
+            U.cur_speed = zone == TABX_ZONE_SWAMP
+                              ? U.speed * zone_magnitude(a, zeff, a.p.swamp_mult) : U.speed;
+            U.alive = U.hp > 0.0f ? 1 : 0;
+            ratio = U.hp / U.hmax;
+        } else {
+            U.alive = 0;
+        }
+    }
+    const bool en = has && U.enabled;
+    sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
+                                (en && U.team != 0) ? ratio : 0.0f);
+    const bool pred[4] = {en && U.team == 0, en && U.team != 0,
+                          has && U.alive && U.team == 0, has && U.alive && U.team != 0};
+    int cnt[4];
+    env_counts(sh, P, N, pred, cnt);
+    // episode metrics need the alive counts at entry as well (first loss of a unit)
+    const bool want_kills = a.st.kill_run != nullptr;
+    int before[4] = {0, 0, 0, 0};
+    if (want_kills) {
+        const bool pred0[4] = {alive0 && U.team == 0, alive0 && U.team != 0, false, false};
+        env_counts(sh, P, N, pred0, before);
+    }
+    lds_barrier<WAVES>();
+
+    // reward (Eq. 1), termination, terminal bonus
+    float m0, m1;
+    team_means(sh, P, N, cnt[0], cnt[1], m0, m1);
+    const float phi = m0 - m1;
+    const float dense = phi - phi_prev;
+    float r0 = dense, r1 = -dense;
+    const bool done = has && (cnt[2] == 0 || cnt[3] == 0 || t_new >= a.p.max_steps);
+    // does any env of this workgroup restart?  (one env per workgroup when WAVES == 2:
+    // the flag is already uniform there, up to the idle lanes)
+    bool any_done;
+    if (WAVES == 1) {
+        any_done = __ballot(done) != 0ull;
+    } else {
+        const uint64_t b = __ballot(done);
+        if ((P.l & 63) == 0) sh.ballots[P.l >> 6][0] = b;
+        lds_barrier<WAVES>();
+        any_done = (sh.ballots[0][0] | sh.ballots[WAVES - 1][0]) != 0ull;
+    }
+    if (done) {
+        const bool ally_win = m0 > m1;
+        r0 = r0 + (ally_win ? 1.0f : -1.0f);
+        r1 = r1 + (ally_win ? -1.0f : 1.0f);
+    }
+    if (has) a.rewards[P.k] = U.enabled ? (U.team ? r1 : r0) : 0.0f;
+
+    // auto-reset of finished envs; the potential of the fresh state seeds phi_prev
+    float phi_next = phi;
+    lds_barrier<WAVES>();          // everyone has read the ratio terms of the finished tick
+    if (any_done) {
+        bool en_next = en;
+        if (a.p.num_levels > 0) {
+            // the finished envs move to their queued level: new specifications, new zones
+            const int row = advance_level<WAVES>(a, sh, P, done);
+            if (row >= 0) {
+                P.row = row;
+                P.ks = (size_t)row * N + P.u;
+                load_spec(a, P.ks, U);
+                en_next = U.enabled != 0;
+                if (a.p.zone_shapes == 1) {
+                    const int zlen = 6 * a.p.max_zones;
+                    for (int q = P.u; q < zlen; q += N) zd[q] = a.sc.zone_desc[(size_t)row * zlen + q];
+                }
+            }
+            if (a.p.zone_shapes == 1) lds_barrier<WAVES>();
+        }
+        if (done) {
+            if (a.pa.mem.mem_valid) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
+            code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
+            ratio = U.enabled ? U.hp / U.hmax : 0.0f;
+            heading_sincos(U.theta, su, cu);
+        }
+        int c0 = cnt[0], c1 = cnt[1];
+        if (a.p.num_levels > 0) {
+            // teams and placeholders may differ in the new level
+            const bool pred1[4] = {en_next && U.team == 0, en_next && U.team != 0, false, false};
+            int fresh[4];
+            env_counts(sh, P, N, pred1, fresh);
+            c0 = fresh[0];
+            c1 = fresh[1];
+        }
+        sh.st.share[P.l] = make_float2((en_next && U.team == 0) ? ratio : 0.0f,
+                                    (en_next && U.team != 0) ? ratio : 0.0f);
+        lds_barrier<WAVES>();
+        float f0, f1;
+        team_means(sh, P, N, c0, c1, f0, f1);
+        if (done) phi_next = f0 - f1;
+    }
+    if (has && P.u == 0) {
+        a.st.t[P.e] = done ? 0 : t_new;
+        a.st.phi_prev[P.e] = phi_next;
+        a.dones[P.e] = done ? 1 : 0;
+        // episode metrics: first loss of a unit, running allied return, summary at the end
+        int kills = 0;
+        if (want_kills) {
+            kills = a.st.kill_run[P.e];
+            if (kills == 0) kills = (cnt[3] < before[1] ? 1 : 0) | (cnt[2] < before[0] ? 2 : 0);
+            a.st.kill_run[P.e] = (int8_t)(done ? 0 : kills);
+        }
+        float ret = 0.0f;
+        if (a.st.ret_run) {
+            ret = a.st.ret_run[P.e] + r0;
+            a.st.ret_run[P.e] = done ? 0.0f : ret;
+        }
+        if (done) {
+            if (a.st.ep_count) a.st.ep_count[P.e] += 1;
+            if (a.st.ep_len) a.st.ep_len[P.e] = t_new;
+            if (a.st.ep_return && a.st.ret_run) a.st.ep_return[P.e] = ret;
+            if (a.st.ep_win) a.st.ep_win[P.e] = (m0 > m1) ? 1 : 0;
+            if (a.st.ep_first_kill && want_kills) a.st.ep_first_kill[P.e] = (int8_t)kills;
+        }
+    }
+    if (has) store_state(a, P.k, U);
+    C.cu = cu;
+    C.su = su;
+    C.ratio = ratio;
+    return any_done;
+}
+
+} // namespace tabx
