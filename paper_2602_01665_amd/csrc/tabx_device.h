@@ -38,7 +38,6 @@ struct KArgs {
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
     int       num_groups;          // workgroups that have envs to process
     int       zdesc_offset;        // elliptical zones: descriptor copy in dynamic LDS, floats
-    int       mask_offset;         // hit-all strikes: per-lane victim masks in dynamic LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
     int       cell_pow2;
@@ -120,9 +119,14 @@ struct Shared {
     static constexpr int L = 64 * WAVES;
     union {
         struct {                  // step stage
-            float4 pj[L];         // pair-loop record of a unit: x, y, r^2, flags
-            int2   hitrec[L];     // {designated victim (local index) or -1, damage bits}
-            float2 share[L];      // this unit's term in the team-0 / team-1 ratio sums
+            union {
+                float4 pj[L];     // collision partners: x, y, radius, mass
+                float4 aim0[L];   // combat, a striker's pose: x, y, cos(theta), sin(theta)
+                float2 share[L];  // afterwards: this unit's term in the team-0 / team-1 ratio sums
+            };
+            float4 aim1[L];       // ... its hurtbox: range | target team in the sign bit,
+                                  //     half-width, damage, cos(cone / 2)
+            unsigned long long best[L];   // ... the closest body in it: (distance^2 bits, index)
         } st;
         struct {                  // policy stage: what a deciding unit needs of the others
             float4 pose[L];       // x, y, cos(theta), sin(theta)

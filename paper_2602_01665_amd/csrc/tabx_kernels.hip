@@ -75,8 +75,7 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su);
     }
     bool restarted = false;
-    uint64_t *masks = reinterpret_cast<uint64_t *>(dyn_lds + a.mask_offset);
-    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, masks, P, U, code_u, C, forced);
+    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
     else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
     if (DO_STEP && DO_OBS && a.p.num_levels > 0 && restarted) {
         // zone slots of the envs that changed level
@@ -260,13 +259,9 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     dyn_floats = 4 * ((dyn_floats + 3) / 4 + (dyn_floats + 3) / 64 + 1);
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
     const size_t zdesc_floats = a.p.zone_shapes == 1 ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
-    // ... and, when a strike lands on everybody in the hurtbox, one victim mask per lane
-    const size_t zdesc_even = (zdesc_floats + 1) & ~(size_t)1;
-    const size_t mask_floats = a.p.hit_all ? (size_t)64 * WAVES * WAVES * 2 : 0;
-    const size_t dyn_bytes = (dyn_floats + zdesc_even + mask_floats) * sizeof(float);
-    const size_t step_bytes = (zdesc_even + mask_floats) * sizeof(float);
+    const size_t dyn_bytes = (dyn_floats + zdesc_floats) * sizeof(float);
+    const size_t step_bytes = zdesc_floats * sizeof(float);
     a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0 : (int)dyn_floats;
-    a.mask_offset = a.zdesc_offset + (int)zdesc_even;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);

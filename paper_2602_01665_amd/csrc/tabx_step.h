@@ -37,8 +37,7 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
 // level.  Returns whether any env of the workgroup restarted.
 template <int WAVES>
 __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, float *zd,
-                                         uint64_t *masks, Place &P, Unit &U, int &code_u,
-                                         Carry &C, int forced)
+                                         Place &P, Unit &U, int &code_u, Carry &C, int forced)
 {
     float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
     const int N = a.p.num_units;
@@ -127,96 +126,103 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         }
         heading_sincos(U.theta, su, cu);
     }
-    // flags: team of a unit alive at entry, 2 for anything that cannot be a target
-    sh.st.pj[P.l] = make_float4(U.x, U.y, U.radius * U.radius,
-                             __int_as_float(alive0 ? U.team : 2));
-    lds_barrier<WAVES>();
-
-    // stage 2b: attackable row of this unit over its env, closest valid target
-    // (strict "<" keeps the lowest index on ties).  Variants: the hurtbox also bounded by the
-    // sight cone's angle; the whole row kept as a bit mask when a strike lands on everybody.
+    // stage 2b: combat, seen from the victims.  Few units strike in a tick (the cooldowns see to
+    // that), so instead of every unit scanning its env for targets, every unit tests itself
+    // against the strikers of its env only.  A striker publishes its pose and hurtbox; each unit
+    // in that hurtbox (body circle against the forward rectangle, role filter, optionally the
+    // sight cone's angle) bids for "closest" with an LDS atomic minimum over the 64-bit key
+    // (squared distance bits, unit index): the smallest key is the closest valid body, the
+    // lowest index among equally distant ones.
     const bool cone_bound = a.p.hurtbox_cone != 0;
     const bool hit_all = a.p.hit_all != 0;
-    int target = -1;
-    {
-        const int want = (U.dmg < 0.0f) ? U.team : 1 - U.team;   // healers reach allies only
-        const float neg_hw = -U.hurt_hw;
-        float best = kInf;
-        if (!cone_bound && !hit_all) {
-            for (int jj = 0; jj < N; ++jj) {
-                const float4 J = sh.st.pj[P.base + jj];
-                const float dx = J.x - U.x;
-                const float dy = J.y - U.y;
-                float along;
-                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
-                const float d2 = (dx * dx) + (dy * dy);
-                const bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
-                const bool take = ok && (d2 < best);
-                best = take ? d2 : best;
-                target = take ? jj : target;
-            }
-        } else {
-            uint64_t row[WAVES] = {};
-            for (int jj = 0; jj < N; ++jj) {
-                const float4 J = sh.st.pj[P.base + jj];
-                const float dx = J.x - U.x;
-                const float dy = J.y - U.y;
-                float along;
-                const float g2 = hurtbox_gap2(dx, dy, cu, su, U.range, U.hurt_hw, neg_hw, along);
-                const float d2 = (dx * dx) + (dy * dy);
-                bool ok = (g2 <= J.z) && (__float_as_int(J.w) == want) && (jj != P.u);
-                if (cone_bound)
-                    ok = ok && ((d2 == 0.0f) || (along >= U.cos_half * __builtin_sqrtf(d2)));
-                const bool take = ok && (d2 < best);
-                best = take ? d2 : best;
-                target = take ? jj : target;
-                const uint64_t bit = (uint64_t)(ok ? 1 : 0) << (jj & 63);
-                row[0] |= (WAVES == 1 || jj < 64) ? bit : 0ull;
-                if (WAVES == 2) row[WAVES - 1] |= jj >= 64 ? bit : 0ull;
-            }
-            if (hit_all) {
-#pragma unroll
-                for (int w = 0; w < WAVES; ++w) masks[P.l * WAVES + w] = row[w];
-            }
-        }
-    }
     const bool eligible = has && alive0 && act == TABX_ACT_ATTACK && U.cd <= 0.0f;
     if (eligible) U.cd = U.cooldown;
-    const bool landed = eligible && target >= 0;
-    // designated victim; -2: everybody in this unit's mask
-    sh.st.hitrec[P.l] = make_int2(landed ? (hit_all ? -2 : target) : -1, __float_as_int(U.dmg));
-    lds_barrier<WAVES>();
-
-    // stage 2c: victim side.  Sum what the attackers that designated this unit
-    // deal, ascending attacker index; subtract once with the arena penalty; clamp.
     {
-        float acc = 0.0f;
-        bool struck = landed && U.dmg > 0.0f;
-        if (!hit_all) {
-            for (int ii = 0; ii < N; ++ii) {
-                const int2 h = sh.st.hitrec[P.base + ii];
-                const bool mine = h.x == P.u;
-                const float d = __int_as_float(h.y);
-                acc = acc + (mine ? d : 0.0f);
-                struck = struck || (mine && d > 0.0f);
-            }
-        } else {
-            const int word = WAVES == 1 ? 0 : (P.u >> 6);
-            for (int ii = 0; ii < N; ++ii) {
-                const int2 h = sh.st.hitrec[P.base + ii];
-                const uint64_t row = masks[(P.base + ii) * WAVES + word];
-                const bool mine = h.x == -2 && ((row >> (P.u & 63)) & 1ull);
-                const float d = __int_as_float(h.y);
-                acc = acc + (mine ? d : 0.0f);
-                struck = struck || (mine && d > 0.0f);
-            }
-        }
-        if (has && alive0) {
-            const float h = (U.hp - acc) - bdmg;
-            U.hp = clamp_between(h, 0.0f, U.hmax);
-            if (struck) U.reveal = a.p.reveal_time;
+        const int want = (U.dmg < 0.0f) ? U.team : 1 - U.team;   // healers reach allies only
+        // the attack range is never negative: its sign bit carries the team the strike is for
+        const float range_want = __int_as_float(__float_as_int(U.range) | (want << 31));
+        sh.st.aim0[P.l] = make_float4(U.x, U.y, cu, su);
+        sh.st.aim1[P.l] = make_float4(range_want, U.hurt_hw, U.dmg, U.cos_half);
+        sh.st.best[P.l] = ~0ull;
+    }
+    // the strikers of this lane's env, as bit masks over its unit indices
+    uint64_t strikers[WAVES];
+    {
+        const uint64_t b = __ballot(eligible);
+        if (WAVES == 1) {
+            strikers[0] = (b >> P.base) & (N >= 64 ? ~0ull : ((1ull << N) - 1ull));
+        } else if ((P.l & 63) == 0) {
+            sh.ballots[P.l >> 6][0] = b;
         }
     }
+    lds_barrier<WAVES>();
+    if (WAVES == 2) {
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) strikers[w] = sh.ballots[w][0];
+    }
+
+    float acc = 0.0f;              // what lands on this unit, strikers in ascending index
+    bool struck = false;           // ... and whether any of it was damage
+    {
+        const float r2 = U.radius * U.radius;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            uint64_t m = strikers[w];
+            while (m != 0ull) {
+                const int s_u = 64 * w + __builtin_ctzll(m);
+                m &= m - 1ull;
+                const float4 A0 = sh.st.aim0[P.base + s_u];
+                const float4 A1 = sh.st.aim1[P.base + s_u];
+                const int rb = __float_as_int(A1.x);
+                const float range = __int_as_float(rb & 0x7fffffff);
+                const int want = (rb >> 31) & 1;
+                const float dx = U.x - A0.x;
+                const float dy = U.y - A0.y;
+                float along;
+                const float g2 = hurtbox_gap2(dx, dy, A0.z, A0.w, range, A1.y, -A1.y, along);
+                const float d2 = (dx * dx) + (dy * dy);
+                bool ok = alive0 && (U.team == want) && (s_u != P.u) && (g2 <= r2);
+                if (cone_bound) ok = ok && ((d2 == 0.0f) || (along >= A1.w * __builtin_sqrtf(d2)));
+                if (ok) {
+                    const unsigned long long key =
+                        ((unsigned long long)(unsigned)__float_as_int(d2) << 32) | (unsigned)P.u;
+                    atomicMin(&sh.st.best[P.base + s_u], key);
+                    if (hit_all) {             // a strike lands on everybody in the hurtbox
+                        acc = acc + A1.z;
+                        struck = struck || (A1.z > 0.0f);
+                    }
+                }
+            }
+        }
+    }
+    lds_barrier<WAVES>();
+
+    // stage 2c: a strike has landed if anybody bid; unless everybody in the hurtbox is struck,
+    // the victims now look up which striker designated them
+    const bool landed = eligible && sh.st.best[P.l] != ~0ull;
+    if (!hit_all) {
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            uint64_t m = strikers[w];
+            while (m != 0ull) {
+                const int s_u = 64 * w + __builtin_ctzll(m);
+                m &= m - 1ull;
+                const bool mine = (unsigned)sh.st.best[P.base + s_u] == (unsigned)P.u;
+                const float d = sh.st.aim1[P.base + s_u].z;
+                acc = acc + (mine ? d : 0.0f);
+                struck = struck || (mine && d > 0.0f);
+            }
+        }
+    }
+    struck = struck || (landed && U.dmg > 0.0f);
+    if (has && alive0) {
+        // subtract once, together with the arena penalty; clamp
+        const float h = (U.hp - acc) - bdmg;
+        U.hp = clamp_between(h, 0.0f, U.hmax);
+        if (struck) U.reveal = a.p.reveal_time;
+    }
+    // (the ratio terms written next share LDS with the strikers' poses, which nobody reads any
+    // more: the bids above were the last use, and a barrier has passed since)
 
     // stage 3: zone effects at the new position, alive flag
     float ratio = 0.0f;
