@@ -39,6 +39,8 @@ struct KArgs {
     int       num_groups;          // workgroups that have envs to process
     int       zdesc_offset;        // elliptical zones: descriptor copy in dynamic LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
+    int       obs_chunks;          // workgroups that share the observers of one env group (>= 1)
+    int       obs_per_chunk;       // observers per such workgroup (a multiple of rows_per_flush)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
     int       cell_pow2;
     PolicyArgs pa;
@@ -107,6 +109,7 @@ struct Unit {
 // workgroup lane of the env's unit 0, e = env index, k = e * N + u.
 struct Place {
     int grp;           // which run of G envs this workgroup owns
+    int chunk;         // which share of the observers of these envs it writes (observe stage)
     int l, g, u, base, e;
     bool has;
     size_t k;
@@ -284,7 +287,10 @@ __device__ __forceinline__ Place locate(const KArgs &a)
     // Workgroups are dealt to the 8 XCDs round robin; give each XCD one contiguous eighth of
     // the env range, so that neighbouring env groups, which share the cache lines at the ends
     // of their SoA segments, meet in the same L2.
-    P.grp = (int)(blockIdx.x & 7) * a.groups_per_xcd + (int)(blockIdx.x >> 3);
+    const int slot = (int)(blockIdx.x >> 3);
+    const int in_xcd = a.obs_chunks > 1 ? slot / a.obs_chunks : slot;
+    P.chunk = slot - in_xcd * a.obs_chunks;
+    P.grp = in_xcd < a.groups_per_xcd ? (int)(blockIdx.x & 7) * a.groups_per_xcd + in_xcd : a.num_groups;
     P.e = P.grp * a.envs_per_block + P.g;
     P.has = P.grp < a.num_groups && P.g < a.envs_per_block && P.u < N && P.e < a.p.num_envs;
     P.base = P.has ? P.l - P.u : 0;

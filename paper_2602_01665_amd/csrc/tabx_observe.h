@@ -110,7 +110,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         sh.ob.pose[P.l] = make_float4(U.x, U.y, cu, su);
         sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
         sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | (key << 8);
-        if (has && a.action_mask) a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
+        if (has && a.action_mask && P.chunk == 0)
+            a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
     }
     // what differs between a unit's block in its own row and in another unit's row
     const int own_mask = enabled ? -1 : 0;
@@ -157,7 +158,11 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     float *out = a.obs + (size_t)P.grp * G * N * D;
     uint64_t my_row = 0;
     const int blk_row0 = (WAVES == 1) ? P.g * R * Dp : 0;
-    for (int i0 = 0; i0 < N; i0 += R) {
+    // the observers this workgroup writes the rows of: all of them, or its share when the rows
+    // of an env group are spread over several short-lived workgroups
+    const int i_begin = P.chunk * a.obs_per_chunk;
+    const int i_end = (i_begin + a.obs_per_chunk < N) ? i_begin + a.obs_per_chunk : N;
+    for (int i0 = i_begin; i0 < i_end; i0 += R) {
     for (int rr = 0; rr < R; ++rr) {
         const int i = i0 + rr;
         const int oi = P.base + i;
@@ -293,7 +298,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
 
     if (a.vis_mask) {
         lds_barrier<WAVES>();
-        if (has) {
+        if (has && P.u >= i_begin && P.u < i_end) {
             if (WAVES == 1) {
                 const uint64_t range = N >= 64 ? ~0ull : ((1ull << N) - 1ull);
                 a.vis_mask[P.k] = (my_row >> P.base) & range;
