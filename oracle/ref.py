@@ -19,6 +19,10 @@ _F = C.POINTER(C.c_float)
 _B = C.POINTER(C.c_ubyte)
 
 
+_I8 = C.POINTER(C.c_byte)
+_I32 = C.POINTER(C.c_int)
+
+
 class RefParams(C.Structure):
     _fields_ = [(n, C.c_int) for n in
                 ("num_envs", "num_units", "grid_w", "grid_h", "max_zones", "max_steps")] + \
@@ -26,7 +30,7 @@ class RefParams(C.Structure):
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
                [("zone_shapes", C.c_int), ("num_levels", C.c_int), ("level_seed", C.c_uint),
-                ("hurtbox_cone", C.c_int), ("hit_all", C.c_int)]
+                ("hurtbox_cone", C.c_int), ("hit_all", C.c_int), ("env_ids", _I32)]
 
 
 _SC_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",
@@ -41,8 +45,6 @@ class RefScenario(C.Structure):
                                                 ("zone_desc", _F)]
 
 
-_I8 = C.POINTER(C.c_byte)
-_I32 = C.POINTER(C.c_int)
 _METRICS = (("ret_run", _F, np.float32), ("kill_run", _I8, np.int8), ("ep_count", _I32, np.int32),
             ("ep_len", _I32, np.int32), ("ep_return", _F, np.float32), ("ep_win", _I8, np.int8),
             ("ep_first_kill", _I8, np.int8))
@@ -149,7 +151,12 @@ class RefEnv:
             zd = None
         self.sc["zone_desc"] = zd
 
-        self.cp = RefParams(**{k: self.p.get(k, 0) for k, _ in RefParams._fields_})
+        self.env_ids = None
+        if self.p.get("env_ids") is not None:
+            self.env_ids = np.ascontiguousarray(self.p["env_ids"], np.int32)
+            assert self.env_ids.shape == (E,)
+        self.cp = RefParams(**{k: self.p.get(k, 0) for k, _ in RefParams._fields_
+                               if k != "env_ids"}, env_ids=_ptr(self.env_ids, _I32))
         self.csc = RefScenario(**{k: _ptr(self.sc[k], _F) for k in _SC_FLOAT},
                                team=_ptr(self.sc["team"], _B),
                                enabled=_ptr(self.sc["enabled"], _B),

@@ -71,6 +71,12 @@ inline float clampf(float v, float lo, float hi)
     return v < lo ? lo : (v > hi ? hi : v);
 }
 
+/* The env's index for the counter-based random draws. */
+unsigned env_id(const RefParams &P, int e)
+{
+    return (unsigned)(P.env_ids ? P.env_ids[e] : e);
+}
+
 /* Which row of the scenario arrays configures env e: its own (no level bank) or the level it
  * currently plays (the configuration is applied at reset, Sec. 4.1; App. A "Environment
  * Parameters"). */
@@ -108,7 +114,7 @@ void advance_level(const RefParams &P, RefState &st, int e)
     const unsigned L = (unsigned)P.num_levels;
     st.level[e] = (int)((unsigned)st.next_level[e] % L);
     const unsigned n = (unsigned)st.level_draws[e];
-    st.next_level[e] = (int)(hash32(P.level_seed, (unsigned)e, 0u, n, 3u) % L);
+    st.next_level[e] = (int)(hash32(P.level_seed, env_id(P, e), 0u, n, 3u) % L);
     st.level_draws[e] = (int)(n + 1u);
 }
 
@@ -700,7 +706,7 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
     }
 
     const unsigned tick = (unsigned)st.t[e];
-    const unsigned coin = hash32(pol.seed, (unsigned)e, (unsigned)i, tick, 2u) & 1u;
+    const unsigned coin = hash32(pol.seed, env_id(P, e), (unsigned)i, tick, 2u) & 1u;
     const int search_turn = coin ? ACT_ROT_L : ACT_ROT_R;
     int act = ACT_NOOP;
     if (tgt >= 0) {
@@ -773,9 +779,9 @@ int policy_unit(const RefParams &P, const RefScenario &S, const RefState &st,
     }
 
     /* epsilon-greedy override */
-    const unsigned h0 = hash32(pol.seed, (unsigned)e, (unsigned)i, tick, 0u);
+    const unsigned h0 = hash32(pol.seed, env_id(P, e), (unsigned)i, tick, 0u);
     const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
-    if (u0 < pol.epsilon) act = (int)(hash32(pol.seed, (unsigned)e, (unsigned)i, tick, 1u) & 7u);
+    if (u0 < pol.epsilon) act = (int)(hash32(pol.seed, env_id(P, e), (unsigned)i, tick, 1u) & 7u);
     return act;
 }
 

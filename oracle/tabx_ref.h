@@ -51,6 +51,9 @@ typedef struct RefParams {
                                    the sight cone's angle (any distance)                         */
     int   hit_all;              /* 0: a strike lands on the closest valid body in the hurtbox;
                                    1: on every valid body in it                                  */
+    const int *env_ids;         /* NULL, or [E]: the index each env has in the batch it was taken
+                                   from; the random draws (level draws, heuristic policy) are
+                                   keyed by it, so a sample of a large batch replays exactly     */
 } RefParams;
 
 typedef struct RefScenario {

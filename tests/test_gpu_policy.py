@@ -184,3 +184,56 @@ def test_uncontrolled_entries_are_left_alone_and_errors():
         B.tabx_heuristic_actions(gpu.params, gpu.scenario, gpu.state,
                                  B.TabxPolicy(**dict(I.policy("expert", 1), xi=float("nan"))),
                                  gpu.memory, None, a)
+
+
+def test_full_size_scripted_tick_with_level_bank():
+    """The launch `bench.py --policy` times (16384 envs 10v10, adversaries scripted inside the
+    tick), here also with a bank of levels; the checker replays a sample of the envs under their
+    original indices and every tick of them is compared."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    from tests.parity import compare_metrics
+    w = I.WORKLOADS["c3_16384env_10v10"]
+    E, N, L, steps = w.num_envs, w.num_units, 96, 300
+    _say(f"[gpu] full size scripted tick E={E} levels={L} steps={steps}")
+    p = I.make_params(w, max_steps=64, num_levels=L, level_seed=5)
+    sc = I.make_scenario(w, L)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, 1, E - 1], rng.choice(E, 9, replace=False)]))
+    ref = RefEnv(dict(p, num_envs=len(rows), env_ids=rows), sc)
+    gpu = TabxEnv(p, sc, want_metrics=True)
+    ref.st["next_level"][:] = rows % L           # what the full batch queues for these envs
+    ref.reset()
+    gpu.reset()
+    rows_t = torch.from_numpy(rows).to("cuda:0")
+    team = torch.from_numpy(np.ascontiguousarray(sc["team"])).to("cuda:0")
+    pol = I.policy("medium", w.seed)
+    # the bank's teams are the same in every level of this workload: one mask serves all
+    assert (sc["team"] == sc["team"][0]).all()
+    ctl_d = team[:1].expand(E, N).contiguous()
+    ctl = np.broadcast_to(sc["team"][0], (len(rows), N)).astype(np.uint8)
+    dones = 0
+    for s in range(steps):
+        a = I.actions_for_step(w.seed, s, E, N)
+        ad = torch.from_numpy(a).to("cuda:0")
+        ar = np.ascontiguousarray(a[rows])
+        gpu.policy_step_observe(pol, ctl_d, ad)
+        ref.policy_step(pol, ctl, ar)
+        ref.observe()
+        torch.cuda.synchronize()
+        where = f"full size scripted step {s}: "
+        assert np.array_equal(ad[rows_t].cpu().numpy(), ar), where + "actions"
+        st = {k: (v.reshape(E, N)[rows_t] if v.numel() == E * N else v[rows_t]).cpu().numpy()
+              for k, v in gpu.st.items()}
+        compare_state(st, ref.st, where)
+        compare_outputs(gpu, ref, where, rows=rows_t)
+        compare_metrics(gpu, ref, where, rows=rows_t)
+        valid = gpu.mem["mem_valid"].view(E, N)[rows_t].cpu().numpy()
+        assert np.array_equal(valid, ref.mem["mem_valid"]), where + "mem_valid"
+        dones += int(ref.dones.sum())
+        if s % 100 == 0:
+            _say(f"[gpu]   step {s} ok")
+    _say(f"[gpu]   sampled episodes ended {dones}")
+    assert dones > len(rows)
+    assert torch.isfinite(gpu.obs).all()

@@ -174,3 +174,32 @@ def test_level_draws_are_uniform_and_reproducible():
     # k-th auto-reset (k from 0) plays draw k
     h = ref.lib().tabx_ref_hash
     assert all(a[k, e] == h(21, e, 0, k, 3) % L for k in (0, 5, 59) for e in (0, 3, 63))
+
+
+def test_a_sample_of_the_batch_replays_with_its_env_ids():
+    """Draws are keyed by the env's index: a sub-batch given the original indices reproduces
+    its envs of the full batch tick for tick (level draws and the heuristic policy alike)."""
+    w = I.WORKLOADS["c2_4096env_5v5"]
+    E, L, N = 24, 5, w.num_units
+    sc = I.make_scenario(w, L)
+    p = I.make_params(w, E, max_steps=6, num_levels=L, level_seed=17)
+    rows = np.array([2, 3, 11, 23])
+    full = ref.RefEnv(p, sc)
+    part = ref.RefEnv(dict(p, num_envs=len(rows), env_ids=rows), sc)
+    full.reset()
+    part.st["next_level"][:] = full.st["level"][rows]      # both start from the same levels
+    part.reset()
+    part.st["next_level"][:] = full.st["next_level"][rows]
+    part.st["level_draws"][:] = full.st["level_draws"][rows]
+    pol = I.policy("medium", 8)
+    ctl_f = np.ones((E, N), np.uint8)
+    ctl_p = np.ones((len(rows), N), np.uint8)
+    for s in range(60):
+        af = np.zeros((E, N), np.uint8)
+        ap = np.zeros((len(rows), N), np.uint8)
+        full.policy_step(pol, ctl_f, af)
+        part.policy_step(pol, ctl_p, ap)
+        assert np.array_equal(af[rows], ap), s
+        for k in full.st:
+            assert np.array_equal(full.st[k][rows], part.st[k]), (s, k)
+    assert full.st["ep_count"].sum() > E
