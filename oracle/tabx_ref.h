@@ -17,7 +17,13 @@
  * Parity pins (tests/test_oracle_*.py): hand-worked combat, heal, cooldown,
  * boundary, terrain and reward cases derived from the paper's unit table and
  * formulas; invariants; brute-force visibility/attackability with an
- * independent double-precision atan2/hypot formulation; sincos against libm.
+ * independent double-precision atan2/hypot formulation; sincos against libm;
+ * the heuristic policy branch by branch on hand-placed units, its tier table
+ * against the paper's; the level bank's queue semantics and an identity bank
+ * against the plain scenario; the hurtbox variants by hand and by a float64
+ * brute force of one tick's health.  The heuristic's numbers the paper does
+ * not give (half-range standoff, arrival radius, the hash behind its random
+ * draws) are this build's readings: "parity unpinned" against the authors'.
  * The free parameters the paper does not print (time step, turn rate, sight
  * cone, reveal duration, zone magnitudes) are inputs; their default values are
  * "parity unpinned" with respect to the authors' own code, which is not
