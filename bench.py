@@ -72,7 +72,11 @@ def main() -> int:
                     help="time tabx_step + tabx_observe as two launches instead of the fused one")
     ap.add_argument("--policy", default=None, metavar="TIER",
                     help="the adversaries are moved by the heuristic policy of this tier inside "
-                         "the tick launch (tabx_policy_step_observe); not the headline tick")
+                         "the tick launch (tabx_scripted_step_observe: they decide in the observe "
+                         "stage); with --separate as tabx_heuristic_actions + tabx_step_observe, "
+                         "with --policy-scan as tabx_policy_step_observe; not the headline tick")
+    ap.add_argument("--policy-scan", action="store_true",
+                    help="with --policy: the policy as a stage of its own in front of the step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (environments are independent; more GPUs "
@@ -111,14 +115,18 @@ def main() -> int:
         if policy and args.separate:
             env.heuristic_actions(policy, scripted, a, stream)
             env.step_observe(a, stream)
-        elif policy:
+        elif policy and args.policy_scan:
             env.policy_step_observe(policy, scripted, a, stream)
+        elif policy:
+            env.scripted_step_observe(policy, scripted, a, stream)
         elif args.separate:
             env.step(a, stream)
             env.observe(stream)
         else:
             env.step_observe(a, stream)
 
+    if policy and not args.separate and not args.policy_scan:
+        env.prime_scripted(policy, scripted, stream)
     for s in range(args.warmup):
         tick(s)
     torch.cuda.synchronize()

@@ -224,6 +224,7 @@ typedef struct TabxPolicy {
 typedef struct TabxPolicyMemory {
     float   *mem_x, *mem_y;
     uint8_t *mem_valid;
+    uint8_t *next_action;      /* [E * N], only for tabx_scripted_step_observe (else may be NULL) */
 } TabxPolicyMemory;
 
 /* Chooses actions[e * N + u] for every enabled, living unit with controlled[e * N + u] != 0
@@ -266,6 +267,22 @@ int tabx_policy_step_observe(const TabxParams *params, const TabxScenario *scena
                              const TabxPolicyMemory *memory, const uint8_t *controlled,
                              uint8_t *actions, float *rewards, uint8_t *dones, float *obs,
                              uint64_t *vis_mask, uint8_t *action_mask, void *stream);
+
+/* The tick for training against scripted units: same results as tabx_policy_step_observe, but
+ * the scripted units decide at the END of the call, on the state the call leaves behind, from
+ * the pair tests its observation rows are made of anyway (so the policy costs a few atomics
+ * instead of a second all-pairs scan); the decision waits in memory->next_action and the next
+ * call applies it (and copies it into `actions`).  The caller primes memory->next_action with
+ *     tabx_heuristic_actions(..., controlled, memory->next_action)
+ * after tabx_reset and after anything else that changes the state, the policy or `controlled`
+ * behind the library's back (a restored snapshot, another tier).  Between such events the
+ * sequence of states, actions, memories and observations is identical to the one
+ * tabx_policy_step_observe produces. */
+int tabx_scripted_step_observe(const TabxParams *params, const TabxScenario *scenario,
+                               const TabxState *state, const TabxPolicy *policy,
+                               const TabxPolicyMemory *memory, const uint8_t *controlled,
+                               uint8_t *actions, float *rewards, uint8_t *dones, float *obs,
+                               uint64_t *vis_mask, uint8_t *action_mask, void *stream);
 
 const char *tabx_strerror(int code);
 

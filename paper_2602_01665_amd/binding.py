@@ -25,7 +25,7 @@ STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
 
 EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
            "tabx_step_observe", "tabx_global_state", "tabx_heuristic_actions",
-           "tabx_policy_step_observe", "tabx_strerror")
+           "tabx_policy_step_observe", "tabx_scripted_step_observe", "tabx_strerror")
 
 _I8 = C.POINTER(C.c_int8)
 _I32 = C.POINTER(C.c_int32)
@@ -71,7 +71,7 @@ class TabxPolicy(C.Structure):
 
 
 class TabxPolicyMemory(C.Structure):
-    _fields_ = [("mem_x", _F), ("mem_y", _F), ("mem_valid", _U8)]
+    _fields_ = [("mem_x", _F), ("mem_y", _F), ("mem_valid", _U8), ("next_action", _U8)]
 
 
 def load_library(path: str = LIB_PATH) -> C.CDLL:
@@ -92,6 +92,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
                                            C.POINTER(TabxPolicyMemory), V, V, V]
     lib.tabx_policy_step_observe.argtypes = [P, S, T, C.POINTER(TabxPolicy),
                                              C.POINTER(TabxPolicyMemory)] + [V] * 8
+    lib.tabx_scripted_step_observe.argtypes = lib.tabx_policy_step_observe.argtypes
     lib.tabx_strerror.argtypes = [C.c_int]
     lib.tabx_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -182,6 +183,16 @@ def tabx_policy_step_observe(params, scenario, state, policy, memory, controlled
            "tabx_policy_step_observe")
 
 
+def tabx_scripted_step_observe(params, scenario, state, policy, memory, controlled, actions,
+                               rewards, dones, obs, vis_mask=None, action_mask=None, stream=None):
+    _check(_lib.tabx_scripted_step_observe(C.byref(params), C.byref(scenario), C.byref(state),
+                                           C.byref(policy), C.byref(memory), _ptr(controlled),
+                                           _ptr(actions), _ptr(rewards), _ptr(dones), _ptr(obs),
+                                           _ptr(vis_mask), _ptr(action_mask),
+                                           _stream_ptr(stream)),
+           "tabx_scripted_step_observe")
+
+
 class TabxEnv:
     """Device buffers of one batch of environments plus the calls on them."""
 
@@ -258,10 +269,12 @@ class TabxEnv:
             n = self.E * self.N
             self.mem = {"mem_x": torch.zeros(n, dtype=torch.float32, device=self.device),
                         "mem_y": torch.zeros(n, dtype=torch.float32, device=self.device),
-                        "mem_valid": torch.zeros(n, dtype=torch.uint8, device=self.device)}
+                        "mem_valid": torch.zeros(n, dtype=torch.uint8, device=self.device),
+                        "next_action": torch.zeros(n, dtype=torch.uint8, device=self.device)}
             self.memory = TabxPolicyMemory(mem_x=_cast(self.mem["mem_x"], _F),
                                            mem_y=_cast(self.mem["mem_y"], _F),
-                                           mem_valid=_cast(self.mem["mem_valid"], _U8))
+                                           mem_valid=_cast(self.mem["mem_valid"], _U8),
+                                           next_action=_cast(self.mem["next_action"], _U8))
         return self.memory
 
     def heuristic_actions(self, policy: dict, controlled, actions, stream=None):
@@ -275,6 +288,17 @@ class TabxEnv:
         tabx_policy_step_observe(self.params, self.scenario, self.state, TabxPolicy(**policy),
                                  self._policy_memory(), controlled, actions, self.rewards,
                                  self.dones, self.obs, self.vis, self.amask, stream)
+
+    def prime_scripted(self, policy: dict, controlled, stream=None):
+        """Decides the scripted units' first actions (after a reset or any outside change)."""
+        self._policy_memory()
+        tabx_heuristic_actions(self.params, self.scenario, self.state, TabxPolicy(**policy),
+                               self.memory, controlled, self.mem["next_action"], stream)
+
+    def scripted_step_observe(self, policy: dict, controlled, actions, stream=None):
+        tabx_scripted_step_observe(self.params, self.scenario, self.state, TabxPolicy(**policy),
+                                   self._policy_memory(), controlled, actions, self.rewards,
+                                   self.dones, self.obs, self.vis, self.amask, stream)
 
     def reset(self, env_mask=None, stream=None):
         tabx_reset(self.params, self.scenario, self.state, env_mask, stream)

@@ -18,6 +18,7 @@ struct PolicyArgs {
     TabxPolicyMemory mem;          // mem_valid == nullptr: no policy in this launch
     const uint8_t   *controlled;
     uint8_t         *actions_out;
+    uint8_t         *next_action;  // scripted tick: decided at the end of one call, applied by the next
 };
 
 struct KArgs {
@@ -37,7 +38,9 @@ struct KArgs {
     int       copy_passes;         // ceil(G * R * row_pitch / 4 / lanes), <= kMaxPasses
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
     int       num_groups;          // workgroups that have envs to process
-    int       zdesc_offset;        // elliptical zones: descriptor copy in dynamic LDS, floats
+    int       zdesc_offset;        // copy of the zone descriptors in dynamic LDS, floats
+    int       zdesc_staged;        // ... which exists for elliptical zones and for deciding units
+    int       script_offset;       // scripted units deciding in the observe stage: their LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
     int       obs_chunks;          // workgroups that share the observers of one env group (>= 1)
     int       obs_per_chunk;       // observers per such workgroup (a multiple of rows_per_flush)
@@ -94,6 +97,8 @@ __device__ __forceinline__ float median3(float v, float lo, float hi)
 struct Carry {
     float cu, su;      // cosine / sine of the heading
     float ratio;       // hp / hmax
+    int   tick;        // the env's tick counter after the step
+    bool  restarted;   // the env's episode ended in this step
 };
 
 // Registers of one unit: mutable state, then read-only specification.

@@ -35,7 +35,7 @@
 
 namespace tabx {
 
-template <int WAVES, bool DO_POLICY, bool DO_STEP, bool DO_OBS>
+template <int WAVES, bool DO_POLICY, bool DO_STEP, bool DO_OBS, bool SCRIPT = false>
 __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
 {
     __shared__ Shared<WAVES> sh;
@@ -49,10 +49,11 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
     }
     ZoneRegs Zr = {};
     if (DO_OBS) Zr = load_zone_regs<WAVES>(a, P);
-    // elliptical zones: the descriptors of the workgroup's envs sit in LDS for the lookups
+    // elliptical zones, deciding units: the descriptors of the workgroup's envs sit in LDS for
+    // the zone lookups and the bush search
     const int zlen = 6 * a.p.max_zones;
     float *zdesc = dyn_lds + a.zdesc_offset;
-    if (a.p.zone_shapes == 1) {
+    if (a.zdesc_staged) {
         const int G = a.envs_per_block;
         for (int q = P.l; q < G * zlen; q += 64 * WAVES) {
             const int g = q / zlen;
@@ -63,16 +64,25 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         lds_barrier<WAVES>();
     }
     float *zd = zdesc + (P.has ? P.g : 0) * zlen;
-    Carry C = {1.0f, 0.0f, 0.0f};
+    Carry C = {1.0f, 0.0f, 0.0f, 0, false};
     float zeff_unused = 0.0f;
     int forced = -1;
+    if (SCRIPT) {
+        // the action this unit decided on at the end of the previous call
+        const bool decides = P.has && U.enabled && U.alive &&
+                             (!a.pa.controlled || a.pa.controlled[P.k]);
+        if (decides) {
+            forced = a.pa.next_action[P.k];
+            a.pa.actions_out[P.k] = (uint8_t)forced;
+        }
+    }
     if (DO_POLICY) {
         float cu = 1.0f, su = 0.0f;
         if (P.has) {
             code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
             heading_sincos(U.theta, su, cu);
         }
-        forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su);
+        forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su, zd);
     }
     bool restarted = false;
     if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
@@ -82,7 +92,9 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         const int row = Zr.lane ? sh.rows[Zr.zg] : -1;
         if (row >= 0) Zr = load_zone_regs<WAVES>(a, P, row);
     }
-    if (DO_OBS) observe_env<WAVES, DO_STEP>(a, sh, dyn_lds, P, U, code_u, C, Zr);
+    if (SCRIPT && !DO_STEP && P.has) C.tick = a.st.t[P.e];
+    ScriptLds<WAVES> *script = reinterpret_cast<ScriptLds<WAVES> *>(dyn_lds + a.script_offset);
+    if (DO_OBS) observe_env<WAVES, DO_STEP, SCRIPT>(a, sh, dyn_lds, P, U, code_u, C, Zr, script, zd);
 }
 
 template <int WAVES>
@@ -175,7 +187,7 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
 // ------------------------------------------------------------------ host side
 
 enum Mode { MODE_RESET, MODE_STEP, MODE_OBSERVE, MODE_STEP_OBSERVE, MODE_POLICY,
-            MODE_POLICY_STEP_OBSERVE };
+            MODE_POLICY_STEP_OBSERVE, MODE_SCRIPTED_STEP_OBSERVE };
 
 static bool aligned(const void *p, size_t n) { return ((uintptr_t)p % n) == 0; }
 
@@ -258,10 +270,14 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     // ... with one spare 16-byte chunk after every 16 (see staged_chunk)
     dyn_floats = 4 * ((dyn_floats + 3) / 4 + (dyn_floats + 3) / 64 + 1);
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
-    const size_t zdesc_floats = a.p.zone_shapes == 1 ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
-    const size_t dyn_bytes = (dyn_floats + zdesc_floats) * sizeof(float);
+    const size_t zdesc_floats = a.zdesc_staged ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
+    // ... and by the bidding area of scripted units that decide in the observe stage
+    const size_t zdesc_even = (zdesc_floats + 1) & ~(size_t)1;
+    const size_t script_floats = mode == MODE_SCRIPTED_STEP_OBSERVE ? sizeof(ScriptLds<WAVES>) / 4 : 0;
+    const size_t dyn_bytes = (dyn_floats + zdesc_even + script_floats) * sizeof(float);
     const size_t step_bytes = zdesc_floats * sizeof(float);
     a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0 : (int)dyn_floats;
+    a.script_offset = a.zdesc_offset + (int)zdesc_even;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
@@ -286,6 +302,10 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
         hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, true, true>), grid, block, dyn_bytes,
                            stream, a);
         break;
+    case MODE_SCRIPTED_STEP_OBSERVE:
+        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true, true>), grid, block,
+                           dyn_bytes, stream, a);
+        break;
     }
 }
 
@@ -301,15 +321,17 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     if (p->num_envs == 0) return TABX_OK;          // empty batch: nothing to validate or do
     if ((rc = check_scenario(p, sc))) return rc;
     if ((rc = check_state(p, st))) return rc;
-    const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE;
+    const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE ||
+                          mode == MODE_SCRIPTED_STEP_OBSERVE;
     const bool stepping = mode == MODE_STEP || mode == MODE_STEP_OBSERVE ||
-                          mode == MODE_POLICY_STEP_OBSERVE;
+                          mode == MODE_POLICY_STEP_OBSERVE || mode == MODE_SCRIPTED_STEP_OBSERVE;
     const bool observing = mode == MODE_OBSERVE || mode == MODE_STEP_OBSERVE ||
-                           mode == MODE_POLICY_STEP_OBSERVE;
+                           mode == MODE_POLICY_STEP_OBSERVE || mode == MODE_SCRIPTED_STEP_OBSERVE;
     if (deciding) {
         if (!policy || !memory || !actions_out) return TABX_ERR_NULL;
         if (!memory->mem_x || !memory->mem_y || !memory->mem_valid) return TABX_ERR_NULL;
         if (!aligned(memory->mem_x, 4) || !aligned(memory->mem_y, 4)) return TABX_ERR_ALIGN;
+        if (mode == MODE_SCRIPTED_STEP_OBSERVE && !memory->next_action) return TABX_ERR_NULL;
         const float fin[] = {policy->epsilon, policy->xi, policy->assassin_speed, policy->ranger_range};
         for (float v : fin)
             if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
@@ -335,11 +357,13 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     a.action_mask = action_mask;
     a.obs_dim = 16 * p->num_units + 6 * p->max_zones;
     a.pa = {};
+    a.zdesc_staged = (p->zone_shapes == 1 || (deciding && p->max_zones > 0)) ? 1 : 0;
     if (deciding) {
         a.pa.pol = *policy;
         a.pa.mem = *memory;
         a.pa.controlled = controlled;
         a.pa.actions_out = actions_out;
+        a.pa.next_action = memory->next_action;
     }
 
     hipStream_t s = (hipStream_t)stream;
@@ -482,6 +506,17 @@ int tabx_policy_step_observe(const TabxParams *p, const TabxScenario *sc, const 
 {
     return tabx::run(tabx::MODE_POLICY_STEP_OBSERVE, p, sc, st, actions, nullptr, rewards, dones,
                      obs, vis_mask, action_mask, stream, policy, memory, controlled, actions);
+}
+
+int tabx_scripted_step_observe(const TabxParams *p, const TabxScenario *sc, const TabxState *st,
+                               const TabxPolicy *policy, const TabxPolicyMemory *memory,
+                               const uint8_t *controlled, uint8_t *actions, float *rewards,
+                               uint8_t *dones, float *obs, uint64_t *vis_mask,
+                               uint8_t *action_mask, void *stream)
+{
+    return tabx::run(tabx::MODE_SCRIPTED_STEP_OBSERVE, p, sc, st, actions, nullptr, rewards,
+                     dones, obs, vis_mask, action_mask, stream, policy, memory, controlled,
+                     actions);
 }
 
 const char *tabx_strerror(int code)

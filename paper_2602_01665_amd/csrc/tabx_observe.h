@@ -1,6 +1,7 @@
 // Observe stage of the TABX tick (App. A "Observation and Global State").
 #pragma once
 #include "tabx_device.h"
+#include "tabx_policy.h"   // the scripted units' rule cascade
 
 #pragma clang fp contract(off)
 
@@ -65,10 +66,29 @@ __device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &
 // Where 16-byte chunk c of the staged row images lives in LDS.
 __device__ __forceinline__ int staged_chunk(int c) { return c + (c >> 4); }
 
-template <int WAVES, bool CARRIED>
+// LDS of the scripted units that decide their next action inside the observe stage: per
+// deciding unit the smallest bids for "target" and "nearest enemy" and the "something to
+// strike" flag, per unit what a bidder or a decider needs beyond the observe-stage records.
+template <int WAVES>
+struct ScriptLds {
+    static constexpr int L = 64 * WAVES;
+    unsigned long long tkey[L];   // role key << 40 | bits(distance^2) << 8 | index << 1 | in hurtbox
+    unsigned long long nkey[L];   // bits(distance^2) << 32 | index
+    int                canhit[L];
+    float2             extra[L];  // body radius, max health
+};
+
+// SCRIPT: the units the heuristic policy moves decide their next action here, from the very
+// pair tests the observation rows are made of (App. A "Role-Appropriate Heuristic Policy
+// Mechanism": a unit acts on what it sees and can reach).  While observer i's pass runs,
+// every unit it sees bids with LDS atomic minima for "i's target" (key: the role's order,
+// then distance, then index, with "in i's hurtbox" riding in the lowest bit) and for "i's
+// nearest enemy"; afterwards each deciding unit reads its winners and runs the rule cascade.
+template <int WAVES, bool CARRIED, bool SCRIPT>
 __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, float *stg,
                                             const Place &P, const Unit &U, int code_u,
-                                            const Carry &C, const ZoneRegs &Zr)
+                                            const Carry &C, const ZoneRegs &Zr,
+                                            ScriptLds<WAVES> *script, const float *zd)
 {
     constexpr int LANES = 64 * WAVES;
     const int N = a.p.num_units;
@@ -109,7 +129,17 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const int key = in_bush ? my_code : 0x100;         // 0x100 matches no cell code
         sh.ob.pose[P.l] = make_float4(U.x, U.y, cu, su);
         sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
-        sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | (key << 8);
+        int role = 0;
+        if (SCRIPT) {
+            const bool decides = enabled && alive && (!a.pa.controlled || a.pa.controlled[P.k]);
+            role = (U.speed >= a.pa.pol.assassin_speed ? 0x10 : 0) | (decides ? 0x20 : 0);
+            script->tkey[P.l] = ~0ull;
+            script->nkey[P.l] = ~0ull;
+            script->canhit[P.l] = 0;
+            script->extra[P.l] = make_float2(U.radius, has ? U.hmax : 0.0f);
+        }
+        sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | role |
+                       (key << 8);
         if (has && a.action_mask && P.chunk == 0)
             a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
     }
@@ -154,6 +184,17 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
 
     lds_barrier<WAVES>();
 
+    // scripted deciders: what this unit contributes to a bid, whoever the observer is
+    bool injured_me = false;
+    unsigned rank_me = 0;          // how many units of the env have a smaller maximum health
+    unsigned order_heal = 0, key_tail = 0;
+    if (SCRIPT) {
+        injured_me = U.hp < U.hmax;
+        order_heal = injured_me ? 0u : 1u;
+        key_tail = (unsigned)P.u << 1;
+        for (int jj = 0; jj < N; ++jj) rank_me += script->extra[P.base + jj].y < U.hmax ? 1u : 0u;
+    }
+
     // ---- one pass per observer index i: every lane's unit seen from observer i of its env
     float *out = a.obs + (size_t)P.grp * G * N * D;
     uint64_t my_row = 0;
@@ -186,6 +227,25 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const bool seen = pair && in_range && in_cone && !concealed;
         const bool hit = pair && ((((fi >> 2) & 1) != 0) == same_team) && (g2 <= r2_me) &&
                          (in_cone || cone_free);
+        if (SCRIPT) {
+            // observer i decides its next action: this unit bids if i sees it (nothing to do
+            // in a pass whose observers decide nothing or see nobody)
+            const bool vis = seen && (fi & 0x20);
+            if (__ballot(vis) != 0ull) {
+                const bool i_heals = (fi & 4) != 0;
+                const unsigned d2b = (unsigned)__float_as_int(d2);
+                if (vis && hit && (!i_heals || injured_me)) atomicOr(&script->canhit[oi], 1);
+                if (vis && !same_team)
+                    atomicMin(&script->nkey[oi], ((unsigned long long)d2b << 32) | (unsigned)P.u);
+                if (vis && (i_heals == same_team)) {
+                    // Healer: injured allies first; Assassin: lowest maximum health first
+                    const unsigned order = i_heals ? order_heal : ((fi & 0x10) ? rank_me : 0u);
+                    const unsigned hi = (order << 8) | (d2b >> 24);
+                    const unsigned lo = (d2b << 8) | key_tail | (hit ? 1u : 0u);
+                    atomicMin(&script->tkey[oi], ((unsigned long long)hi << 32) | lo);
+                }
+            }
+        }
         if (a.vis_mask) {
             // the ballot over the lanes is observer i's row; its own lane keeps it
             const uint64_t b = __ballot(seen);
@@ -306,6 +366,33 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 const int words = (N + 63) >> 6;
                 for (int w = 0; w < words; ++w) a.vis_mask[P.k * words + w] = sh.rowbits[P.u][w];
             }
+        }
+    }
+
+    if (SCRIPT) {
+        lds_barrier<WAVES>();      // all bids are in
+        const bool decides = (sh.seer[P.l] & 0x20) != 0;
+        if (decides) {
+            const unsigned long long tk = script->tkey[P.l];
+            const unsigned long long nk = script->nkey[P.l];
+            Sighting S;
+            S.tgt = tk == ~0ull ? -1 : (int)((tk >> 1) & 0x7f);
+            S.tgt_d2 = __int_as_float((int)(unsigned)(tk >> 8));
+            S.tgt_in_box = (tk & 1ull) != 0ull;
+            const int tl = P.base + (S.tgt >= 0 ? S.tgt : 0);
+            S.T = sh.ob.pose[tl];
+            S.tr = script->extra[tl].x;
+            S.any_enemy = nk != ~0ull;
+            S.near_d2 = __int_as_float((int)(unsigned)(nk >> 32));
+            const float4 E = sh.ob.pose[P.base + (S.any_enemy ? (int)(nk & 0x7f) : 0)];
+            S.near_dx = E.x - U.x;
+            S.near_dy = E.y - U.y;
+            S.can_hit = script->canhit[P.l] != 0;
+            const int remembered = C.restarted ? 0 : a.pa.mem.mem_valid[P.k];
+            const float mx = a.pa.mem.mem_x[P.k];
+            const float my = a.pa.mem.mem_y[P.k];
+            policy_cascade(a, P, U, cu, su, in_bush, S, (uint32_t)C.tick, remembered, mx, my, zd,
+                           a.pa.next_action);
         }
     }
 }

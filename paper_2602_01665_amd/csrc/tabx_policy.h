@@ -38,12 +38,103 @@ __device__ __forceinline__ int move_along(float gx, float gy)
     return ax >= ay ? along_x : along_y;
 }
 
+// What a deciding unit has made out of the units it sees.
+struct Sighting {
+    int    tgt;            // selected target (unit index in the env) or -1
+    float  tgt_d2;         // its squared distance
+    bool   tgt_in_box;     // ... and whether the unit's combat action would reach it
+    float4 T;              // its x, y, cos(theta), sin(theta)
+    float  tr;             // its body radius
+    bool   any_enemy;      // nearest visible enemy: exists,
+    float  near_d2, near_dx, near_dy;   // squared distance and offset
+    bool   can_hit;        // something worth a strike is in the hurtbox
+};
+
+// The rule cascade of the policy for one deciding unit (state in U, heading cosine / sine
+// cu, su): first rule that applies, then the epsilon-greedy override.  Updates the unit's
+// remembered target position and writes the action to out[k].
+__device__ __forceinline__ int policy_cascade(const KArgs &a, const Place &P, const Unit &U,
+                                              float cu, float su, bool in_bush, const Sighting &S,
+                                              uint32_t tick, int remembered, float mx, float my,
+                                              const float *zd, uint8_t *out)
+{
+    const PolicyArgs &pa = a.pa;
+    const bool healer = U.dmg < 0.0f;
+    const bool assassin = U.speed >= pa.pol.assassin_speed;
+    const bool ranger = U.range >= pa.pol.ranger_range;
+    int act;
+    const uint32_t coin = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 2u) & 1u;
+    const int search_turn = coin ? TABX_ACT_ROT_LEFT : TABX_ACT_ROT_RIGHT;
+    if (S.tgt >= 0) {
+        const float4 T = S.T;
+        pa.mem.mem_x[P.k] = T.x;
+        pa.mem.mem_y[P.k] = T.y;
+        if (!remembered) pa.mem.mem_valid[P.k] = 1;
+        const float tdx = T.x - U.x;
+        const float tdy = T.y - U.y;
+        const float reach = U.range + S.tr;
+        const bool within = S.tgt_d2 <= reach * reach;
+        const float kite = pa.pol.xi * U.range;
+        // turning towards the side the target is on
+        const float lx = (tdx * cu) + (tdy * su);
+        const float ly = (tdy * cu) - (tdx * su);
+        const int turn = ly > 0.0f ? TABX_ACT_ROT_LEFT
+                                   : (ly < 0.0f ? TABX_ACT_ROT_RIGHT
+                                                : (lx < 0.0f ? TABX_ACT_ROT_LEFT : TABX_ACT_NOOP));
+        // Assassins go behind the target, Healers to it, the rest in front of it
+        const float standoff = 0.5f * U.range;
+        const float ox = T.z * standoff, oy = T.w * standoff;
+        const float gx = healer ? T.x : (assassin ? T.x - ox : T.x + ox);
+        const float gy = healer ? T.y : (assassin ? T.y - oy : T.y + oy);
+        const int approach = move_along(gx - U.x, gy - U.y);
+        const int retreat = move_along(-S.near_dx, -S.near_dy);
+        act = (S.can_hit && U.cd <= 0.0f) ? (int)TABX_ACT_ATTACK
+              : (within && !S.tgt_in_box) ? turn
+              : (ranger && S.any_enemy && S.near_d2 < kite * kite) ? retreat
+              : S.tgt_in_box ? (int)TABX_ACT_NOOP            // aligned, waiting for the cooldown
+                             : approach;
+    } else if (remembered) {
+        const float gx = mx - U.x;
+        const float gy = my - U.y;
+        const bool arrived = (gx * gx) + (gy * gy) <= 1.0f;
+        if (arrived) pa.mem.mem_valid[P.k] = 0;
+        act = arrived ? search_turn : move_along(gx, gy);
+    } else {
+        // Rangers outside a bush walk to the nearest bush zone they know of, then search
+        // (`zd`: the env's zone descriptors in LDS)
+        bool found = false;
+        float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
+        if (ranger && !in_bush) {
+            for (int z = 0; z < a.p.max_zones; ++z) {
+                const float *d = zd + 6 * z;
+                const float zx = d[1] - U.x;
+                const float zy = d[2] - U.y;
+                const float d2 = (zx * zx) + (zy * zy);
+                const bool take = ((int)d[0] == TABX_ZONE_BUSH) && (!found || d2 < bush_d2);
+                found = found || take;
+                bush_d2 = take ? d2 : bush_d2;
+                bx = take ? zx : bx;
+                by = take ? zy : by;
+            }
+        }
+        act = found ? move_along(bx, by) : search_turn;
+    }
+    // epsilon-greedy override
+    const uint32_t h0 = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 0u);
+    const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
+    if (u0 < pa.pol.epsilon)
+        act = (int)(policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 1u) & 7u);
+    out[P.k] = (uint8_t)act;
+    return act;
+}
+
 // Decides for the lane's unit from the state in U (heading cosine / sine cu, su, zone code
 // code_u under it); returns the action, or -1 if the unit is not the policy's to move.  Writes
 // the action and the remembered target position.  All lanes of the workgroup call it.
 template <int WAVES>
 __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, const Place &P,
-                                          const Unit &U, int code_u, float cu, float su)
+                                          const Unit &U, int code_u, float cu, float su,
+                                          const float *zd)
 {
     const PolicyArgs &pa = a.pa;
     const int N = a.p.num_units;
@@ -63,7 +154,6 @@ __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, con
 
     const bool healer = U.dmg < 0.0f;
     const bool assassin = U.speed >= pa.pol.assassin_speed;
-    const bool ranger = U.range >= pa.pol.ranger_range;
     const float sight2 = U.sight_range * U.sight_range;
     const float neg_hw = -U.hurt_hw;
 
@@ -110,71 +200,19 @@ __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, con
 
     int act = -1;
     if (decide) {
-        const uint32_t coin = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 2u) & 1u;
-        const int search_turn = coin ? TABX_ACT_ROT_LEFT : TABX_ACT_ROT_RIGHT;
-        if (tgt >= 0) {
-            const float4 T = sh.po.pose[P.base + tgt];
-            const float tr = sh.po.body[P.base + tgt].x;
-            pa.mem.mem_x[P.k] = T.x;
-            pa.mem.mem_y[P.k] = T.y;
-            if (!remembered) pa.mem.mem_valid[P.k] = 1;
-            const float tdx = T.x - U.x;
-            const float tdy = T.y - U.y;
-            const float reach = U.range + tr;
-            const bool within = tgt_d2 <= reach * reach;
-            const float kite = pa.pol.xi * U.range;
-            // turning towards the side the target is on
-            const float lx = (tdx * cu) + (tdy * su);
-            const float ly = (tdy * cu) - (tdx * su);
-            const int turn = ly > 0.0f ? TABX_ACT_ROT_LEFT
-                                       : (ly < 0.0f ? TABX_ACT_ROT_RIGHT
-                                                    : (lx < 0.0f ? TABX_ACT_ROT_LEFT : TABX_ACT_NOOP));
-            // Assassins go behind the target, Healers to it, the rest in front of it
-            const float standoff = 0.5f * U.range;
-            const float ox = T.z * standoff, oy = T.w * standoff;
-            const float gx = healer ? T.x : (assassin ? T.x - ox : T.x + ox);
-            const float gy = healer ? T.y : (assassin ? T.y - oy : T.y + oy);
-            const int approach = move_along(gx - U.x, gy - U.y);
-            const int retreat = move_along(-near_dx, -near_dy);
-            act = (can_hit && U.cd <= 0.0f) ? (int)TABX_ACT_ATTACK
-                  : (within && !tgt_in_box) ? turn
-                  : (ranger && any_enemy && near_d2 < kite * kite) ? retreat
-                  : tgt_in_box ? (int)TABX_ACT_NOOP            // aligned, waiting for the cooldown
-                               : approach;
-        } else if (remembered) {
-            const float gx = mx - U.x;
-            const float gy = my - U.y;
-            const bool arrived = (gx * gx) + (gy * gy) <= 1.0f;
-            if (arrived) pa.mem.mem_valid[P.k] = 0;
-            act = arrived ? search_turn : move_along(gx, gy);
-        } else {
-            // Rangers outside a bush walk to the nearest bush zone they know of, then search
-            int bush = -1;
-            float bush_d2 = 0.0f, bx = 0.0f, by = 0.0f;
-            if (ranger && !in_bush && a.sc.zone_desc) {
-                const float *zd = a.sc.zone_desc + (size_t)P.row * 6 * a.p.max_zones;
-                for (int z = 0; z < a.p.max_zones; ++z) {
-                    const float *d = zd + 6 * z;
-                    if ((int)d[0] != TABX_ZONE_BUSH) continue;
-                    const float zx = d[1] - U.x;
-                    const float zy = d[2] - U.y;
-                    const float d2 = (zx * zx) + (zy * zy);
-                    if (bush < 0 || d2 < bush_d2) {
-                        bush = z;
-                        bush_d2 = d2;
-                        bx = zx;
-                        by = zy;
-                    }
-                }
-            }
-            act = bush >= 0 ? move_along(bx, by) : search_turn;
-        }
-        // epsilon-greedy override
-        const uint32_t h0 = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 0u);
-        const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
-        if (u0 < pa.pol.epsilon)
-            act = (int)(policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 1u) & 7u);
-        pa.actions_out[P.k] = (uint8_t)act;
+        Sighting S;
+        S.tgt = tgt;
+        S.tgt_d2 = tgt_d2;
+        S.tgt_in_box = tgt_in_box;
+        S.T = sh.po.pose[P.base + (tgt >= 0 ? tgt : 0)];
+        S.tr = sh.po.body[P.base + (tgt >= 0 ? tgt : 0)].x;
+        S.any_enemy = any_enemy;
+        S.near_d2 = near_d2;
+        S.near_dx = near_dx;
+        S.near_dy = near_dy;
+        S.can_hit = can_hit;
+        act = policy_cascade(a, P, U, cu, su, in_bush, S, tick, remembered, mx, my, zd,
+                             pa.actions_out);
     }
     lds_barrier<WAVES>();          // the records may be overwritten by the next stage
     return act;

@@ -295,12 +295,12 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
                 P.ks = (size_t)row * N + P.u;
                 load_spec(a, P.ks, U);
                 en_next = U.enabled != 0;
-                if (a.p.zone_shapes == 1) {
+                if (a.zdesc_staged) {
                     const int zlen = 6 * a.p.max_zones;
                     for (int q = P.u; q < zlen; q += N) zd[q] = a.sc.zone_desc[(size_t)row * zlen + q];
                 }
             }
-            if (a.p.zone_shapes == 1) lds_barrier<WAVES>();
+            if (a.zdesc_staged) lds_barrier<WAVES>();
         }
         if (done) {
             if (a.pa.mem.mem_valid) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
@@ -352,6 +352,8 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     C.cu = cu;
     C.su = su;
     C.ratio = ratio;
+    C.tick = done ? 0 : t_new;
+    C.restarted = done;
     return any_done;
 }
 

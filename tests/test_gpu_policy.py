@@ -237,3 +237,102 @@ def test_full_size_scripted_tick_with_level_bank():
     _say(f"[gpu]   sampled episodes ended {dones}")
     assert dones > len(rows)
     assert torch.isfinite(gpu.obs).all()
+
+
+def _scripted_rollout(w, E, steps, tier, who, scenario=None, seed=5, **override):
+    """tabx_scripted_step_observe (decisions taken inside the observe stage, applied by the next
+    call) against the checker's decide-then-step sequence: actions, states, observations,
+    memories and the waiting decisions must all agree, tick by tick."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    p = I.make_params(w, E, **override)
+    L = p.get("num_levels", 0)
+    sc = I.make_scenario(w, L if L else E) if scenario is None else scenario
+    N = p["num_units"]
+    ref = RefEnv(p, sc)
+    gpu = TabxEnv(p, sc, want_metrics=True)
+    ref.reset()
+    gpu.reset()
+    team = np.asarray(sc["team"]).reshape(-1, N)
+    team = team[ref.st["level"]] if L else team
+    ctl = {"adversaries": team == 1, "both": np.ones_like(team, bool)}[who].astype(np.uint8)
+    ctl_d = None if who == "both" else torch.from_numpy(ctl).to(gpu.device)
+    pol = I.policy(tier, seed)
+    gpu.prime_scripted(pol, ctl_d)
+    hist = np.zeros(8, np.int64)
+    dones = 0
+    for s in range(steps):
+        where = f"{w.name} E={E} scripted {tier}/{who} step {s}: "
+        a = I.actions_for_step(w.seed, s, E, N)
+        ad = torch.from_numpy(a).to(gpu.device)
+        ref.heuristic_actions(pol, ctl, a)               # decides on the current state
+        torch.cuda.synchronize()
+        _check_memory(gpu, ref, E, N, where + "before the step: ")
+        deciding = (ctl == 1) & (ref.st["alive"] == 1)
+        waiting = gpu.mem["next_action"].cpu().numpy().reshape(E, N)
+        assert np.array_equal(waiting[deciding], a[deciding]), where + "waiting decisions"
+        ref.step(a)
+        ref.mem["mem_valid"][ref.dones.astype(bool)] = 0
+        ref.observe()
+        gpu.scripted_step_observe(pol, ctl_d, ad)
+        torch.cuda.synchronize()
+        got = ad.cpu().numpy()
+        assert np.array_equal(got, a), where + f"actions differ at {np.argwhere(got != a)[:4].tolist()}"
+        compare_state(gpu.state_numpy(), ref.st, where)
+        compare_outputs(gpu, ref, where, check_obs=True)
+        hist += np.bincount(a[ctl == 1], minlength=8)
+        dones += int(ref.dones.sum())
+    return hist, dones
+
+
+@pytest.mark.parametrize("tier", TIERS)
+def test_scripted_tick_every_tier(tier):
+    _say(f"[gpu] scripted tick c3 subset, adversaries, tier {tier}")
+    hist, dones = _scripted_rollout(I.WORKLOADS["c3_16384env_10v10"], 48, 120, tier,
+                                    "adversaries", max_steps=96)
+    _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
+    assert hist.sum() > 0
+
+
+@pytest.mark.parametrize("name,E,steps,over", [
+    ("c1_16env_3v3", 16, 256, dict()),
+    ("c2_4096env_5v5", 200, 200, dict(max_steps=128)),
+    ("c3_16384env_10v10", 70, 200, dict(max_steps=128)),
+    ("c3e_16384env_10v10_ellipses", 70, 200, dict(max_steps=128)),
+    ("c5_1024env_64v64", 3, 80, dict(max_steps=60)),
+    ("c3_16384env_10v10", 40, 150, dict(max_steps=24, hurtbox_cone=1, hit_all=1)),
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_scripted_tick_self_play(name, E, steps, over):
+    _say(f"[gpu] scripted tick self-play {name} E={E} steps={steps} {over}")
+    hist, dones = _scripted_rollout(I.WORKLOADS[name], E, steps, "expert", "both", **over)
+    _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
+    assert hist[5] > 0 and hist[1:5].sum() > 0 and hist[6:].sum() > 0
+    assert dones > 0
+
+
+def test_scripted_tick_roster_and_ragged():
+    names = list(I.ROSTER)
+    E, N = 40, 2 * len(names)
+    w = I.Workload("roster_scripted", E, len(names), 48.0, 24, "iid", 0.5, "iid", steps=150,
+                   seed=778)
+    sc = I.make_scenario(w, E)
+    for u in range(N):
+        row = I.ROSTER[names[u % len(names)]]
+        for k, v in zip(("hmax", "radius", "mass", "speed", "dmg", "range", "cooldown"), row):
+            sc[k][:, u] = np.float32(v)
+        sc["hurt_halfwidth"][:, u] = np.float32(row[1])
+    _say("[gpu] scripted tick roster mix")
+    hist, dones = _scripted_rollout(w, E, 150, "medium", "both", scenario=sc, max_steps=120)
+    assert hist[5] > 0
+    for team_size, disabled in [(1, 0), (7, 2), (33, 4), (50, 9)]:
+        w = I.Workload(f"ragged_scripted_{team_size}", 5, team_size, 40.0, 20, "iid", 0.6, "iid",
+                       steps=60, seed=6262 + team_size)
+        sc = I.make_scenario(w, 5)
+        rng = np.random.default_rng(team_size)
+        for e in range(5):
+            off = rng.choice(w.num_units, size=min(disabled, w.num_units - 2), replace=False)
+            off = [u for u in off if u not in (0, w.num_units - 1)]
+            sc["enabled"][e, off] = 0
+        _say(f"[gpu] scripted tick ragged N={w.num_units} disabled={disabled}")
+        _scripted_rollout(w, 5, 60, "advanced", "adversaries", scenario=sc, max_steps=40)
