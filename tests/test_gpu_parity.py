@@ -412,3 +412,41 @@ def test_full_size_sampled_envs(name, steps, n_sample):
     team = gpu.sc["team"].reshape(E, N).bool()
     assert torch.equal(r[:, :1].expand(E, N)[~team], r[~team])
     assert torch.equal((-r[:, :1]).expand(E, N)[team], r[team])
+
+
+def test_calls_can_be_captured_into_a_graph():
+    """The entry points allocate nothing and only enqueue kernels, so a stream capture records
+    them; replays (with eager work and synchronisations in between) give what eager calls give."""
+    import torch
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = I.WORKLOADS["c2_4096env_5v5"]
+    E, N, K = 512, w.num_units, 6
+    p, sc = I.make_params(w, E, max_steps=10), I.make_scenario(w, E)
+    acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, N)).to("cuda:0") for s in range(K)]
+    eager = TabxEnv(p, sc, want_metrics=True)
+    graphed = TabxEnv(p, sc, want_metrics=True)
+    eager.reset()
+    graphed.reset()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for s in range(K):
+                graphed.step_observe(acts[s], stream=side)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        _say(f"[gpu] graph replay {replay}")
+        g.replay()
+        for s in range(K):
+            eager.step_observe(acts[s])
+        torch.cuda.synchronize()
+        for k in eager.st:
+            assert torch.equal(eager.st[k], graphed.st[k]), (replay, k)
+        assert torch.equal(eager.obs, graphed.obs) and torch.equal(eager.rewards, graphed.rewards)
+        assert torch.equal(eager.vis, graphed.vis) and torch.equal(eager.dones, graphed.dones)
+        for k in eager.metrics:
+            assert torch.equal(eager.metrics[k], graphed.metrics[k]), (replay, k)
+        # unrelated eager work between the replays
+        _ = (eager.obs * 2).sum().item()
+    assert int(eager.metrics["ep_count"].sum()) > 0
