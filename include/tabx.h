@@ -21,7 +21,8 @@
  *    16-byte aligned.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls validate their arguments on the host, enqueue kernels and return
- *    without synchronising.
+ *    without synchronising; they allocate nothing and enqueue no memsets or
+ *    copies, so a stream capture can record them into a graph.
  *  - Every entry point returns TABX_OK (0) or a negative TabxError; on error
  *    nothing has been enqueued.  num_envs == 0 is a valid no-op.
  *  - An action id >= TABX_NUM_ACTIONS acts as TABX_ACT_NOOP.
