@@ -52,7 +52,6 @@ struct KArgs {
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte store, 4-byte aligned
 
 constexpr float kTwoPi = 6.28318530717958647692f;
-constexpr float kInf = __builtin_huge_valf();
 // Sine and cosine of a heading in [0, 2*pi]: quadrant index n = trunc(theta *
 // 2/pi + 1/2), remainder through a two-term split of pi/2, degree-9 / degree-8
 // Taylor polynomials in Horner form with explicit fused multiply-adds.

@@ -16,6 +16,11 @@
 // 16 bytes per lane and 1 KB per store instruction.  Own blocks and zone slots
 // join the same stream.
 //
+// Files: tabx_device.h (launch arguments, registers, LDS exchange area, helpers),
+// tabx_policy.h (heuristic policy: scan stage and rule cascade), tabx_step.h
+// (step stage), tabx_observe.h (observe stage, where scripted units also decide),
+// this file (kernels, argument checks, launches, the C entry points).
+//
 // The rules follow the paper's App. A ("Interaction Dynamics", "Reward",
 // "Observation and Global State", "Zones").  All arithmetic is float32 with one
 // rounding per written operation: the file is compiled with -ffp-contract=off
