@@ -85,3 +85,41 @@ def test_null_and_alignment_errors_come_back_before_any_launch(B):
     # an empty batch is a no-op that needs no buffers
     p0 = _params(B, num_envs=0)
     assert lib.tabx_step(C.byref(p0), None, None, None, None, None, None) == 0
+
+
+def test_policy_level_and_variant_arguments_are_validated(B):
+    lib = B._lib
+    for bad in (dict(num_levels=-1), dict(hit_all=2), dict(hurtbox_cone=-1)):
+        assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -2, bad
+    p = _params(B, max_zones=0)
+    sc, st = B.TabxScenario(), B.TabxState()
+    fake = 0x1000
+    for k, typ in B.TabxScenario._fields_:
+        if k not in ("terrain", "zone_desc"):
+            setattr(sc, k, C.cast(C.c_void_p(fake), typ))
+    for k, typ in B.TabxState._fields_:
+        setattr(st, k, C.cast(C.c_void_p(fake), typ))
+    pol = B.TabxPolicy(epsilon=0.1, xi=0.3, assassin_speed=1.4, ranger_range=10.0, seed=1)
+    mem = B.TabxPolicyMemory()
+    acts = C.c_void_p(fake)
+    heur = lib.tabx_heuristic_actions
+    # no policy, no memory struct, empty memory struct, no output
+    assert heur(C.byref(p), C.byref(sc), C.byref(st), None, C.byref(mem), None, acts, None) == -1
+    assert heur(C.byref(p), C.byref(sc), C.byref(st), C.byref(pol), None, None, acts, None) == -1
+    assert heur(C.byref(p), C.byref(sc), C.byref(st), C.byref(pol), C.byref(mem), None, acts, None) == -1
+    for k, typ in B.TabxPolicyMemory._fields_:
+        if k != "next_action":
+            setattr(mem, k, C.cast(C.c_void_p(fake), typ))
+    assert heur(C.byref(p), C.byref(sc), C.byref(st), C.byref(pol), C.byref(mem), None, None, None) == -1
+    bad_pol = B.TabxPolicy(epsilon=float("nan"), xi=0.3, assassin_speed=1.4, ranger_range=10.0, seed=1)
+    assert heur(C.byref(p), C.byref(sc), C.byref(st), C.byref(bad_pol), C.byref(mem), None, acts, None) == -5
+    # the scripted tick needs the buffer its decisions wait in
+    assert lib.tabx_scripted_step_observe(C.byref(p), C.byref(sc), C.byref(st), C.byref(pol),
+                                          C.byref(mem), None, acts, acts, acts, acts, None, None,
+                                          None) == -1
+    # a level bank needs its three per-env arrays
+    pl = _params(B, max_zones=0, num_levels=3)
+    st.next_level = C.cast(None, B._I32)
+    assert lib.tabx_reset(C.byref(pl), C.byref(sc), C.byref(st), None, None) == -1
+    st.next_level = C.cast(C.c_void_p(fake + 1), B._I32)
+    assert lib.tabx_reset(C.byref(pl), C.byref(sc), C.byref(st), None, None) == -3
