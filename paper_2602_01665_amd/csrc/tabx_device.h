@@ -42,6 +42,9 @@ struct KArgs {
     int       zdesc_staged;        // ... which exists for elliptical zones and for deciding units
     int       script_offset;       // scripted units deciding in the observe stage: their LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
+    int       twin;                // 2: two wavefronts per workgroup own the same env group and
+                                   //    share its observers (chunk = wavefront index)
+    int       dyn_stride;          // twin: floats of dynamic LDS per wavefront
     int       obs_chunks;          // workgroups that share the observers of one env group (>= 1)
     int       obs_per_chunk;       // observers per such workgroup (a multiple of rows_per_flush)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)
@@ -149,6 +152,13 @@ struct Shared {
     uint64_t rowbits[WAVES == 1 ? 1 : L][WAVES];   // two-wave workgroups: ballots of "observer i sees lane"
     uint64_t ballots[WAVES][4];
     int      rows[WAVES == 1 ? 64 : 1];   // level bank: the row an env slot has just switched to, or -1
+};
+
+// Twin wavefronts: both load the same units and run the step stage redundantly in their own
+// LDS areas; wavefront 0 alone writes the state, each writes the rows of its half of the
+// observers.  What they do share sits here.
+struct TwinShared {
+    int rows[64];      // level bank: the row an env slot has just switched to, or -1
 };
 
 // Orders LDS traffic between the lanes of a workgroup without waiting for global
@@ -280,7 +290,7 @@ __device__ __forceinline__ Place locate(const KArgs &a)
 {
     Place P;
     const int N = a.p.num_units;
-    P.l = threadIdx.x;
+    P.l = a.twin ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
     if (WAVES == 1) {
         P.g = P.l / N;
         P.u = P.l - P.g * N;
@@ -293,7 +303,7 @@ __device__ __forceinline__ Place locate(const KArgs &a)
     // of their SoA segments, meet in the same L2.
     const int slot = (int)(blockIdx.x >> 3);
     const int in_xcd = a.obs_chunks > 1 ? slot / a.obs_chunks : slot;
-    P.chunk = slot - in_xcd * a.obs_chunks;
+    P.chunk = a.twin ? (int)(threadIdx.x >> 6) : slot - in_xcd * a.obs_chunks;
     P.grp = in_xcd < a.groups_per_xcd ? (int)(blockIdx.x & 7) * a.groups_per_xcd + in_xcd : a.num_groups;
     P.e = P.grp * a.envs_per_block + P.g;
     P.has = P.grp < a.num_groups && P.g < a.envs_per_block && P.u < N && P.e < a.p.num_envs;

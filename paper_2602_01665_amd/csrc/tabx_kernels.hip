@@ -40,11 +40,17 @@
 
 namespace tabx {
 
-template <int WAVES, bool DO_POLICY, bool DO_STEP, bool DO_OBS, bool SCRIPT = false>
-__global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
+template <int WAVES, bool DO_POLICY, bool DO_STEP, bool DO_OBS, bool SCRIPT = false,
+          int TWIN = 0>
+__global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kernel(const KArgs a)
 {
-    __shared__ Shared<WAVES> sh;
-    extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
+    __shared__ Shared<WAVES> sh_all[TWIN ? TWIN : 1];
+    __shared__ TwinShared twin;
+    extern __shared__ __attribute__((aligned(16))) float dyn_all[];
+    const int half = TWIN ? (int)(threadIdx.x >> 6) : 0;
+    Shared<WAVES> &sh = sh_all[half];
+    float *dyn_lds = dyn_all + half * a.dyn_stride;
+    int *rows = TWIN ? twin.rows : sh.rows;     // TWIN: 0, or the 2 of twin wavefronts
     Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
@@ -78,7 +84,7 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
                              (!a.pa.controlled || a.pa.controlled[P.k]);
         if (decides) {
             forced = a.pa.next_action[P.k];
-            a.pa.actions_out[P.k] = (uint8_t)forced;
+            if (P.chunk == 0) a.pa.actions_out[P.k] = (uint8_t)forced;
         }
     }
     if (DO_POLICY) {
@@ -90,11 +96,11 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_tick_kernel(const KArgs a)
         forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su, zd);
     }
     bool restarted = false;
-    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, P, U, code_u, C, forced);
+    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, rows, P, U, code_u, C, forced);
     else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
     if (DO_STEP && DO_OBS && a.p.num_levels > 0 && restarted) {
         // zone slots of the envs that changed level
-        const int row = Zr.lane ? sh.rows[Zr.zg] : -1;
+        const int row = Zr.lane ? rows[Zr.zg] : -1;
         if (row >= 0) Zr = load_zone_regs<WAVES>(a, P, row);
     }
     if (SCRIPT && !DO_STEP && P.has) C.tick = a.st.t[P.e];
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
     const int N = a.p.num_units;
     const bool go = P.has && !(a.env_mask && a.env_mask[P.e] == 0);
     if (a.p.num_levels > 0) {
-        const int row = advance_level<WAVES>(a, sh, P, go);
+        const int row = advance_level<WAVES>(a, sh, P, go, sh.rows);
         if (row >= 0) {
             P.row = row;
             P.ks = (size_t)row * N + P.u;
@@ -264,7 +270,8 @@ static int check_state(const TabxParams *p, const TabxState *s)
 template <int WAVES>
 static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
 {
-    const dim3 grid((unsigned)(8 * a.groups_per_xcd * a.obs_chunks)), block(64 * WAVES);
+    const dim3 grid((unsigned)(8 * a.groups_per_xcd * a.obs_chunks));
+    const dim3 block(64 * WAVES * (a.twin ? a.twin : 1));
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
     // buffers for a two-wave workgroup)
     const size_t rows_staged = WAVES == 1 ? (size_t)a.envs_per_block * a.rows_per_flush : 2;
@@ -279,7 +286,9 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     // ... and by the bidding area of scripted units that decide in the observe stage
     const size_t zdesc_even = (zdesc_floats + 1) & ~(size_t)1;
     const size_t script_floats = mode == MODE_SCRIPTED_STEP_OBSERVE ? sizeof(ScriptLds<WAVES>) / 4 : 0;
-    const size_t dyn_bytes = (dyn_floats + zdesc_even + script_floats) * sizeof(float);
+    // (twin wavefronts: one such area each)
+    a.dyn_stride = (int)((dyn_floats + zdesc_even + script_floats + 3) & ~(size_t)3);
+    const size_t dyn_bytes = (size_t)a.dyn_stride * (a.twin ? a.twin : 1) * sizeof(float);
     const size_t step_bytes = zdesc_floats * sizeof(float);
     a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0 : (int)dyn_floats;
     a.script_offset = a.zdesc_offset + (int)zdesc_even;
@@ -296,8 +305,12 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
                            stream, a);
         break;
     case MODE_STEP_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true>), grid, block, dyn_bytes,
-                           stream, a);
+        if (WAVES == 1 && a.twin)
+            hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, false, 2>), grid, block,
+                               dyn_bytes, stream, a);
+        else
+            hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true>), grid, block, dyn_bytes,
+                               stream, a);
         break;
     case MODE_POLICY:
         hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false, false>), grid, block, step_bytes,
@@ -308,8 +321,12 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
                            stream, a);
         break;
     case MODE_SCRIPTED_STEP_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true, true>), grid, block,
-                           dyn_bytes, stream, a);
+        if (WAVES == 1 && a.twin)
+            hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, true, 2>), grid, block,
+                               dyn_bytes, stream, a);
+        else
+            hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true, true>), grid, block,
+                               dyn_bytes, stream, a);
         break;
     }
 }
@@ -408,13 +425,34 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     // loads the group's units and writes half of its rows): shorter-lived wavefronts, twice as
     // many of them; measured -3 ... -9 % on the packed-env kernels, +5 % with two-wave envs.
     // A launch that steps cannot: the second workgroup would need the state after the step.
+    // Long-lived wavefronts make a long tail at the end of the launch, and a wavefront's chain
+    // of flushes is the latency floor of a small batch.  Where that matters the observers of an
+    // env group are split between two wavefronts:
+    //  - a stand-alone observe uses two workgroups per group (each loads the group's units and
+    //    writes half of its rows): measured -3 ... -9 % on the packed-env kernels;
+    //  - a launch that also steps cannot (the second workgroup would need the state after the
+    //    first one's step), but twin wavefronts of ONE workgroup can: both load the units, both
+    //    run the step stage, a workgroup barrier keeps the first one's state stores behind the
+    //    second one's loads.  Measured: c3 107 -> 99.5 us, c2 15.8 -> 14.0 us, but c4 (10 observers,
+    //    five flushes per wavefront, a full machine) 87 -> 102 us, c3 with elliptical zones (a
+    //    costlier step to repeat) 110 -> 112.5 us and the scripted c3 tick +3 us, hence the
+    //    conditions below.  Three or four wavefronts per group: 120 us and more on c3.
     a.obs_chunks = 1;
     a.obs_per_chunk = N;
-    if (mode == MODE_OBSERVE && waves == 1 && N >= 4) {
+    a.twin = 0;
+    if (waves == 1 && N >= 4) {
         const int per = ((N + 1) / 2 + R - 1) / R * R;
-        if (per < N) {
+        const int num_groups = (p->num_envs + G - 1) / G;
+        const bool small_batch = num_groups <= 2048;             // under one residency round
+        // eight or more flushes, and a step stage that is cheap to run twice
+        const bool long_chain = N >= 16 * R / 2 && p->zone_shapes == 0;
+        if (per < N && mode == MODE_OBSERVE) {
             a.obs_per_chunk = per;
             a.obs_chunks = (N + per - 1) / per;
+        } else if (per < N && ((mode == MODE_STEP_OBSERVE && (small_batch || long_chain)) ||
+                               (mode == MODE_SCRIPTED_STEP_OBSERVE && small_batch))) {
+            a.obs_per_chunk = per;
+            a.twin = 2;
         }
     }
     a.copy_passes = (G * R * cpr + 64 * waves - 1) / (64 * waves);

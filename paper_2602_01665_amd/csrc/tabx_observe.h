@@ -371,7 +371,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
 
     if (SCRIPT) {
         lds_barrier<WAVES>();      // all bids are in
-        const bool decides = (sh.seer[P.l] & 0x20) != 0;
+        // (twin wavefronts: the one that ran the unit's pass as observer holds its bids)
+        const bool decides = (sh.seer[P.l] & 0x20) != 0 && P.u >= i_begin && P.u < i_end;
         if (decides) {
             const unsigned long long tk = script->tkey[P.l];
             const unsigned long long nk = script->nkey[P.l];

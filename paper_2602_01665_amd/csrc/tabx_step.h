@@ -11,12 +11,13 @@ namespace tabx {
 // Level bank: an episode of the lane's env is about to start (`take`, uniform over the env's
 // lanes).  Unit 0 takes the queued level (folded into [0, num_levels)), refills the queue with
 // a uniform draw, the hash of (level_seed, env, draws so far), and tells the env's other lanes
-// through LDS.  Returns the env's new row, or -1 if it keeps its level.  All lanes call it.
+// through LDS (`rows`: one slot per env of the workgroup).  Returns the env's new row, or -1
+// if it keeps its level.  All lanes call it.
 template <int WAVES>
 __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, const Place &P,
-                                             bool take)
+                                             bool take, int *rows)
 {
-    if (P.has && P.u == 0) {
+    if (P.has && P.u == 0 && P.chunk == 0) {
         int row = -1;
         if (take) {
             const uint32_t L = (uint32_t)a.p.num_levels;
@@ -26,10 +27,11 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
             a.st.next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)P.e, 0u, n, 3u) % L);
             a.st.level_draws[P.e] = (int)(n + 1u);
         }
-        sh.rows[P.g] = row;
+        rows[P.g] = row;
     }
-    lds_barrier<WAVES>();
-    return P.has ? sh.rows[P.g] : -1;
+    if (a.twin) lds_barrier<2>();          // `rows` is shared by the two wavefronts
+    else lds_barrier<WAVES>();
+    return P.has ? rows[P.g] : -1;
 }
 
 // `forced` >= 0 replaces the unit's entry of the action array (the policy stage chose it).
@@ -37,7 +39,8 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
 // level.  Returns whether any env of the workgroup restarted.
 template <int WAVES>
 __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, float *zd,
-                                         Place &P, Unit &U, int &code_u, Carry &C, int forced)
+                                         int *rows, Place &P, Unit &U, int &code_u, Carry &C,
+                                         int forced)
 {
     float zeff = 0.0f;             // effect magnitude of the zone under the unit (elliptical zones)
     const int N = a.p.num_units;
@@ -49,6 +52,10 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     const int t_new = has ? a.st.t[P.e] + 1 : 0;
     const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
     float bdmg = 0.0f;
+    // twin wavefronts compute the same step; only the first one writes it back, and not before
+    // both have everything they read from global memory
+    const bool writer = P.chunk == 0;
+    if (a.twin) __syncthreads();
 
     // stage 1: cooldown / reveal timers, explicit Euler move, arena penalty + clip
     if (has && U.enabled) {
@@ -280,7 +287,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         r0 = r0 + (ally_win ? 1.0f : -1.0f);
         r1 = r1 + (ally_win ? -1.0f : 1.0f);
     }
-    if (has) a.rewards[P.k] = U.enabled ? (U.team ? r1 : r0) : 0.0f;
+    if (has && writer) a.rewards[P.k] = U.enabled ? (U.team ? r1 : r0) : 0.0f;
 
     // auto-reset of finished envs; the potential of the fresh state seeds phi_prev
     float phi_next = phi;
@@ -289,7 +296,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         bool en_next = en;
         if (a.p.num_levels > 0) {
             // the finished envs move to their queued level: new specifications, new zones
-            const int row = advance_level<WAVES>(a, sh, P, done);
+            const int row = advance_level<WAVES>(a, sh, P, done, rows);
             if (row >= 0) {
                 P.row = row;
                 P.ks = (size_t)row * N + P.u;
@@ -303,7 +310,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             if (a.zdesc_staged) lds_barrier<WAVES>();
         }
         if (done) {
-            if (a.pa.mem.mem_valid) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
+            if (a.pa.mem.mem_valid && writer) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
             code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
@@ -324,7 +331,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         team_means(sh, P, N, c0, c1, f0, f1);
         if (done) phi_next = f0 - f1;
     }
-    if (has && P.u == 0) {
+    if (has && P.u == 0 && writer) {
         a.st.t[P.e] = done ? 0 : t_new;
         a.st.phi_prev[P.e] = phi_next;
         a.dones[P.e] = done ? 1 : 0;
@@ -348,7 +355,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             if (a.st.ep_first_kill && want_kills) a.st.ep_first_kill[P.e] = (int8_t)kills;
         }
     }
-    if (has) store_state(a, P.k, U);
+    if (has && writer) store_state(a, P.k, U);
     C.cu = cu;
     C.su = su;
     C.ratio = ratio;
