@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/tabx_tick_c3_16384env_10v10.md: WRITE_SIZE 487659.0 KiB x 1.0 + FETCH_SIZE 30657.6 KiB x 2.0
-    "c3_16384env_10v10": int((487659.0 + 2.0 * 30657.6) * 1024),
+    # profiles/tabx_tick_c3_16384env_10v10.md: WRITE_SIZE 487590.7 KiB x 1.0 + FETCH_SIZE 30610.1 KiB x 2.0
+    "c3_16384env_10v10": int((487590.7 + 2.0 * 30610.1) * 1024),
 }
 
 
