@@ -97,6 +97,9 @@ def main() -> int:
                          "the tick launch (tabx_scripted_step_observe: they decide in the observe "
                          "stage); with --separate as tabx_heuristic_actions + tabx_step_observe, "
                          "with --policy-scan as tabx_policy_step_observe; not the headline tick")
+    ap.add_argument("--global-state", action="store_true",
+                    help="also have every tick write the global state (TabxState.global_state), "
+                         "as a centralised critic would want it; not the headline tick")
     ap.add_argument("--policy-scan", action="store_true",
                     help="with --policy: the policy as a stage of its own in front of the step")
     args = ap.parse_args()
@@ -121,7 +124,7 @@ def main() -> int:
     E, N = w.num_envs, w.num_units
     p = I.make_params(w, **(dict(collision_alpha=0.8) if args.collisions else {}))
     scenario = I.make_scenario(w)
-    env = TabxEnv(p, scenario)
+    env = TabxEnv(p, scenario, want_global_state=args.global_state)
     env.reset()
     n_act = min(args.steps + args.warmup, 64)
     acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, N)).to("cuda:0")
@@ -186,6 +189,7 @@ def main() -> int:
                    "launch": "separate step+observe" if args.separate else "fused step_observe",
                    "body_collisions": bool(args.collisions),
                    "scripted_adversaries": args.policy,
+                   "global_state_every_tick": bool(args.global_state),
                    "actions": f"{n_act} pre-generated seeded uniform action batches, cycled"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -154,6 +154,11 @@ typedef struct TabxState {
     int32_t *level;          /* the level the env is playing                            */
     int32_t *next_level;     /* the level its next episode will take                    */
     int32_t *level_draws;    /* how many uniform draws the env has made                 */
+    /* Optional output, [E][16 * N + 6 * max_zones] f32, 4-byte aligned: if not NULL, every call
+     * that produces observations (tabx_observe, tabx_step_observe and the policy / scripted
+     * ticks) also writes the global state of tabx_global_state here, for centralised critics
+     * that want it every tick; it costs its bytes and no second launch. */
+    float   *global_state;
 } TabxState;
 
 /* Floats per agent observation: 16 * N + 6 * max_zones.

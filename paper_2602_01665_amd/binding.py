@@ -58,7 +58,7 @@ class TabxState(C.Structure):
     _fields_ = [(n, _F) for n in STATE_FLOAT] + \
                [("alive", _U8), ("t", C.POINTER(C.c_int32)), ("phi_prev", _F)] + \
                [(n, t) for n, t, _ in METRICS] + \
-               [(n, _I32) for n in LEVELS]
+               [(n, _I32) for n in LEVELS] + [("global_state", _F)]
 
 
 class TabxError(RuntimeError):
@@ -197,7 +197,7 @@ class TabxEnv:
     """Device buffers of one batch of environments plus the calls on them."""
 
     def __init__(self, params: dict, scenario: dict, device="cuda:0", want_vis=True,
-                 want_action_mask=True, want_metrics=False):
+                 want_action_mask=True, want_metrics=False, want_global_state=False):
         self.device = torch.device(device)
         self.p = dict(params)
         self.params = make_params(self.p)
@@ -236,7 +236,10 @@ class TabxEnv:
             self.st["level"] = torch.zeros(E, dtype=torch.int32, device=dev)
             self.st["next_level"] = (torch.arange(E, device=dev) % L).to(torch.int32)
             self.st["level_draws"] = torch.zeros(E, dtype=torch.int32, device=dev)
-        self.state = self._state_struct(self.st, self.metrics)
+        # global state written by every observing call (else only by global_state())
+        self.gs_live = (torch.zeros(E, self.D, dtype=torch.float32, device=dev)
+                        if want_global_state else None)
+        self.state = self._state_struct(self.st, self.metrics, self.gs_live)
         self.gstate = None
         self.memory = None
 
@@ -249,13 +252,14 @@ class TabxEnv:
                       if want_action_mask else None)
 
     @staticmethod
-    def _state_struct(st: dict, metrics: dict) -> TabxState:
+    def _state_struct(st: dict, metrics: dict, global_state=None) -> TabxState:
         return TabxState(**{k: _cast(st[k], _F) for k in STATE_FLOAT},
                          alive=_cast(st["alive"], _U8),
                          t=_cast(st["t"], C.POINTER(C.c_int32)),
                          phi_prev=_cast(st["phi_prev"], _F),
                          **{n: _cast(metrics[n], t) for n, t, _ in METRICS if n in metrics},
-                         **{n: _cast(st[n], _I32) for n in LEVELS if n in st})
+                         **{n: _cast(st[n], _I32) for n in LEVELS if n in st},
+                         global_state=_cast(global_state, _F))
 
     def global_state(self, stream=None):
         if self.gstate is None:

@@ -261,7 +261,7 @@ static int check_state(const TabxParams *p, const TabxState *s)
     }
     if (!s->alive || !s->t) return TABX_ERR_NULL;
     if (!aligned(s->t, 4)) return TABX_ERR_ALIGN;
-    const void *m4[] = {s->ret_run, s->ep_count, s->ep_len, s->ep_return};
+    const void *m4[] = {s->ret_run, s->ep_count, s->ep_len, s->ep_return, s->global_state};
     for (const void *q : m4)
         if (q && !aligned(q, 4)) return TABX_ERR_ALIGN;
     return TABX_OK;

@@ -96,6 +96,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int D = a.obs_dim;
     const int Dp = a.row_pitch;
     const int CPR = Dp >> 2;                     // 16-byte chunks per staged row
+    const int zlen = 6 * a.p.max_zones;
     const bool has = P.has;
     const int lane = P.l & 63;
     const int wv = P.l >> 6;
@@ -278,6 +279,14 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                                           __int_as_float(__float_as_int(c13) & m),
                                           __int_as_float(__float_as_int(c14) & m),
                                           __int_as_float(__float_as_int(c15) & m));
+            if (self && a.st.global_state) {
+                // the own block with its absolute position is the unit's block of the global state
+                f4u *gs = reinterpret_cast<f4u *>(a.st.global_state + (size_t)P.e * D + 16 * P.u);
+                gs[0] = f4u{q0.x, q0.y, q0.z, q0.w};
+                gs[1] = f4u{q1.x, q1.y, q1.z, q1.w};
+                gs[2] = f4u{q2.x, q2.y, q2.z, q2.w};
+                gs[3] = f4u{q3.x, q3.y, q3.z, q3.w};
+            }
             const int cb = (buf + blk_row0 + 16 * blk) >> 2;       // first 16-byte chunk of the block
             if (blocks_aligned) {
                 float4 *d = stage + staged_chunk(cb);
@@ -303,6 +312,16 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 zo[k] = __int_as_float(__float_as_int(zval[k] - shift) & en);
             }
             stage[staged_chunk((buf + zone_dst0) >> 2)] = make_float4(zo[0], zo[1], zo[2], zo[3]);
+            if (a.st.global_state && i == 0) {
+                // ... and the zone slots with absolute centres are its tail
+                float *gz = a.st.global_state + (size_t)(P.grp * G + zg) * D + 16 * N + 4 * zc;
+                const int left = zlen - 4 * zc;
+                if (left >= 4) {
+                    *reinterpret_cast<f4u *>(gz) = f4u{zval[0], zval[1], zval[2], zval[3]};
+                } else {
+                    for (int k = 0; k < left; ++k) gz[k] = zval[k];
+                }
+            }
         }
     }
         lds_barrier<WAVES>();

@@ -32,7 +32,7 @@ def _pair(w, E, scenario=None, **override):
     p = I.make_params(w, E, **override)
     sc = I.make_scenario(w, E) if scenario is None else scenario
     ref = RefEnv(p, sc)
-    gpu = TabxEnv(p, sc, want_metrics=True)
+    gpu = TabxEnv(p, sc, want_metrics=True, want_global_state=True)
     ref.reset()
     gpu.reset()
     torch.cuda.synchronize()
@@ -63,6 +63,10 @@ def _rollout(w, E, steps, fused, scenario=None, obs_every=1, **override):
         inexact += compare_state(gpu.state_numpy(), ref.st, where)
         inexact += compare_outputs(gpu, ref, where, check_obs=look or fused)
         inexact += compare_metrics(gpu, ref, where)
+        if look or fused:
+            # the global state every observing call leaves in the state's output buffer
+            assert np.array_equal(gpu.gs_live.cpu().numpy(), ref.global_state()), \
+                where + "global state written by the observe stage"
         if s % 16 == 0:
             g = gpu.global_state()
             torch.cuda.synchronize()

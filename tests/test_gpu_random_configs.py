@@ -50,7 +50,7 @@ def test_random_configuration(seed):
     p = I.make_params(w, E, num_levels=L, level_seed=seed, **over)
     sc = I.make_scenario(w, L if L else E)
     ref = RefEnv(p, sc)
-    gpu = TabxEnv(p, sc, want_metrics=True)
+    gpu = TabxEnv(p, sc, want_metrics=True, want_global_state=True)
     ref.reset()
     gpu.reset()
     pol = I.policy("advanced", seed)
@@ -78,6 +78,8 @@ def test_random_configuration(seed):
         compare_state(gpu.state_numpy(), ref.st, where)
         compare_outputs(gpu, ref, where)
         compare_metrics(gpu, ref, where)
+        assert np.array_equal(gpu.gs_live.cpu().numpy(), ref.global_state()), \
+            where + "global state written by the observe stage"
         if s % 10 == 0:
             g = gpu.global_state()
             torch.cuda.synchronize()
