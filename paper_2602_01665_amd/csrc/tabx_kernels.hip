@@ -305,7 +305,10 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
                            stream, a);
         break;
     case MODE_STEP_OBSERVE:
-        if (WAVES == 1 && a.twin)
+        if (WAVES == 1 && a.twin > 2)
+            hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, false, 4>), grid, block,
+                               dyn_bytes, stream, a);
+        else if (WAVES == 1 && a.twin)
             hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, false, 2>), grid, block,
                                dyn_bytes, stream, a);
         else
@@ -453,6 +456,17 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
                                (mode == MODE_SCRIPTED_STEP_OBSERVE && small_batch))) {
             a.obs_per_chunk = per;
             a.twin = 2;
+            // 16 or more flushes: four wavefronts (N = 32: 99.6 -> 96.8 us, N = 64: 97.4 ->
+            // 91.7 us at 0.45 GB of rows per tick; fewer than four flushes each costs more than
+            // it saves: N = 16 with four, 92 -> 124 us)
+            // (as long as four staging areas fit the 64 KB of LDS a workgroup may take)
+            const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) * 17 / 16 + 64;
+            const size_t lds4 = 4 * (staged + sizeof(Shared<1>)) + sizeof(TwinShared);
+            if (mode == MODE_STEP_OBSERVE && N >= 16 * R && p->zone_shapes == 0 &&
+                lds4 <= 60 * 1024) {
+                a.twin = 4;
+                a.obs_per_chunk = ((N + 3) / 4 + R - 1) / R * R;
+            }
         }
     }
     a.copy_passes = (G * R * cpr + 64 * waves - 1) / (64 * waves);

@@ -112,6 +112,19 @@ def test_level_bank_rollouts(name, E, L, steps, over, fused):
     assert dones > E and len(seen) == L
 
 
+@pytest.mark.parametrize("team_size", [16, 23, 32])
+def test_level_bank_with_large_teams(team_size):
+    """32 to 64 units per env: the rows of an env group are written by four wavefronts, all of
+    which follow the level switch."""
+    import dataclasses
+    third = team_size // 3
+    w = dataclasses.replace(I.WORKLOADS["c3_16384env_10v10"], name=f"levels_{team_size}v{team_size}",
+                            team_size=team_size, role_counts=(team_size - 2 * third, third, third))
+    _say(f"[gpu] level bank {w.name}")
+    dones, seen = _rollout(w, 7, 5, 80, True, max_steps=11)
+    assert dones > 7 and len(seen) == 5
+
+
 def test_curriculum_overrides_the_draws():
     _say("[gpu] level bank with caller-chosen next levels")
     dones, seen = _rollout(I.WORKLOADS["c2_4096env_5v5"], 50, 11, 140, True, curriculum=True,
