@@ -152,6 +152,18 @@ def test_zone_descriptor_slots_and_full_cone():
     _rollout(w, 9, 40, False, scenario=sc, max_steps=30)
 
 
+@pytest.mark.parametrize("terrain", ["rects", "ellipses"])
+@pytest.mark.parametrize("team_size", [32, 64])
+def test_maximum_sizes(team_size, terrain):
+    """The largest rows the library takes: 128 units (two wavefronts per env) or 64 units (four
+    wavefronts per env group) with all 16 zone slots, as grid zones and as ellipses."""
+    w = I.Workload(f"max_{team_size}_{terrain}", 3, team_size, 96.0, 0 if terrain == "ellipses" else 48,
+                   terrain, 1.0, "iid", max_zones=16, spawn="clusters", steps=40, seed=5150 + team_size)
+    _say(f"[gpu] maximum sizes N={w.num_units} Z=16 {terrain}")
+    _rollout(w, 3, 40, True, max_steps=17)
+    _rollout(w, 3, 20, False, max_steps=17)
+
+
 @pytest.mark.parametrize("zones", [1, 2, 3, 5, 7])
 @pytest.mark.parametrize("team_size", [2, 5, 10, 40])
 def test_odd_zone_counts_and_row_alignment(zones, team_size):
