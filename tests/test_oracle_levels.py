@@ -102,6 +102,25 @@ def test_teams_and_enabled_flags_come_from_the_level():
     assert rew[0].tolist() == [0.75, 0.0, -0.75]       # disabled unit: no reward
 
 
+def test_team_of_an_enabled_unit_differs_between_levels():
+    # the same two farmers, sides swapped in level 1
+    l0 = I.custom_scenario([unit("farmer", 0, 4, 4), unit("farmer", 1, 24, 24)])
+    l1 = I.custom_scenario([unit("farmer", 1, 4, 4), unit("farmer", 0, 24, 24)])
+    p = I.custom_params(2, num_envs=2, num_levels=2)
+    env = ref.RefEnv(p, bank(l0, l1))
+    env.st["next_level"][:] = [0, 1]
+    env.reset()
+    hp = env.st["hp"].copy()
+    hp[:, 0] = 30.0                             # unit 0 at half health in both envs
+    env.set_state(hp=hp)
+    rew, _ = env.step(np.zeros((2, 2), np.uint8))
+    assert rew[0].tolist() == [-0.5, 0.5]       # level 0: unit 0 is the ally that suffers
+    assert rew[1].tolist() == [-0.5, 0.5]       # level 1: it is the adversary; its own team loses
+    assert env.st["phi_prev"].tolist() == [-0.5, 0.5]
+    obs, _, _ = env.observe()
+    assert obs[:, :, 15].tolist() == [[0.0, 1.0], [1.0, 0.0]]
+
+
 def test_terrain_and_zone_slots_come_from_the_level():
     g0 = np.zeros((1, 8, 8), np.int8)
     g1 = np.zeros((1, 8, 8), np.int8)

@@ -279,3 +279,98 @@ def test_heuristic_self_play_finishes_episodes():
         env.step(a)
         early += int((env.dones.astype(bool) & (env.st["ep_len"] < 256)).sum())
     assert early >= 4
+
+
+# ---- cases that separate the checker from copies with one slip (tests/oracle_mutants.py)
+def _with_memory(env, x, y):
+    if not hasattr(env, "mem"):          # the first call allocates the memory arrays
+        decide(env, controlled=np.zeros((env.E, env.N), np.uint8))
+    env.mem["mem_x"][0, 0], env.mem["mem_y"][0, 0], env.mem["mem_valid"][0, 0] = x, y, 1
+
+
+def test_equal_offsets_move_along_x():
+    # nothing in view (the enemy is behind); remembered positions on the diagonals
+    ctl = np.array([[1, 0]], np.uint8)
+    for (mx, my), move in [((13, 13), "xp"), ((7, 13), "xm"), ((13, 7), "xp"), ((7, 7), "xm")]:
+        env = make_ref([unit("farmer", 0, 10, 10, 0.0), unit("farmer", 1, 2, 10, 0.0)])
+        _with_memory(env, mx, my)
+        assert decide(env, controlled=ctl)[0, 0] == A[move]
+
+
+def test_arrival_radius_is_one():
+    ctl = np.array([[1, 0]], np.uint8)
+    env = make_ref([unit("farmer", 0, 10, 10, 0.0), unit("farmer", 1, 2, 10, 0.0)])
+    _with_memory(env, 10.9, 11.2)                 # 1.5 away: keep walking
+    assert decide(env, controlled=ctl)[0, 0] == A["yp"]
+    assert env.mem["mem_valid"][0, 0] == 1
+    _with_memory(env, 10.0, 11.25)                # 1.25 away
+    assert decide(env, controlled=ctl)[0, 0] == A["yp"]
+    _with_memory(env, 10.0, 11.0)                 # exactly 1 away: arrived (closed)
+    assert decide(env, controlled=ctl)[0, 0] in (A["left"], A["right"])
+    assert env.mem["mem_valid"][0, 0] == 0
+
+
+def test_ranger_threshold_is_inclusive_and_only_rangers_kite():
+    # a unit whose range is exactly the threshold is a Ranger: with the enemy in its hurtbox,
+    # 5 away (< 0.7 * 10) and the strike cooling down it steps back
+    cd = np.array([[3.0, 0.0]], np.float32)
+    env = make_ref([unit("farmer", 0, 16, 16, 0.0, range=10.0), unit("farmer", 1, 21, 16, math.pi)])
+    env.set_state(cd=cd)
+    assert decide(env)[0, 0] == A["xm"]
+    env = make_ref([unit("farmer", 0, 16, 16, 0.0, range=9.99), unit("farmer", 1, 21, 16, math.pi)])
+    env.set_state(cd=cd)
+    assert decide(env)[0, 0] == A["noop"]
+    # a plain farmer (range 2.5) with the enemy 1.5 away, inside 0.7 * 2.5, holds its ground
+    env = make_ref([unit("farmer", 0, 16, 10, math.pi / 2), unit("farmer", 1, 16, 11.5, 0.0)])
+    env.set_state(cd=cd)
+    assert decide(env)[0, 0] == A["noop"]
+
+
+def test_retreat_is_from_the_nearest_visible_enemy():
+    # archer heading +y, cooling down; enemy 1 straight ahead 4 away (in the hurtbox), enemy 2
+    # farther, up and to the right: away from enemy 1 is -y, away from enemy 2 would be -x
+    env = make_ref([unit("archer", 0, 16, 16, math.pi / 2), unit("farmer", 1, 16, 20, 0.0),
+                    unit("farmer", 1, 24, 22, 0.0)])
+    env.set_state(cd=np.array([[3.0, 0.0, 0.0]], np.float32))
+    assert decide(env, controlled=np.array([[1, 0, 0]], np.uint8))[0, 0] == A["ym"]
+    # the same with the two enemies listed in the other order
+    env = make_ref([unit("archer", 0, 16, 16, math.pi / 2), unit("farmer", 1, 24, 22, 0.0),
+                    unit("farmer", 1, 16, 20, 0.0)])
+    env.set_state(cd=np.array([[3.0, 0.0, 0.0]], np.float32))
+    assert decide(env, controlled=np.array([[1, 0, 0]], np.uint8))[0, 0] == A["ym"]
+
+
+def test_healer_keeps_an_injured_target_over_a_nearer_healthy_ally():
+    # the injured ally comes first in index order, the nearer healthy one after it
+    env = make_ref([unit("healer", 0, 4, 16, 0.0), unit("farmer", 0, 14, 17, 0.0),
+                    unit("farmer", 0, 8, 16, 0.0), unit("farmer", 1, 30, 2, 0.0)])
+    hp = env.st["hp"].copy()
+    hp[0, 1] = 10.0
+    env.set_state(hp=hp)
+    decide(env, controlled=np.array([[1, 0, 0, 0]], np.uint8))
+    assert (env.mem["mem_x"][0, 0], env.mem["mem_y"][0, 0]) == (14.0, 17.0)
+
+
+def test_a_possible_strike_comes_before_turning_to_the_target():
+    # the nearest enemy (the target) is within reach but off to the side; another enemy stands
+    # in the hurtbox: strike it now
+    env = make_ref([unit("archer", 0, 10, 10, 0.0), unit("farmer", 1, 12.0, 12.3, 0.0),
+                    unit("farmer", 1, 20, 10, 0.0)])
+    ctl = np.array([[1, 0, 0]], np.uint8)
+    assert decide(env, controlled=ctl)[0, 0] == A["attack"]
+    assert (env.mem["mem_x"][0, 0], env.mem["mem_y"][0, 0]) == (np.float32(12.0), np.float32(12.3))
+    # while the strike cools down it turns towards the target instead
+    env.set_state(cd=np.array([[3.0, 0.0, 0.0]], np.float32))
+    assert decide(env, controlled=ctl)[0, 0] == A["left"]
+
+
+def test_standoff_is_half_the_attack_range():
+    # target at (14, 12) heading +y: the point in front of it is (14, 13.25), offset (4, 3.25)
+    # from the farmer at (10, 10): along x; a full-range standoff (14, 14.5) would be along y
+    env = make_ref([unit("farmer", 0, 10, 10, math.pi / 4), unit("farmer", 1, 14, 12, math.pi / 2)])
+    assert decide(env, controlled=np.array([[1, 0]], np.uint8))[0, 0] == A["xp"]
+    # heading -y: the point (14, 10.75), offset (4, 0.75): along x as well; the assassin goes
+    # behind it, (14, 13.25)... with the target turned by a quarter, (12.75, 12): offset
+    # (2.75, 2) along x, where a full-range standoff (11.5, 12) would be along y
+    env = make_ref([unit("assassin", 0, 10, 10, math.pi / 4), unit("farmer", 1, 14, 12, 0.0)])
+    assert decide(env, controlled=np.array([[1, 0]], np.uint8))[0, 0] == A["xp"]
