@@ -42,8 +42,8 @@ struct KArgs {
     int       zdesc_staged;        // ... which exists for elliptical zones and for deciding units
     int       script_offset;       // scripted units deciding in the observe stage: their LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)
-    int       twin;                // 2: two wavefronts per workgroup own the same env group and
-                                   //    share its observers (chunk = wavefront index)
+    int       twin;                // 2 or 4: that many wavefronts of a workgroup own the same env
+                                   //    group and share its observers (chunk = wavefront index)
     int       dyn_stride;          // twin: floats of dynamic LDS per wavefront
     int       obs_chunks;          // workgroups that share the observers of one env group (>= 1)
     int       obs_per_chunk;       // observers per such workgroup (a multiple of rows_per_flush)

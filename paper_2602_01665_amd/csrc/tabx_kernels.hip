@@ -50,7 +50,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     const int half = TWIN ? (int)(threadIdx.x >> 6) : 0;
     Shared<WAVES> &sh = sh_all[half];
     float *dyn_lds = dyn_all + half * a.dyn_stride;
-    int *rows = TWIN ? twin.rows : sh.rows;     // TWIN: 0, or the 2 of twin wavefronts
+    int *rows = TWIN ? twin.rows : sh.rows;     // TWIN: 0, or how many wavefronts share an env group
     Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
@@ -424,22 +424,20 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         a.cell_pow2 = (mant == 0.5f && ex > -100 && ex < 100) ? 1 : 0;
         a.inv_cell = 1.0f / p->cell_size;
     }
-    // A stand-alone observe spreads the observers of an env group over two workgroups (each
-    // loads the group's units and writes half of its rows): shorter-lived wavefronts, twice as
-    // many of them; measured -3 ... -9 % on the packed-env kernels, +5 % with two-wave envs.
-    // A launch that steps cannot: the second workgroup would need the state after the step.
     // Long-lived wavefronts make a long tail at the end of the launch, and a wavefront's chain
     // of flushes is the latency floor of a small batch.  Where that matters the observers of an
     // env group are split between two wavefronts:
     //  - a stand-alone observe uses two workgroups per group (each loads the group's units and
-    //    writes half of its rows): measured -3 ... -9 % on the packed-env kernels;
+    //    writes half of its rows): measured -3 ... -9 % on the packed-env kernels, +5 % with
+    //    two-wave envs, which therefore do not split;
     //  - a launch that also steps cannot (the second workgroup would need the state after the
     //    first one's step), but twin wavefronts of ONE workgroup can: both load the units, both
     //    run the step stage, a workgroup barrier keeps the first one's state stores behind the
     //    second one's loads.  Measured: c3 107 -> 99.5 us, c2 15.8 -> 14.0 us, but c4 (10 observers,
     //    five flushes per wavefront, a full machine) 87 -> 102 us, c3 with elliptical zones (a
     //    costlier step to repeat) 110 -> 112.5 us and the scripted c3 tick +3 us, hence the
-    //    conditions below.  Three or four wavefronts per group: 120 us and more on c3.
+    //    conditions below.  Three or four wavefronts per group: 120 us and more on c3, but a
+    //    gain from 32 units per env on (below).
     a.obs_chunks = 1;
     a.obs_per_chunk = N;
     a.twin = 0;
