@@ -430,6 +430,53 @@ def test_full_size_sampled_envs(name, steps, n_sample):
     assert torch.equal((-r[:, :1]).expand(E, N)[team], r[team])
 
 
+def test_observation_tensor_beyond_two_giga_floats():
+    """1.44 million 5v5 envs: the observation tensor has more than 2^31 floats (9.2 GB), so every
+    row offset must be computed in 64 bits; sampled envs from both ends and from behind the 2^31
+    boundary are compared tick by tick, fused and as separate calls."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = I.WORKLOADS["c4_65536env_5v5"]
+    E, N = 1441792 + 5, w.num_units
+    p = I.make_params(w, E, max_steps=3)
+    D = I.obs_dim(N, p["max_zones"])
+    assert E * N * D > 2 ** 31 and E * N <= 2 ** 30
+    _say(f"[gpu] large batch: E={E} N={N} D={D}: {E * N * D * 4 / 1e9:.1f} GB of observations")
+    sc = I.make_scenario(w, E)
+    first_behind = 2 ** 31 // (N * D) + 1
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, first_behind - 1, first_behind, E - 2, E - 1],
+                                     rng.choice(E, 26, replace=False)]))
+    ref = RefEnv(I.make_params(w, len(rows), max_steps=3), I.take_envs(sc, rows))
+    gpu = TabxEnv(p, sc, want_metrics=True)
+    ref.reset()
+    gpu.reset()
+    rows_t = torch.from_numpy(rows).to("cuda:0")
+    dones = 0
+    for s in range(8):
+        a = I.actions_for_step(w.seed, s, E, N)
+        ad = torch.from_numpy(a).to("cuda:0")
+        if s % 2 == 0:
+            gpu.step_observe(ad)
+        else:
+            gpu.step(ad)
+            gpu.observe()
+        ref.step(a[rows])
+        ref.observe()
+        st = {k: (v.reshape(E, N)[rows_t] if v.numel() == E * N else v[rows_t]).cpu().numpy()
+              for k, v in gpu.st.items()}
+        where = f"large batch step {s}: "
+        compare_state(st, ref.st, where)
+        compare_outputs(gpu, ref, where, rows=rows_t)
+        compare_metrics(gpu, ref, where, rows=rows_t)
+        dones += int(ref.dones.sum())
+    assert dones >= 2 * len(rows)
+    assert torch.isfinite(gpu.obs[-4096:]).all()
+    del gpu
+    torch.cuda.empty_cache()
+
+
 def test_calls_can_be_captured_into_a_graph():
     """The entry points allocate nothing and only enqueue kernels, so a stream capture records
     them; replays (with eager work and synchronisations in between) give what eager calls give."""
