@@ -77,7 +77,8 @@ def cpu_baseline(w, I, scenario: dict, sample_envs: int, ticks: int) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed ticks (default: the workload's own step count, 1000 for the headline)")
     ap.add_argument("--warmup", type=int, default=300,
                     help="untimed ticks before the timed region (the clocks of an idle GPU take a few ms to settle)")
     ap.add_argument("--workload", default=None)
@@ -101,6 +102,9 @@ def main() -> int:
     ap.add_argument("--global-state", action="store_true",
                     help="also have every tick write the global state (TabxState.global_state), "
                          "as a centralised critic would want it; not the headline tick")
+    ap.add_argument("--action-batches", type=int, default=None,
+                    help="distinct pre-generated action batches (default: one per tick, at most "
+                         "1 GiB of them); fewer are cycled")
     ap.add_argument("--policy-scan", action="store_true",
                     help="with --policy: the policy as a stage of its own in front of the step")
     args = ap.parse_args()
@@ -127,7 +131,13 @@ def main() -> int:
     scenario = I.make_scenario(w)
     env = TabxEnv(p, scenario, want_global_state=args.global_state)
     env.reset()
-    n_act = min(args.steps + args.warmup, 64)
+    if args.steps is None:
+        args.steps = w.steps
+    # one seeded action batch per tick, resident on the device before the clock starts (at most
+    # 1 GiB of them; longer runs cycle)
+    n_act = max(1, min(args.steps + args.warmup, (1 << 30) // (E * N)))
+    if args.action_batches:
+        n_act = max(1, min(n_act, args.action_batches))
     acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, N)).to("cuda:0")
             for s in range(n_act)]
     stream = torch.cuda.current_stream()
@@ -191,7 +201,8 @@ def main() -> int:
                    "body_collisions": bool(args.collisions),
                    "scripted_adversaries": args.policy,
                    "global_state_every_tick": bool(args.global_state),
-                   "actions": f"{n_act} pre-generated seeded uniform action batches, cycled"},
+                   "actions": f"{n_act} pre-generated seeded uniform action batches on the device"
+                              + ("" if n_act >= args.steps + args.warmup else ", cycled")},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": B_env * E,

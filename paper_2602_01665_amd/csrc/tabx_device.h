@@ -101,6 +101,7 @@ struct Carry {
     float ratio;       // hp / hmax
     int   tick;        // the env's tick counter after the step
     bool  restarted;   // the env's episode ended in this step
+    int   warm;        // a byte loaded only to bring its cache line in (see step_env)
 };
 
 // Registers of one unit: mutable state, then read-only specification.

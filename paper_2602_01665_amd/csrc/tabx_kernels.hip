@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         lds_barrier<WAVES>();
     }
     float *zd = zdesc + (P.has ? P.g : 0) * zlen;
-    Carry C = {1.0f, 0.0f, 0.0f, 0, false};
+    Carry C = {1.0f, 0.0f, 0.0f, 0, false, 0};
     float zeff_unused = 0.0f;
     int forced = -1;
     if (SCRIPT) {
@@ -106,6 +106,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     if (SCRIPT && !DO_STEP && P.has) C.tick = a.st.t[P.e];
     ScriptLds<WAVES> *script = reinterpret_cast<ScriptLds<WAVES> *>(dyn_lds + a.script_offset);
     if (DO_OBS) observe_env<WAVES, DO_STEP, SCRIPT>(a, sh, dyn_lds, P, U, code_u, C, Zr, script, zd);
+    if (DO_STEP) asm volatile("" ::"v"(C.warm));    // keeps the cache-warming load of step_env
 }
 
 template <int WAVES>

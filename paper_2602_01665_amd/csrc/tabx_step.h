@@ -109,6 +109,19 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     // the position is final for this tick: fetch the terrain cell under it now, the zone
     // effects of stage 3 use it after the combat exchange
     if (has && U.enabled) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff);
+    // The action array is the one input that is new in every tick, so its lines come from HBM,
+    // where a read queues behind the observation stores for microseconds once those are
+    // flowing, and every wavefront's step stage waits for its action bytes.  The first
+    // wavefronts of each XCD, which start while HBM is still idle, therefore touch every line of
+    // their XCD's share of the array (lane l of the j-th wavefront: line 64 j + l); the later
+    // generations find them in the cache.  Measured with a fresh action batch per tick:
+    // c3 108.6 -> 102.5 us, c4 95.4 -> 89.7 us (101 / 88 us with actions that are cached anyway).
+    if (writer) {
+        const size_t span = (size_t)a.groups_per_xcd * a.envs_per_block * N;   // units per XCD
+        const size_t first = (size_t)(blockIdx.x & 7) * span;
+        const size_t off = ((size_t)(blockIdx.x >> 3) * 64 + (size_t)(threadIdx.x & 63)) * 128;
+        if (off < span && first + off < (size_t)a.p.num_envs * N) C.warm = a.actions[first + off];
+    }
 
     // stage 2a: movement sets next tick's velocity, rotation turns the heading now
     float cu = 1.0f, su = 0.0f;
