@@ -23,8 +23,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
 # copy kernel of known size); see profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/tabx_tick_c3_16384env_10v10.md: WRITE_SIZE 487590.7 KiB x 1.0 + FETCH_SIZE 30610.1 KiB x 2.0
-    "c3_16384env_10v10": int((487590.7 + 2.0 * 30610.1) * 1024),
+    # profiles/tabx_tick_<workload>.md: (WRITE_SIZE KiB x 1.0 + FETCH_SIZE KiB x 2.0) x 1024
+    "c3_16384env_10v10": int((487573.3 + 2.0 * 30688.4) * 1024),
+    "c4_65536env_5v5": int((442461.9 + 2.0 * 27459.0) * 1024),
+    "c5_1024env_64v64": int((1056009.0 + 2.0 * 9794.9) * 1024),
+    "c2_4096env_5v5": int((27636.9 + 2.0 * 4123.1) * 1024),
 }
 
 
@@ -187,7 +190,8 @@ def main() -> int:
     assert torch.isfinite(env.obs).all()
     B_env = algorithmic_bytes_per_env(N, env.D, p["max_zones"])
     achieved = B_env * E / (kernel_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(name)
+    plain = not (args.collisions or args.separate or args.policy or args.global_state)
+    traffic = MEASURED_TRAFFIC_BYTES.get(name) if plain else None     # measured for the fused tick
     out = {
         "metric": "agent-steps/sec (step+observe) at 16384 envs 10v10; HBM GB/s vs peak",
         "value": E * N * args.steps / wall,

@@ -319,7 +319,11 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 if (left >= 4) {
                     *reinterpret_cast<f4u *>(gz) = f4u{zval[0], zval[1], zval[2], zval[3]};
                 } else {
-                    for (int k = 0; k < left; ++k) gz[k] = zval[k];
+                    // (constant indices: a runtime index would move the zone registers to
+                    // scratch memory for the whole kernel)
+#pragma unroll
+                    for (int k = 0; k < 3; ++k)
+                        if (k < left) gz[k] = zval[k];
                 }
             }
         }
