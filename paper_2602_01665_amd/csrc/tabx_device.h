@@ -102,6 +102,10 @@ struct Carry {
     int   tick;        // the env's tick counter after the step
     bool  restarted;   // the env's episode ended in this step
     int   warm;        // a byte loaded only to bring its cache line in (see step_env)
+    // scripted units: the remembered target position as it was at the start of the call
+    // (loaded with the state: at the end of the wavefront a load would queue behind its stores)
+    int   mem_valid;
+    float mem_x, mem_y;
 };
 
 // Registers of one unit: mutable state, then read-only specification.

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         lds_barrier<WAVES>();
     }
     float *zd = zdesc + (P.has ? P.g : 0) * zlen;
-    Carry C = {1.0f, 0.0f, 0.0f, 0, false, 0};
+    Carry C = {1.0f, 0.0f, 0.0f, 0, false, 0, 0, 0.0f, 0.0f};
     float zeff_unused = 0.0f;
     int forced = -1;
     if (SCRIPT) {
@@ -85,6 +85,9 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         if (decides) {
             forced = a.pa.next_action[P.k];
             if (P.chunk == 0) a.pa.actions_out[P.k] = (uint8_t)forced;
+            C.mem_valid = a.pa.mem.mem_valid[P.k];
+            C.mem_x = a.pa.mem.mem_x[P.k];
+            C.mem_y = a.pa.mem.mem_y[P.k];
         }
     }
     if (DO_POLICY) {

@@ -412,9 +412,9 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             S.near_dx = E.x - U.x;
             S.near_dy = E.y - U.y;
             S.can_hit = script->canhit[P.l] != 0;
-            const int remembered = C.restarted ? 0 : a.pa.mem.mem_valid[P.k];
-            const float mx = a.pa.mem.mem_x[P.k];
-            const float my = a.pa.mem.mem_y[P.k];
+            const int remembered = C.restarted ? 0 : C.mem_valid;
+            const float mx = C.mem_x;
+            const float my = C.mem_y;
             policy_cascade(a, P, U, cu, su, in_bush, S, (uint32_t)C.tick, remembered, mx, my, zd,
                            a.pa.next_action);
         }
