@@ -51,6 +51,11 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     // per-env scalars, requested early: they are needed only after three LDS exchanges
     const int t_new = has ? a.st.t[P.e] + 1 : 0;
     const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
+    // ... and the running episode metrics, if kept: loaded where they are used, at the end of the
+    // stage, they would queue behind the observation stores of the other wavefronts
+    const bool want_kills = a.st.kill_run != nullptr;
+    const int kills_run = (want_kills && has) ? a.st.kill_run[P.e] : 0;
+    const float ret_run = (a.st.ret_run && has) ? a.st.ret_run[P.e] : 0.0f;
     float bdmg = 0.0f;
     // twin wavefronts compute the same step; only the first one writes it back, and not before
     // both have everything they read from global memory
@@ -269,7 +274,6 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     int cnt[4];
     env_counts(sh, P, N, pred, cnt);
     // episode metrics need the alive counts at entry as well (first loss of a unit)
-    const bool want_kills = a.st.kill_run != nullptr;
     int before[4] = {0, 0, 0, 0};
     if (want_kills) {
         const bool pred0[4] = {alive0 && U.team == 0, alive0 && U.team != 0, false, false};
@@ -351,13 +355,13 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         // episode metrics: first loss of a unit, running allied return, summary at the end
         int kills = 0;
         if (want_kills) {
-            kills = a.st.kill_run[P.e];
+            kills = kills_run;
             if (kills == 0) kills = (cnt[3] < before[1] ? 1 : 0) | (cnt[2] < before[0] ? 2 : 0);
             a.st.kill_run[P.e] = (int8_t)(done ? 0 : kills);
         }
         float ret = 0.0f;
         if (a.st.ret_run) {
-            ret = a.st.ret_run[P.e] + r0;
+            ret = ret_run + r0;
             a.st.ret_run[P.e] = done ? 0.0f : ret;
         }
         if (done) {
