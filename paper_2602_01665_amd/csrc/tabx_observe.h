@@ -166,13 +166,18 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     int valid[kMaxPasses];
     {
         const int RC = R * CPR;                    // chunks per env slot and flush
-        int tg = P.l / RC;                         // env slot of chunk t
-        int q = P.l - tg * RC;                     // chunk within the env's R staged rows
+        const bool whole = (D & 3) == 0;           // no row ends inside a chunk (always so if R > 1)
+        int tg = 0;                                // env slot of chunk t
+        int q = P.l;                               // chunk within the env's R staged rows
+        while (q >= RC) {                          // (RC >= 64 for all but tiny rows)
+            q -= RC;
+            tg += 1;
+        }
 #pragma unroll
         for (int p = 0; p < kMaxPasses; ++p) {
-            int vm = 0;                            // R > 1 only when D is a multiple of 4
-#pragma unroll
-            for (int k = 0; k < 4; ++k) vm |= (R > 1 || 4 * q + k < D) ? (1 << k) : 0;
+            // which of the chunk's four floats belong to the row
+            const int left = D - 4 * q;
+            const int vm = (whole || left >= 4) ? 15 : ((1 << (left > 0 ? left : 0)) - 1);
             valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
             dst_off[p] = (unsigned)(tg * N * D + 4 * q);
             q += LANES;                            // chunk t + LANES of the next pass
