@@ -178,7 +178,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             // which of the chunk's four floats belong to the row
             const int left = D - 4 * q;
             const int vm = (whole || left >= 4) ? 15 : ((1 << (left > 0 ? left : 0)) - 1);
-            valid[p] = (p < a.copy_passes && tg < envs_here) ? vm : 0;
+            // (a pass beyond copy_passes holds only chunks of env slots >= G >= envs_here)
+            valid[p] = tg < envs_here ? vm : 0;
             dst_off[p] = (unsigned)(tg * N * D + 4 * q);
             q += LANES;                            // chunk t + LANES of the next pass
             while (q >= RC) {
