@@ -352,7 +352,11 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                     v[p] = src[p * PASS_STRIDE];
 #pragma unroll
             for (int p = 0; p < kMaxPasses; ++p) {
-                if (p < a.copy_passes && valid[p] != 0) {
+                // (the mask is made opaque here: as a loop invariant its tests would be hoisted
+                // out of the observer loop as forty lane masks, most of them spilled)
+                int vm = valid[p];
+                asm volatile("" : "+v"(vm));
+                if (p < a.copy_passes && vm != 0) {
                     // single-wave workgroups stream with the non-temporal hint: the rows are
                     // never read back by the kernel, and the hint measurably raises the store
                     // rate there (it lowers it for the two-wave, 8 KB-row case)
@@ -366,7 +370,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             // rows that are not a multiple of 16 bytes end in a partial chunk
 #pragma unroll
             for (int p = 0; p < kMaxPasses; ++p) {
-                const int vm = valid[p];
+                int vm = valid[p];
+                asm volatile("" : "+v"(vm));
                 if (p < a.copy_passes && vm != 0) {
                     const float4 v = src[p * PASS_STRIDE];
                     float *dp = row + dst_off[p];
