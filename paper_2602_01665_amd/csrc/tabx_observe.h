@@ -182,9 +182,15 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             valid[p] = tg < envs_here ? vm : 0;
             dst_off[p] = (unsigned)(tg * N * D + 4 * q);
             q += LANES;                            // chunk t + LANES of the next pass
-            while (q >= RC) {
-                q -= RC;
-                tg += 1;
+            if (RC >= LANES) {                     // at most one env slot further
+                const bool next_slot = q >= RC;
+                q = next_slot ? q - RC : q;
+                tg = next_slot ? tg + 1 : tg;
+            } else {
+                while (q >= RC) {
+                    q -= RC;
+                    tg += 1;
+                }
             }
         }
     }
