@@ -159,9 +159,9 @@ struct Shared {
     int      rows[WAVES == 1 ? 64 : 1];   // level bank: the row an env slot has just switched to, or -1
 };
 
-// Twin wavefronts: both load the same units and run the step stage redundantly in their own
-// LDS areas; wavefront 0 alone writes the state, each writes the rows of its half of the
-// observers.  What they do share sits here.
+// Several wavefronts of one workgroup may share an env group (fused tick): the first one runs
+// the step stage and alone touches the state; the others take the stepped units over through
+// LDS and each writes the rows of its share of the observers.  What they all see sits here.
 struct TwinShared {
     int rows[64];      // level bank: the row an env slot has just switched to, or -1
 };

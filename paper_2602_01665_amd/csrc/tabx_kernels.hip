@@ -54,9 +54,12 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
+    // TWIN: the first wavefront of the workgroup runs the step stage; the others, which only
+    // write their share of the observers' rows afterwards, take its result over through LDS
+    const bool lead = !TWIN || half == 0;
     if (P.has) {
         load_spec(a, P.ks, U);
-        load_state(a, P.k, U);
+        if (lead) load_state(a, P.k, U);
     }
     ZoneRegs Zr = {};
     if (DO_OBS) Zr = load_zone_regs<WAVES>(a, P);
@@ -80,11 +83,15 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     int forced = -1;
     if (SCRIPT) {
         // the action this unit decided on at the end of the previous call
-        const bool decides = P.has && U.enabled && U.alive &&
+        // (a wavefront that does not step has no alive flags yet: it loads the memories of
+        // all the units the policy may move)
+        const bool decides = P.has && U.enabled && (U.alive || !lead) &&
                              (!a.pa.controlled || a.pa.controlled[P.k]);
         if (decides) {
-            forced = a.pa.next_action[P.k];
-            if (P.chunk == 0) a.pa.actions_out[P.k] = (uint8_t)forced;
+            if (lead) {
+                forced = a.pa.next_action[P.k];
+                a.pa.actions_out[P.k] = (uint8_t)forced;
+            }
             C.mem_valid = a.pa.mem.mem_valid[P.k];
             C.mem_x = a.pa.mem.mem_x[P.k];
             C.mem_y = a.pa.mem.mem_y[P.k];
@@ -99,8 +106,53 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su, zd);
     }
     bool restarted = false;
-    if (DO_STEP) restarted = step_env<WAVES>(a, sh, zd, rows, P, U, code_u, C, forced);
-    else if (P.has && !DO_POLICY) code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
+    if (DO_STEP && lead) {
+        restarted = step_env<WAVES>(a, sh, zd, rows, P, U, code_u, C, forced);
+        if (TWIN) {
+            // hand the stepped units to the other wavefronts: three 16-byte records per lane in
+            // each one's row staging area, which it does not use before it has read them
+            const float4 r0 = make_float4(U.x, U.y, U.theta, U.hp);
+            const float4 r1 = make_float4(U.cd, U.reveal, U.cur_speed, __int_as_float(C.tick));
+            const float4 r2 = make_float4(C.cu, C.su, __int_as_float(code_u),
+                                          __int_as_float(U.alive | (C.restarted ? 2 : 0)));
+            for (int w = 1; w < TWIN; ++w) {
+                float4 *box = reinterpret_cast<float4 *>(dyn_all + w * a.dyn_stride);
+                box[P.l] = r0;
+                box[64 + P.l] = r1;
+                box[128 + P.l] = r2;
+            }
+            lds_barrier<2>();
+        }
+    } else if (DO_STEP) {
+        lds_barrier<2>();
+        const float4 *box = reinterpret_cast<const float4 *>(dyn_lds);
+        const float4 r0 = box[P.l], r1 = box[64 + P.l], r2 = box[128 + P.l];
+        U.x = r0.x; U.y = r0.y; U.theta = r0.z; U.hp = r0.w;
+        U.cd = r1.x; U.reveal = r1.y; U.cur_speed = r1.z; C.tick = __float_as_int(r1.w);
+        C.cu = r2.x; C.su = r2.y; code_u = __float_as_int(r2.z);
+        const int flags = __float_as_int(r2.w);
+        U.alive = flags & 1;
+        C.restarted = (flags & 2) != 0;
+        restarted = __ballot(C.restarted) != 0ull;
+        lds_barrier<1>();          // the records are read: the staging area may take rows now
+        if (a.p.num_levels > 0 && restarted) {
+            // envs that moved to another level: their specifications and elliptical zones
+            const int row = (P.has && C.restarted) ? rows[P.g] : -1;
+            if (row >= 0) {
+                P.row = row;
+                P.ks = (size_t)row * a.p.num_units + P.u;
+                load_spec(a, P.ks, U);
+                if (a.zdesc_staged)
+                    for (int q = P.u; q < zlen; q += a.p.num_units)
+                        zd[q] = a.sc.zone_desc[(size_t)row * zlen + q];
+            }
+            if (a.zdesc_staged) lds_barrier<1>();
+        }
+        // the unit's health ratio, as the step stage leaves it (same operands, same rounding)
+        C.ratio = (P.has && U.enabled) ? U.hp / U.hmax : 0.0f;
+    } else if (P.has && !DO_POLICY) {
+        code_u = zone_at(a, zd, P.row, U.x, U.y, zeff_unused);
+    }
     if (DO_STEP && DO_OBS && a.p.num_levels > 0 && restarted) {
         // zone slots of the envs that changed level
         const int row = Zr.lane ? rows[Zr.zg] : -1;
@@ -283,6 +335,8 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     size_t dyn_floats = rows_staged * a.row_pitch;
     const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
     if (dyn_floats < pass_floats) dyn_floats = pass_floats;
+    // (wavefronts that take over another one's step receive three 16-byte records per lane here)
+    if (a.twin && dyn_floats < 3 * 64 * 4) dyn_floats = 3 * 64 * 4;
     // ... with one spare 16-byte chunk after every 16 (see staged_chunk)
     dyn_floats = 4 * ((dyn_floats + 3) / 4 + (dyn_floats + 3) / 64 + 1);
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
@@ -430,16 +484,18 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     }
     // Long-lived wavefronts make a long tail at the end of the launch, and a wavefront's chain
     // of flushes is the latency floor of a small batch.  Where that matters the observers of an
-    // env group are split between two wavefronts:
+    // env group are split between several wavefronts:
     //  - a stand-alone observe uses two workgroups per group (each loads the group's units and
     //    writes half of its rows): measured -3 ... -9 % on the packed-env kernels, +5 % with
     //    two-wave envs, which therefore do not split;
     //  - a launch that also steps cannot (the second workgroup would need the state after the
-    //    first one's step), but twin wavefronts of ONE workgroup can: both load the units, both
-    //    run the step stage, a workgroup barrier keeps the first one's state stores behind the
-    //    second one's loads.  Measured: c3 107 -> 99.5 us, c2 15.8 -> 14.0 us, but c4 (10 observers,
-    //    five flushes per wavefront, a full machine) 87 -> 102 us, c3 with elliptical zones (a
-    //    costlier step to repeat) 110 -> 112.5 us and the scripted c3 tick +3 us, hence the
+    //    first one's step), but the wavefronts of ONE workgroup can: the first one runs the step
+    //    stage and hands the stepped units to the others through LDS (see the kernel); all of
+    //    them load the specifications meanwhile and then write their share of the rows.
+    //    Measured: c3 107 -> 99.5 us, c2 15.8 -> 14.0 us, but c4 (10 observers, five flushes per
+    //    wavefront, a full machine) 87 -> 102 us; with a longer step stage the wavefronts that
+    //    wait for it cost more than the shorter chains save: elliptical zones 107.3 -> 111.6 us,
+    //    body collisions 111.9 -> 114.0 us, the scripted c3 tick 117.0 -> 129.0 us; hence the
     //    conditions below.  Three or four wavefronts per group: 120 us and more on c3, but a
     //    gain from 32 units per env on (below).
     a.obs_chunks = 1;
@@ -449,8 +505,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         const int per = ((N + 1) / 2 + R - 1) / R * R;
         const int num_groups = (p->num_envs + G - 1) / G;
         const bool small_batch = num_groups <= 2048;             // under one residency round
-        // eight or more flushes, and a step stage that is cheap to run twice (with body
-        // collisions on c3: 116.9 us with twin wavefronts, 114.1 without)
+        // eight or more flushes, and a short step stage
         const bool long_chain = N >= 16 * R / 2 && p->zone_shapes == 0 && !(p->collision_alpha > 0.0f);
         if (per < N && mode == MODE_OBSERVE) {
             a.obs_per_chunk = per;

@@ -29,8 +29,7 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
         }
         rows[P.g] = row;
     }
-    if (a.twin) lds_barrier<2>();          // `rows` is shared by the two wavefronts
-    else lds_barrier<WAVES>();
+    lds_barrier<WAVES>();
     return P.has ? rows[P.g] : -1;
 }
 
@@ -57,10 +56,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     const int kills_run = (want_kills && has) ? a.st.kill_run[P.e] : 0;
     const float ret_run = (a.st.ret_run && has) ? a.st.ret_run[P.e] : 0.0f;
     float bdmg = 0.0f;
-    // twin wavefronts compute the same step; only the first one writes it back, and not before
-    // both have everything they read from global memory
-    const bool writer = P.chunk == 0;
-    if (a.twin) __syncthreads();
+    const bool writer = P.chunk == 0;      // (always: only a group's first wavefront steps)
 
     // stage 1: cooldown / reveal timers, explicit Euler move, arena penalty + clip
     if (has && U.enabled) {
