@@ -225,35 +225,44 @@ __device__ __forceinline__ float zone_magnitude(const KArgs &a, float own_effect
     return a.p.zone_shapes == 1 ? own_effect : global_value;
 }
 
+// Element k of a per-unit array (at most 2^30 elements: its byte offset fits 32 bits, so the
+// access is "uniform base + 32-bit lane offset" and needs no 64-bit address arithmetic per lane).
+template <class T>
+__device__ __forceinline__ const T &at32(const T *base, size_t k)
+{
+    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) +
+                                        (uint32_t)(k * sizeof(T)));
+}
+
 __device__ __forceinline__ void load_spec(const KArgs &a, size_t k, Unit &U)
 {
-    U.hmax = a.sc.hmax[k];
-    U.radius = a.sc.radius[k];
-    U.mass = a.sc.mass[k];
-    U.speed = a.sc.speed[k];
-    U.dmg = a.sc.dmg[k];
-    U.range = a.sc.range[k];
-    U.cooldown = a.sc.cooldown[k];
-    U.sight_angle = a.sc.sight_angle[k];
-    U.cos_half = a.sc.sight_cos_half[k];
-    U.sight_range = a.sc.sight_range[k];
-    U.hurt_hw = a.sc.hurt_halfwidth[k];
-    U.team = a.sc.team[k];
-    U.enabled = a.sc.enabled[k];
+    U.hmax = at32(a.sc.hmax, k);
+    U.radius = at32(a.sc.radius, k);
+    U.mass = at32(a.sc.mass, k);
+    U.speed = at32(a.sc.speed, k);
+    U.dmg = at32(a.sc.dmg, k);
+    U.range = at32(a.sc.range, k);
+    U.cooldown = at32(a.sc.cooldown, k);
+    U.sight_angle = at32(a.sc.sight_angle, k);
+    U.cos_half = at32(a.sc.sight_cos_half, k);
+    U.sight_range = at32(a.sc.sight_range, k);
+    U.hurt_hw = at32(a.sc.hurt_halfwidth, k);
+    U.team = at32(a.sc.team, k);
+    U.enabled = at32(a.sc.enabled, k);
 }
 
 __device__ __forceinline__ void load_state(const KArgs &a, size_t k, Unit &U)
 {
-    U.x = a.st.x[k];
-    U.y = a.st.y[k];
-    U.vx = a.st.vx[k];
-    U.vy = a.st.vy[k];
-    U.theta = a.st.theta[k];
-    U.hp = a.st.hp[k];
-    U.cd = a.st.cd[k];
-    U.reveal = a.st.reveal[k];
-    U.cur_speed = a.st.cur_speed[k];
-    U.alive = a.st.alive[k];
+    U.x = at32(a.st.x, k);
+    U.y = at32(a.st.y, k);
+    U.vx = at32(a.st.vx, k);
+    U.vy = at32(a.st.vy, k);
+    U.theta = at32(a.st.theta, k);
+    U.hp = at32(a.st.hp, k);
+    U.cd = at32(a.st.cd, k);
+    U.reveal = at32(a.st.reveal, k);
+    U.cur_speed = at32(a.st.cur_speed, k);
+    U.alive = at32(a.st.alive, k);
 }
 
 __device__ __forceinline__ void store_state(const KArgs &a, size_t k, const Unit &U)

@@ -86,15 +86,15 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         // (a wavefront that does not step has no alive flags yet: it loads the memories of
         // all the units the policy may move)
         const bool decides = P.has && U.enabled && (U.alive || !lead) &&
-                             (!a.pa.controlled || a.pa.controlled[P.k]);
+                             (!a.pa.controlled || at32(a.pa.controlled, P.k));
         if (decides) {
             if (lead) {
-                forced = a.pa.next_action[P.k];
+                forced = at32(a.pa.next_action, P.k);
                 a.pa.actions_out[P.k] = (uint8_t)forced;
             }
-            C.mem_valid = a.pa.mem.mem_valid[P.k];
-            C.mem_x = a.pa.mem.mem_x[P.k];
-            C.mem_y = a.pa.mem.mem_y[P.k];
+            C.mem_valid = at32(a.pa.mem.mem_valid, P.k);
+            C.mem_x = at32(a.pa.mem.mem_x, P.k);
+            C.mem_y = at32(a.pa.mem.mem_y, P.k);
         }
     }
     if (DO_POLICY) {

@@ -132,7 +132,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         sh.ob.reach[P.l] = make_float4(U.range, U.hurt_hw, U.sight_range * U.sight_range, U.cos_half);
         int role = 0;
         if (SCRIPT) {
-            const bool decides = enabled && alive && (!a.pa.controlled || a.pa.controlled[P.k]);
+            const bool decides = enabled && alive && (!a.pa.controlled || at32(a.pa.controlled, P.k));
             role = (U.speed >= a.pa.pol.assassin_speed ? 0x10 : 0) | (decides ? 0x20 : 0);
             script->tkey[P.l] = ~0ull;
             script->nkey[P.l] = ~0ull;

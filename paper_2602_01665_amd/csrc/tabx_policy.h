@@ -145,7 +145,7 @@ __device__ __forceinline__ int policy_env(const KArgs &a, Shared<WAVES> &sh, con
     sh.po.body[P.l] = make_float4(U.radius, U.hmax, U.hp, 0.0f);
     sh.seer[P.l] = (P.has ? U.alive : 0) | (U.team << 1) | (concealable ? 4 : 0) | (my_key << 8);
     // per-env tick counter and the unit's memory, requested before the scan
-    const bool decide = P.has && U.enabled && U.alive && (!pa.controlled || pa.controlled[P.k]);
+    const bool decide = P.has && U.enabled && U.alive && (!pa.controlled || at32(pa.controlled, P.k));
     const uint32_t tick = decide ? (uint32_t)a.st.t[P.e] : 0u;
     const int remembered = decide ? pa.mem.mem_valid[P.k] : 0;
     const float mx = decide ? pa.mem.mem_x[P.k] : 0.0f;

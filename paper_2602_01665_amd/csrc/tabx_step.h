@@ -46,15 +46,15 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     const float dt = a.p.dt;
     const bool has = P.has;
     const int alive0 = has ? U.alive : 0;
-    const int act = forced >= 0 ? forced : (has ? (int)a.actions[P.k] : 0);
+    const int act = forced >= 0 ? forced : (has ? (int)at32(a.actions, P.k) : 0);
     // per-env scalars, requested early: they are needed only after three LDS exchanges
-    const int t_new = has ? a.st.t[P.e] + 1 : 0;
-    const float phi_prev = has ? a.st.phi_prev[P.e] : 0.0f;
+    const int t_new = has ? at32(a.st.t, (size_t)P.e) + 1 : 0;
+    const float phi_prev = has ? at32(a.st.phi_prev, (size_t)P.e) : 0.0f;
     // ... and the running episode metrics, if kept: loaded where they are used, at the end of the
     // stage, they would queue behind the observation stores of the other wavefronts
     const bool want_kills = a.st.kill_run != nullptr;
-    const int kills_run = (want_kills && has) ? a.st.kill_run[P.e] : 0;
-    const float ret_run = (a.st.ret_run && has) ? a.st.ret_run[P.e] : 0.0f;
+    const int kills_run = (want_kills && has) ? at32(a.st.kill_run, (size_t)P.e) : 0;
+    const float ret_run = (a.st.ret_run && has) ? at32(a.st.ret_run, (size_t)P.e) : 0.0f;
     float bdmg = 0.0f;
     const bool writer = P.chunk == 0;      // (always: only a group's first wavefront steps)
 
@@ -121,7 +121,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         const size_t span = (size_t)a.groups_per_xcd * a.envs_per_block * N;   // units per XCD
         const size_t first = (size_t)(blockIdx.x & 7) * span;
         const size_t off = ((size_t)(blockIdx.x >> 3) * 64 + (size_t)(threadIdx.x & 63)) * 128;
-        if (off < span && first + off < (size_t)a.p.num_envs * N) C.warm = a.actions[first + off];
+        if (off < span && first + off < (size_t)a.p.num_envs * N) C.warm = at32(a.actions, first + off);
     }
 
     // stage 2a: movement sets next tick's velocity, rotation turns the heading now
