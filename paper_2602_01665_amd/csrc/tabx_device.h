@@ -44,7 +44,7 @@ struct KArgs {
     int       groups_per_xcd;      // ceil(num_groups / 8)
     int       twin;                // 2 or 4: that many wavefronts of a workgroup own the same env
                                    //    group and share its observers (chunk = wavefront index)
-    int       dyn_stride;          // twin: floats of dynamic LDS per wavefront
+    int       dyn_stride;          // floats of dynamic LDS per wavefront (when several share an env group)
     int       obs_chunks;          // workgroups that share the observers of one env group (>= 1)
     int       obs_per_chunk;       // observers per such workgroup (a multiple of rows_per_flush)
     float     inv_cell;            // 1 / cell_size, used only when that is exact (power of two)

@@ -344,7 +344,7 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     // ... and by the bidding area of scripted units that decide in the observe stage
     const size_t zdesc_even = (zdesc_floats + 1) & ~(size_t)1;
     const size_t script_floats = mode == MODE_SCRIPTED_STEP_OBSERVE ? sizeof(ScriptLds<WAVES>) / 4 : 0;
-    // (twin wavefronts: one such area each)
+    // (wavefronts sharing an env group: one such area each)
     a.dyn_stride = (int)((dyn_floats + zdesc_even + script_floats + 3) & ~(size_t)3);
     const size_t dyn_bytes = (size_t)a.dyn_stride * (a.twin ? a.twin : 1) * sizeof(float);
     const size_t step_bytes = zdesc_floats * sizeof(float);

@@ -411,7 +411,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
 
     if (SCRIPT) {
         lds_barrier<WAVES>();      // all bids are in
-        // (twin wavefronts: the one that ran the unit's pass as observer holds its bids)
+        // (wavefronts sharing an env group: the one that ran the unit's pass as observer holds its bids)
         const bool decides = (sh.seer[P.l] & 0x20) != 0 && P.u >= i_begin && P.u < i_end;
         if (decides) {
             const unsigned long long tk = script->tkey[P.l];

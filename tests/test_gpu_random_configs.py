@@ -1,6 +1,6 @@
 """Seeded random configurations: unit counts, batch sizes, terrain kinds, zone slots, optional
 stages and launch forms drawn at random (all valid), each rolled out against the checker.
-The point is the combinations: twin wavefronts with a level bank and elliptical zones, the
+The point is the combinations: several wavefronts per env group with a level bank and elliptical zones, the
 scripted tick with collisions and strikes on everybody, ragged counts with each of them."""
 import sys
 
