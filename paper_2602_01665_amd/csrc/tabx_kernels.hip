@@ -527,7 +527,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
             }
         }
     }
-    a.copy_passes = (G * R * cpr + 64 * waves - 1) / (64 * waves);
+    a.copy_passes = waves == 1 ? (G * R * cpr + 63) / 64 : ((cpr + 1) / 2 + 63) / 64;
     if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
     if (waves == 1) launch_mode<1>(mode, a, s);
     else launch_mode<2>(mode, a, s);

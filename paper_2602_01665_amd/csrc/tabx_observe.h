@@ -164,7 +164,23 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     // ---- store passes: chunk t = p * LANES + l of the staged rows -> (row slot, chunk in row)
     unsigned dst_off[kMaxPasses];
     int valid[kMaxPasses];
-    {
+    // two-wave workgroups (one env, one row per flush): each wavefront streams one contiguous half
+    // of the row, 64 chunks per pass
+    const int half_row = (CPR + 1) >> 1;
+    const int first_chunk = WAVES == 2 ? wv * half_row + lane : P.l;
+    if (WAVES == 2) {
+        const bool whole = (D & 3) == 0;
+        const int end = wv == 0 ? half_row : CPR;
+        int q = first_chunk;
+#pragma unroll
+        for (int p = 0; p < kMaxPasses; ++p) {
+            const int left = D - 4 * q;
+            const int vm = (whole || left >= 4) ? 15 : ((1 << (left > 0 ? left : 0)) - 1);
+            valid[p] = (q < end && envs_here > 0) ? vm : 0;
+            dst_off[p] = (unsigned)(4 * q);
+            q += 64;
+        }
+    } else {
         const int RC = R * CPR;                    // chunks per env slot and flush
         const bool whole = (D & 3) == 0;           // no row ends inside a chunk (always so if R > 1)
         int tg = 0;                                // env slot of chunk t
@@ -345,10 +361,10 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
         const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
         float *row = out + i0 * D;
-        // chunk t = p * LANES + lane of the staged rows sits at staged_chunk(t): LANES is a
-        // multiple of 16, so the passes are a constant stride apart
-        const float4 *src = stage + staged_chunk((buf >> 2) + P.l);
-        constexpr int PASS_STRIDE = LANES + LANES / 16;
+        // the lane's chunk of pass p is 64 p chunks after its first one; staged_chunk() of a
+        // multiple of 16 is linear, so the passes are a constant stride apart in LDS
+        const float4 *src = stage + staged_chunk((buf >> 2) + first_chunk);
+        constexpr int PASS_STRIDE = 64 + 64 / 16;     // 64 chunks further, with their spare chunks
         if (D == Dp) {
             // every chunk is whole: fetch all passes from LDS first, then issue the stores
             float4 v[kMaxPasses];
