@@ -10,7 +10,8 @@
  *
  * Conventions
  *  - E = num_envs, N = num_units per env (allies first or in any order; `team`
- *    says which), D = tabx_obs_dim().
+ *    says which), D = tabx_obs_dim().  E * N (and num_levels * N) may not exceed 2^30:
+ *    TABX_ERR_SHAPE otherwise.
  *  - Every pointer inside TabxScenario / TabxState and every array argument is a
  *    DEVICE pointer into memory owned by the caller.  The library allocates and
  *    frees nothing and keeps no global state; it borrows the pointers until the

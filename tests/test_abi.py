@@ -52,6 +52,10 @@ def test_obs_dim_and_shape_errors(B):
                 dict(num_envs=-1), dict(grid_w=4), dict(max_steps=0), dict(zone_shapes=2),
                 dict(zone_shapes=1, max_zones=0), dict(zone_shapes=1, grid_w=4, grid_h=4)):
         assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -2, bad
+    # per-unit arrays hold at most 2^30 elements (the kernels address them with 32-bit offsets)
+    assert lib.tabx_obs_dim(C.byref(_params(B, num_envs=(1 << 30) // 20, num_units=20))) > 0
+    assert lib.tabx_obs_dim(C.byref(_params(B, num_envs=(1 << 30) // 20 + 1, num_units=20))) == -2
+    assert lib.tabx_obs_dim(C.byref(_params(B, num_levels=(1 << 30) // 20 + 1, num_units=20))) == -2
     for bad in (dict(dt=0.0), dict(cell_size=-1.0), dict(map_w=float("nan")),
                 dict(lava_dps=float("inf"))):
         assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -5, bad
