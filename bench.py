@@ -108,6 +108,9 @@ def main() -> int:
     ap.add_argument("--action-batches", type=int, default=None,
                     help="distinct pre-generated action batches (default: one per tick, at most "
                          "1 GiB of them); fewer are cycled")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="also time the tick with the batch split into this many parts, each "
+                         "launched on a stream of its own (reported as `pipelined`; 0 or 1: skip)")
     ap.add_argument("--policy-scan", action="store_true",
                     help="with --policy: the policy as a stage of its own in front of the step")
     args = ap.parse_args()
@@ -189,6 +192,41 @@ def main() -> int:
 
     assert torch.isfinite(env.obs).all()
     B_env = algorithmic_bytes_per_env(N, env.D, p["max_zones"])
+
+    # The same batch as parts on streams of their own: one part's launch fills the start and the
+    # end of another's (whole-batch throughput; the roofline above stays the single launch's).
+    pipelined = None
+    if args.streams > 1 and not args.separate and not args.policy_scan:
+        parts = env.parts(args.streams)
+        streams = [torch.cuda.Stream() for _ in parts]
+
+        def tick_parts(s):
+            a = acts[s % n_act]
+            for q, st in zip(parts, streams):
+                sl = slice(q.first_env, q.first_env + q.E)
+                if policy:
+                    q.scripted_step_observe(policy, scripted[sl], a[sl], st)
+                else:
+                    q.step_observe(a[sl], st)
+
+        torch.cuda.synchronize()
+        for s in range(min(args.warmup, 100)):
+            tick_parts(s)
+        best = None
+        for _ in range(max(1, min(args.reps, 3))):
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for s in range(args.steps):
+                tick_parts(args.warmup + s)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t1
+            best = dt if best is None else min(best, dt)
+        assert torch.isfinite(env.obs).all()
+        pipelined = {"streams": len(parts), "ms_per_step": best * 1e3 / args.steps,
+                     "value": E * N * args.steps / best, "unit": "agent-steps/s",
+                     "algorithmic_GBs": B_env * E * args.steps / best / 1e9,
+                     "frac_of_hbm_peak": B_env * E * args.steps / best / 1e9 / HBM_PEAK_GBS}
+
     achieved = B_env * E / (kernel_ms * 1e-3) / 1e9
     plain = not (args.collisions or args.separate or args.policy or args.global_state)
     traffic = MEASURED_TRAFFIC_BYTES.get(name) if plain else None     # measured for the fused tick
@@ -214,6 +252,8 @@ def main() -> int:
                      "kernel_ms_median": float(np.median(rep_ms)), "kernel_ms_min": min(rep_ms),
                      "repetitions": len(rep_ms)},
     }
+    if pipelined:
+        out["pipelined"] = pipelined
     if args.calibrate:
         src = torch.empty_like(env.obs)
         dst = torch.empty_like(env.obs)

@@ -111,6 +111,13 @@ typedef struct TabxParams {
      * a damaging strike is revealed). */
     int32_t  hurtbox_cone;
     int32_t  hit_all;
+    /* A batch may be processed as several calls on parts of it (every pointer advanced to the
+     * part's first env, num_envs = the part's size), for instance on two streams so that one
+     * part's launch fills the start and the end of the other's.  env_id_offset = index of the
+     * part's first env in the whole batch (>= 0): it is added to the env index in the keys of
+     * the random draws (level bank, heuristic policy), so the parts draw what the whole batch
+     * would.  Nothing else depends on it. */
+    int32_t  env_id_offset;
 } TabxParams;
 
 /* The scenario: unit specifications and zones (the unit and zone axes of the

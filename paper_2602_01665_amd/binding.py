@@ -45,7 +45,8 @@ class TabxParams(C.Structure):
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
                [("zone_shapes", C.c_int32), ("num_levels", C.c_int32), ("level_seed", C.c_uint32),
-                ("hurtbox_cone", C.c_int32), ("hit_all", C.c_int32)]
+                ("hurtbox_cone", C.c_int32), ("hit_all", C.c_int32),
+                ("env_id_offset", C.c_int32)]
 
 
 class TabxScenario(C.Structure):
@@ -260,6 +261,58 @@ class TabxEnv:
                          **{n: _cast(metrics[n], t) for n, t, _ in METRICS if n in metrics},
                          **{n: _cast(st[n], _I32) for n in LEVELS if n in st},
                          global_state=_cast(global_state, _F))
+
+    def parts(self, k: int):
+        """This batch as k consecutive parts that share its device tensors (views, nothing is
+        copied): each part is a TabxEnv of its own with `env_id_offset` set, so calls on the
+        parts compute exactly what the same calls on the whole batch would.  Launching the
+        parts on different streams lets one part's launch fill the start and the end of
+        another's.  Part boundaries are multiples of four envs (pointer alignment)."""
+        E, N = self.E, self.N
+        L = self.p.get("num_levels", 0)
+        self._policy_memory()
+        cuts = [min(E, (j * E // k + 3) // 4 * 4) for j in range(k)] + [E]
+        out = []
+        for start, stop in zip(cuts[:-1], cuts[1:]):
+            count = stop - start
+            if count <= 0:
+                continue
+
+            def unit(t):
+                return t[start * N:stop * N]
+
+            def env(t):
+                return None if t is None else t[start:stop]
+
+            v = object.__new__(TabxEnv)
+            v.device, v.N, v.D, v.words, v.E = self.device, N, self.D, self.words, count
+            v.p = dict(self.p, num_envs=count,
+                       env_id_offset=self.p.get("env_id_offset", 0) + start)
+            v.params = make_params(v.p)
+            names = list(SCENARIO_FLOAT) + ["team", "enabled"]
+            v.sc = {n: (self.sc[n] if L > 0 else unit(self.sc[n])) for n in names}
+            v.sc["terrain"] = self.sc["terrain"] if L > 0 else env(self.sc["terrain"])
+            v.sc["zone_desc"] = self.sc["zone_desc"] if L > 0 else env(self.sc["zone_desc"])
+            v.scenario = TabxScenario(
+                **{n: _cast(v.sc[n], _F) for n in SCENARIO_FLOAT},
+                team=_cast(v.sc["team"], _U8), enabled=_cast(v.sc["enabled"], _U8),
+                terrain=_cast(v.sc["terrain"], C.POINTER(C.c_int8)),
+                zone_desc=_cast(v.sc["zone_desc"], _F))
+            v.st = {n: (unit(t) if t.numel() == E * N else env(t)) for n, t in self.st.items()}
+            v.metrics = {n: env(t) for n, t in self.metrics.items()}
+            v.gs_live = env(self.gs_live)
+            v.state = self._state_struct(v.st, v.metrics, v.gs_live)
+            v.gstate = env(self.gstate)
+            v.mem = {n: unit(t) for n, t in self.mem.items()}
+            v.memory = TabxPolicyMemory(mem_x=_cast(v.mem["mem_x"], _F),
+                                        mem_y=_cast(v.mem["mem_y"], _F),
+                                        mem_valid=_cast(v.mem["mem_valid"], _U8),
+                                        next_action=_cast(v.mem["next_action"], _U8))
+            v.rewards, v.dones, v.obs = env(self.rewards), env(self.dones), env(self.obs)
+            v.vis, v.amask = env(self.vis), env(self.amask)
+            v.first_env = start
+            out.append(v)
+        return out
 
     def global_state(self, stream=None):
         if self.gstate is None:

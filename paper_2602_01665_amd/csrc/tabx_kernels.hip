@@ -270,6 +270,8 @@ static int check_params(const TabxParams *p)
     if (p->zone_shapes == 1 && (p->grid_w != 0 || p->max_zones < 1)) return TABX_ERR_SHAPE;
     if (p->num_levels < 0) return TABX_ERR_SHAPE;
     if ((p->hurtbox_cone | p->hit_all) & ~1) return TABX_ERR_SHAPE;
+    if (p->env_id_offset < 0 || (int64_t)p->env_id_offset + p->num_envs > INT32_MAX)
+        return TABX_ERR_SHAPE;
     if ((int64_t)p->num_levels * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     if ((int64_t)p->num_envs * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
     const float pos[] = {p->map_w, p->map_h, p->cell_size, p->dt};

@@ -63,7 +63,8 @@ __device__ __forceinline__ int policy_cascade(const KArgs &a, const Place &P, co
     const bool assassin = U.speed >= pa.pol.assassin_speed;
     const bool ranger = U.range >= pa.pol.ranger_range;
     int act;
-    const uint32_t coin = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 2u) & 1u;
+    const uint32_t env_id = (uint32_t)(P.e + a.p.env_id_offset);     // the env's index in the whole batch
+    const uint32_t coin = policy_hash(pa.pol.seed, env_id, (uint32_t)P.u, tick, 2u) & 1u;
     const int search_turn = coin ? TABX_ACT_ROT_LEFT : TABX_ACT_ROT_RIGHT;
     if (S.tgt >= 0) {
         const float4 T = S.T;
@@ -120,10 +121,10 @@ __device__ __forceinline__ int policy_cascade(const KArgs &a, const Place &P, co
         act = found ? move_along(bx, by) : search_turn;
     }
     // epsilon-greedy override
-    const uint32_t h0 = policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 0u);
+    const uint32_t h0 = policy_hash(pa.pol.seed, env_id, (uint32_t)P.u, tick, 0u);
     const float u0 = (float)(h0 >> 8) * (1.0f / 16777216.0f);
     if (u0 < pa.pol.epsilon)
-        act = (int)(policy_hash(pa.pol.seed, (uint32_t)P.e, (uint32_t)P.u, tick, 1u) & 7u);
+        act = (int)(policy_hash(pa.pol.seed, env_id, (uint32_t)P.u, tick, 1u) & 7u);
     out[P.k] = (uint8_t)act;
     return act;
 }

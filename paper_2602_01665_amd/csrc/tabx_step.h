@@ -24,7 +24,7 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
             row = (int)((uint32_t)a.st.next_level[P.e] % L);
             const uint32_t n = (uint32_t)a.st.level_draws[P.e];
             a.st.level[P.e] = row;
-            a.st.next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)P.e, 0u, n, 3u) % L);
+            a.st.next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)(P.e + a.p.env_id_offset), 0u, n, 3u) % L);
             a.st.level_draws[P.e] = (int)(n + 1u);
         }
         rows[P.g] = row;

@@ -144,7 +144,7 @@ def make_params(w: Workload, num_envs: int | None = None, **override) -> dict:
         reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"],
         collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"],
         zone_shapes=1 if w.terrain == "ellipses" else 0,
-        num_levels=0, level_seed=0, hurtbox_cone=0, hit_all=0,
+        num_levels=0, level_seed=0, hurtbox_cone=0, hit_all=0, env_id_offset=0,
     )
     p.update(override)
     return p
@@ -344,6 +344,7 @@ def custom_params(num_units, map_size=32.0, grid=0, max_zones=0, **override) -> 
              lava_dps=DEFAULTS["lava_dps"], swamp_mult=DEFAULTS["swamp_mult"],
              reveal_time=DEFAULTS["reveal_time"], boundary_frac=DEFAULTS["boundary_frac"],
              collision_alpha=DEFAULTS["collision_alpha"], collision_slop=DEFAULTS["collision_slop"],
-             zone_shapes=0, num_levels=0, level_seed=0, hurtbox_cone=0, hit_all=0)
+             zone_shapes=0, num_levels=0, level_seed=0, hurtbox_cone=0, hit_all=0,
+             env_id_offset=0)
     p.update(override)
     return p

@@ -56,6 +56,9 @@ def test_obs_dim_and_shape_errors(B):
     assert lib.tabx_obs_dim(C.byref(_params(B, num_envs=(1 << 30) // 20, num_units=20))) > 0
     assert lib.tabx_obs_dim(C.byref(_params(B, num_envs=(1 << 30) // 20 + 1, num_units=20))) == -2
     assert lib.tabx_obs_dim(C.byref(_params(B, num_levels=(1 << 30) // 20 + 1, num_units=20))) == -2
+    assert lib.tabx_obs_dim(C.byref(_params(B, env_id_offset=-1))) == -2
+    assert lib.tabx_obs_dim(C.byref(_params(B, env_id_offset=2 ** 31 - 5))) > 0
+    assert lib.tabx_obs_dim(C.byref(_params(B, env_id_offset=2 ** 31 - 4))) == -2
     for bad in (dict(dt=0.0), dict(cell_size=-1.0), dict(map_w=float("nan")),
                 dict(lava_dps=float("inf"))):
         assert lib.tabx_obs_dim(C.byref(_params(B, **bad))) == -5, bad
