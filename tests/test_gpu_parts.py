@@ -74,3 +74,47 @@ def test_parts_equal_the_whole_batch(name, E, k, levels):
         _same(whole.amask, split.amask, where + "action_mask")
         _same(whole.gs_live, split.gs_live, where + "global state")
     assert int(whole.metrics["ep_count"].sum()) >= E        # episodes ended, levels were drawn
+
+
+def test_a_part_matches_the_checker_under_its_original_env_indices():
+    """The second part of a batch (env_id_offset = its first env) against the CPU checker that
+    replays those envs with their original indices: level draws and scripted decisions agree."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    from tests.parity import compare_metrics, compare_outputs, compare_state
+    w = I.WORKLOADS["c3_16384env_10v10"]
+    E, N, L = 40, w.num_units, 5
+    p = I.make_params(w, E, max_steps=15, num_levels=L, level_seed=11)
+    sc = I.make_scenario(w, L)
+    batch = TabxEnv(p, sc, want_metrics=True, want_global_state=True)
+    part = batch.parts(2)[1]
+    rows = np.arange(part.first_env, part.first_env + part.E)
+    _say(f"[gpu] part [{rows[0]}, {rows[-1]}] of {E} envs against the checker")
+    ref = RefEnv(dict(p, num_envs=len(rows), env_ids=rows), sc)
+    ref.st["next_level"][:] = rows % L
+    ref.reset()
+    part.reset()
+    pol = I.policy("advanced", 2)
+    assert (sc["team"] == sc["team"][0]).all()
+    ctl = np.broadcast_to(sc["team"][0], (len(rows), N)).astype(np.uint8)
+    ctl_d = torch.from_numpy(np.ascontiguousarray(ctl)).to("cuda:0")
+    dones = 0
+    for s in range(60):
+        a = np.ascontiguousarray(I.actions_for_step(w.seed, s, E, N)[rows])
+        ad = torch.from_numpy(a).to("cuda:0")
+        part.policy_step_observe(pol, ctl_d, ad)
+        ref.policy_step(pol, ctl, a)
+        ref.observe()
+        torch.cuda.synchronize()
+        where = f"part tick {s}: "
+        assert np.array_equal(ad.cpu().numpy(), a), where + "actions"
+        compare_state(part.state_numpy(), ref.st, where)
+        compare_outputs(part, ref, where)
+        compare_metrics(part, ref, where)
+        assert np.array_equal(part.mem["mem_valid"].view(len(rows), N).cpu().numpy(),
+                              ref.mem["mem_valid"]), where + "mem_valid"
+        dones += int(ref.dones.sum())
+    assert dones > len(rows)
+    # the first part's envs were never touched
+    assert float(batch.obs[:part.first_env].abs().sum()) == 0.0
