@@ -298,6 +298,20 @@ int tabx_scripted_step_observe(const TabxParams *params, const TabxScenario *sce
                                uint8_t *actions, float *rewards, uint8_t *dones, float *obs,
                                uint64_t *vis_mask, uint8_t *action_mask, void *stream);
 
+/* Host-only helper for processing a batch in parts (see TabxParams.env_id_offset): fills
+ * part_params / part_scenario / part_state with the structs of the envs [first_env,
+ * first_env + count) of the given batch: num_envs = count, env_id_offset advanced, every
+ * per-unit pointer advanced by first_env * N elements, every per-env pointer by first_env,
+ * terrain and zone_desc by first_env rows (scenario arrays are left alone when they are a bank
+ * of levels); NULL pointers stay NULL.  The caller advances the other arrays the same way:
+ * actions, rewards, action_mask, controlled and the policy memory by first_env * N, dones by
+ * first_env, obs by first_env * N * D floats, vis_mask by first_env * N * ceil(N/64) words.
+ * obs and vis_mask must stay 16-byte aligned: choose first_env accordingly (a multiple of 4
+ * always does).  TABX_ERR_SHAPE if the range does not lie inside the batch. */
+int tabx_part(const TabxParams *params, const TabxScenario *scenario, const TabxState *state,
+              int32_t first_env, int32_t count, TabxParams *part_params,
+              TabxScenario *part_scenario, TabxState *part_state);
+
 const char *tabx_strerror(int code);
 
 #ifdef __cplusplus

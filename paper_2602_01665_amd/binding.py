@@ -25,7 +25,7 @@ STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
 
 EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
            "tabx_step_observe", "tabx_global_state", "tabx_heuristic_actions",
-           "tabx_policy_step_observe", "tabx_scripted_step_observe", "tabx_strerror")
+           "tabx_policy_step_observe", "tabx_scripted_step_observe", "tabx_part", "tabx_strerror")
 
 _I8 = C.POINTER(C.c_int8)
 _I32 = C.POINTER(C.c_int32)
@@ -126,6 +126,15 @@ def tabx_obs_dim(params: TabxParams) -> int:
     if d < 0:
         _check(d, "tabx_obs_dim")
     return d
+
+
+def tabx_part(params: TabxParams, scenario: TabxScenario, state: TabxState, first_env: int,
+              count: int):
+    """The structs of the envs [first_env, first_env + count) of a batch."""
+    pp, psc, pst = TabxParams(), TabxScenario(), TabxState()
+    _check(_lib.tabx_part(C.byref(params), C.byref(scenario), C.byref(state), int(first_env),
+                          int(count), C.byref(pp), C.byref(psc), C.byref(pst)), "tabx_part")
+    return pp, psc, pst
 
 
 def tabx_num_actions() -> int:
@@ -288,20 +297,15 @@ class TabxEnv:
             v.device, v.N, v.D, v.words, v.E = self.device, N, self.D, self.words, count
             v.p = dict(self.p, num_envs=count,
                        env_id_offset=self.p.get("env_id_offset", 0) + start)
-            v.params = make_params(v.p)
+            v.params, v.scenario, v.state = tabx_part(self.params, self.scenario, self.state,
+                                                      start, count)
             names = list(SCENARIO_FLOAT) + ["team", "enabled"]
             v.sc = {n: (self.sc[n] if L > 0 else unit(self.sc[n])) for n in names}
             v.sc["terrain"] = self.sc["terrain"] if L > 0 else env(self.sc["terrain"])
             v.sc["zone_desc"] = self.sc["zone_desc"] if L > 0 else env(self.sc["zone_desc"])
-            v.scenario = TabxScenario(
-                **{n: _cast(v.sc[n], _F) for n in SCENARIO_FLOAT},
-                team=_cast(v.sc["team"], _U8), enabled=_cast(v.sc["enabled"], _U8),
-                terrain=_cast(v.sc["terrain"], C.POINTER(C.c_int8)),
-                zone_desc=_cast(v.sc["zone_desc"], _F))
             v.st = {n: (unit(t) if t.numel() == E * N else env(t)) for n, t in self.st.items()}
             v.metrics = {n: env(t) for n, t in self.metrics.items()}
             v.gs_live = env(self.gs_live)
-            v.state = self._state_struct(v.st, v.metrics, v.gs_live)
             v.gstate = env(self.gstate)
             v.mem = {n: unit(t) for n, t in self.mem.items()}
             v.memory = TabxPolicyMemory(mem_x=_cast(v.mem["mem_x"], _F),

@@ -636,6 +636,54 @@ int tabx_scripted_step_observe(const TabxParams *p, const TabxScenario *sc, cons
                      actions);
 }
 
+int tabx_part(const TabxParams *p, const TabxScenario *sc, const TabxState *st, int32_t first_env,
+              int32_t count, TabxParams *pp, TabxScenario *psc, TabxState *pst)
+{
+    int rc = tabx::check_params(p);
+    if (rc) return rc;
+    if (!sc || !st || !pp || !psc || !pst) return TABX_ERR_NULL;
+    if (first_env < 0 || count < 0 || (int64_t)first_env + count > p->num_envs) return TABX_ERR_SHAPE;
+    const size_t N = (size_t)p->num_units;
+    const size_t e0 = (size_t)first_env, u0 = e0 * N;
+    *pp = *p;
+    pp->num_envs = count;
+    pp->env_id_offset = p->env_id_offset + first_env;
+    *psc = *sc;
+    if (p->num_levels == 0) {          // one scenario row per env: the part starts at its own
+        const float **f[] = {&psc->init_x, &psc->init_y, &psc->init_theta, &psc->hmax, &psc->radius,
+                             &psc->mass, &psc->speed, &psc->dmg, &psc->range, &psc->cooldown,
+                             &psc->sight_angle, &psc->sight_cos_half, &psc->sight_range,
+                             &psc->hurt_halfwidth};
+        for (const float **q : f)
+            if (*q) *q += u0;
+        if (psc->team) psc->team += u0;
+        if (psc->enabled) psc->enabled += u0;
+        if (psc->terrain) psc->terrain += e0 * (size_t)p->grid_h * (size_t)p->grid_w;
+        if (psc->zone_desc) psc->zone_desc += e0 * 6 * (size_t)p->max_zones;
+    }
+    *pst = *st;
+    float **uf[] = {&pst->x, &pst->y, &pst->vx, &pst->vy, &pst->theta, &pst->hp, &pst->cd,
+                    &pst->reveal, &pst->cur_speed};
+    for (float **q : uf)
+        if (*q) *q += u0;
+    if (pst->alive) pst->alive += u0;
+    if (pst->t) pst->t += e0;
+    if (pst->phi_prev) pst->phi_prev += e0;
+    if (pst->ret_run) pst->ret_run += e0;
+    if (pst->kill_run) pst->kill_run += e0;
+    if (pst->ep_count) pst->ep_count += e0;
+    if (pst->ep_len) pst->ep_len += e0;
+    if (pst->ep_return) pst->ep_return += e0;
+    if (pst->ep_win) pst->ep_win += e0;
+    if (pst->ep_first_kill) pst->ep_first_kill += e0;
+    if (pst->level) pst->level += e0;
+    if (pst->next_level) pst->next_level += e0;
+    if (pst->level_draws) pst->level_draws += e0;
+    if (pst->global_state)
+        pst->global_state += e0 * (16 * N + 6 * (size_t)p->max_zones);
+    return TABX_OK;
+}
+
 const char *tabx_strerror(int code)
 {
     switch (code) {

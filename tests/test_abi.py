@@ -130,3 +130,51 @@ def test_policy_level_and_variant_arguments_are_validated(B):
     assert lib.tabx_reset(C.byref(pl), C.byref(sc), C.byref(st), None, None) == -1
     st.next_level = C.cast(C.c_void_p(fake + 1), B._I32)
     assert lib.tabx_reset(C.byref(pl), C.byref(sc), C.byref(st), None, None) == -3
+
+
+def test_part_structs_advance_every_pointer(B):
+    """tabx_part is host arithmetic: per-unit pointers advance by first_env * N elements, per-env
+    pointers by first_env, terrain / zone slots by first_env rows, NULL stays NULL, a bank of
+    levels is left alone, env_id_offset accumulates."""
+    lib = B._lib
+    N, Z, gw, gh = 20, 8, 6, 5
+    p = _params(B, num_envs=64, num_units=N, max_zones=Z, grid_w=gw, grid_h=gh, env_id_offset=7)
+    base = 1 << 20
+
+    def fake(struct):
+        out = struct()
+        for k, (name, typ) in enumerate(struct._fields_):
+            setattr(out, name, C.cast(C.c_void_p(base * (k + 1)), typ))
+        return out
+
+    def addr(struct_obj, name):
+        return C.cast(getattr(struct_obj, name), C.c_void_p).value or 0
+
+    sc, st = fake(B.TabxScenario), fake(B.TabxState)
+    st.kill_run = C.cast(None, type(st.kill_run))
+    pp, psc, pst = B.tabx_part(p, sc, st, 12, 16)
+    assert (pp.num_envs, pp.env_id_offset, pp.num_units) == (16, 19, N)
+    for name, typ in B.TabxScenario._fields_:
+        step = {"team": 1, "enabled": 1, "terrain": gw * gh, "zone_desc": 4 * 6 * Z}.get(name, 4 * N)
+        if name in ("terrain", "zone_desc"):
+            assert addr(psc, name) - addr(sc, name) == 12 * step, name
+        else:
+            assert addr(psc, name) - addr(sc, name) == 12 * N * (step // N if step >= N else step), name
+    unit4 = {"x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed"}
+    size = {"alive": N, "t": 4, "phi_prev": 4, "ret_run": 4, "ep_count": 4, "ep_len": 4,
+            "ep_return": 4, "ep_win": 1, "ep_first_kill": 1, "level": 4, "next_level": 4,
+            "level_draws": 4, "global_state": 4 * (16 * N + 6 * Z)}
+    for name, typ in B.TabxState._fields_:
+        if name == "kill_run":
+            assert addr(pst, name) == 0
+            continue
+        want = 12 * (4 * N if name in unit4 else size[name])
+        assert addr(pst, name) - addr(st, name) == want, name
+    # a bank of levels: the scenario arrays are shared by all parts
+    pl = _params(B, num_envs=64, num_units=N, max_zones=Z, grid_w=gw, grid_h=gh, num_levels=3)
+    _, psc, _ = B.tabx_part(pl, sc, st, 12, 16)
+    for name, _ in B.TabxScenario._fields_:
+        assert addr(psc, name) == addr(sc, name), name
+    for first, count in ((-1, 4), (60, 5), (0, -1)):
+        with pytest.raises(B.TabxError):
+            B.tabx_part(p, sc, st, first, count)
