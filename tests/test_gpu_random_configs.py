@@ -38,7 +38,7 @@ def _draw_config(seed):
     return w, E, over, levels, form
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_configuration(seed):
     import torch
     from oracle.ref import RefEnv
