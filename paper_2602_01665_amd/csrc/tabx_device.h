@@ -225,6 +225,16 @@ __device__ __forceinline__ float zone_magnitude(const KArgs &a, float own_effect
     return a.p.zone_shapes == 1 ? own_effect : global_value;
 }
 
+// The launch arguments where the kernel-argument segment holds them.  The kernels have more
+// argument words than scalar registers; fields that are needed once, late or rarely (episode
+// metrics, level bank, masks written at the end) are read through this pointer at the point of
+// use instead of sitting in registers, or spilled, from the first instruction on.
+typedef const __attribute__((address_space(4))) KArgs *LateArgs;
+__device__ __forceinline__ LateArgs late_args()
+{
+    return (LateArgs)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
 // Element k of a per-unit array (at most 2^30 elements: its byte offset fits 32 bits, so the
 // access is "uniform base + 32-bit lane offset" and needs no 64-bit address arithmetic per lane).
 template <class T>

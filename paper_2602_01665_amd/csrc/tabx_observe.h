@@ -98,6 +98,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int CPR = Dp >> 2;                     // 16-byte chunks per staged row
     const int zlen = 6 * a.p.max_zones;
     const bool has = P.has;
+    const bool want_vis = late_args()->vis_mask != nullptr;
+    const bool want_gs = late_args()->st.global_state != nullptr;
     const int lane = P.l & 63;
     const int wv = P.l >> 6;
     const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
@@ -141,8 +143,9 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         }
         sh.seer[P.l] = alive | (U.team << 1) | (U.dmg < 0.0f ? 4 : 0) | (enabled ? 8 : 0) | role |
                        (key << 8);
-        if (has && a.action_mask && P.chunk == 0)
-            a.action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
+        uint8_t *const action_mask = late_args()->action_mask;
+        if (has && action_mask && P.chunk == 0)
+            action_mask[P.k] = (alive && U.cd <= 0.0f) ? 1 : 0;
     }
     // what differs between a unit's block in its own row and in another unit's row
     const int own_mask = enabled ? -1 : 0;
@@ -275,7 +278,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 }
             }
         }
-        if (a.vis_mask) {
+        if (want_vis) {
             // the ballot over the lanes is observer i's row; its own lane keeps it
             const uint64_t b = __ballot(seen);
             if (WAVES == 1) my_row = self ? b : my_row;
@@ -307,9 +310,9 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                                           __int_as_float(__float_as_int(c13) & m),
                                           __int_as_float(__float_as_int(c14) & m),
                                           __int_as_float(__float_as_int(c15) & m));
-            if (self && a.st.global_state) {
+            if (self && want_gs) {
                 // the own block with its absolute position is the unit's block of the global state
-                f4u *gs = reinterpret_cast<f4u *>(a.st.global_state + (size_t)P.e * D + 16 * P.u);
+                f4u *gs = reinterpret_cast<f4u *>(late_args()->st.global_state + (size_t)P.e * D + 16 * P.u);
                 gs[0] = f4u{q0.x, q0.y, q0.z, q0.w};
                 gs[1] = f4u{q1.x, q1.y, q1.z, q1.w};
                 gs[2] = f4u{q2.x, q2.y, q2.z, q2.w};
@@ -340,9 +343,9 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 zo[k] = __int_as_float(__float_as_int(zval[k] - shift) & en);
             }
             stage[staged_chunk((buf + zone_dst0) >> 2)] = make_float4(zo[0], zo[1], zo[2], zo[3]);
-            if (a.st.global_state && i == 0) {
+            if (want_gs && i == 0) {
                 // ... and the zone slots with absolute centres are its tail
-                float *gz = a.st.global_state + (size_t)(P.grp * G + zg) * D + 16 * N + 4 * zc;
+                float *gz = late_args()->st.global_state + (size_t)(P.grp * G + zg) * D + 16 * N + 4 * zc;
                 const int left = zlen - 4 * zc;
                 if (left >= 4) {
                     *reinterpret_cast<f4u *>(gz) = f4u{zval[0], zval[1], zval[2], zval[3]};
@@ -412,15 +415,16 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         if (WAVES == 1) lds_barrier<WAVES>();    // two waves alternate between two staging buffers
     }
 
-    if (a.vis_mask) {
+    if (want_vis) {
+        uint64_t *const vis_mask = late_args()->vis_mask;
         lds_barrier<WAVES>();
         if (has && P.u >= i_begin && P.u < i_end) {
             if (WAVES == 1) {
                 const uint64_t range = N >= 64 ? ~0ull : ((1ull << N) - 1ull);
-                a.vis_mask[P.k] = (my_row >> P.base) & range;
+                vis_mask[P.k] = (my_row >> P.base) & range;
             } else {
                 const int words = (N + 63) >> 6;
-                for (int w = 0; w < words; ++w) a.vis_mask[P.k * words + w] = sh.rowbits[P.u][w];
+                for (int w = 0; w < words; ++w) vis_mask[P.k * words + w] = sh.rowbits[P.u][w];
             }
         }
     }

@@ -20,12 +20,15 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
     if (P.has && P.u == 0 && P.chunk == 0) {
         int row = -1;
         if (take) {
+            const LateArgs late = late_args();
+            int32_t *const level = late->st.level, *const next_level = late->st.next_level;
+            int32_t *const level_draws = late->st.level_draws;
             const uint32_t L = (uint32_t)a.p.num_levels;
-            row = (int)((uint32_t)a.st.next_level[P.e] % L);
-            const uint32_t n = (uint32_t)a.st.level_draws[P.e];
-            a.st.level[P.e] = row;
-            a.st.next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)(P.e + a.p.env_id_offset), 0u, n, 3u) % L);
-            a.st.level_draws[P.e] = (int)(n + 1u);
+            row = (int)((uint32_t)next_level[P.e] % L);
+            const uint32_t n = (uint32_t)level_draws[P.e];
+            level[P.e] = row;
+            next_level[P.e] = (int)(policy_hash(a.p.level_seed, (uint32_t)(P.e + a.p.env_id_offset), 0u, n, 3u) % L);
+            level_draws[P.e] = (int)(n + 1u);
         }
         rows[P.g] = row;
     }
@@ -52,9 +55,12 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     const float phi_prev = has ? at32(a.st.phi_prev, (size_t)P.e) : 0.0f;
     // ... and the running episode metrics, if kept: loaded where they are used, at the end of the
     // stage, they would queue behind the observation stores of the other wavefronts
-    const bool want_kills = a.st.kill_run != nullptr;
-    const int kills_run = (want_kills && has) ? at32(a.st.kill_run, (size_t)P.e) : 0;
-    const float ret_run = (a.st.ret_run && has) ? at32(a.st.ret_run, (size_t)P.e) : 0.0f;
+    const LateArgs late = late_args();
+    int8_t *const kill_run_p = late->st.kill_run;
+    float *const ret_run_p = late->st.ret_run;
+    const bool want_kills = kill_run_p != nullptr;
+    const int kills_run = (want_kills && has) ? at32(kill_run_p, (size_t)P.e) : 0;
+    const float ret_run = (ret_run_p && has) ? at32(ret_run_p, (size_t)P.e) : 0.0f;
     float bdmg = 0.0f;
     const bool writer = P.chunk == 0;      // (always: only a group's first wavefront steps)
 
@@ -323,7 +329,8 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             if (a.zdesc_staged) lds_barrier<WAVES>();
         }
         if (done) {
-            if (a.pa.mem.mem_valid && writer) a.pa.mem.mem_valid[P.k] = 0;   // a new episode remembers nothing
+            uint8_t *const mem_valid = late->pa.mem.mem_valid;
+            if (mem_valid && writer) mem_valid[P.k] = 0;   // a new episode remembers nothing
             code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
@@ -353,19 +360,19 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         if (want_kills) {
             kills = kills_run;
             if (kills == 0) kills = (cnt[3] < before[1] ? 1 : 0) | (cnt[2] < before[0] ? 2 : 0);
-            a.st.kill_run[P.e] = (int8_t)(done ? 0 : kills);
+            late->st.kill_run[P.e] = (int8_t)(done ? 0 : kills);
         }
         float ret = 0.0f;
-        if (a.st.ret_run) {
+        if (late->st.ret_run) {
             ret = ret_run + r0;
-            a.st.ret_run[P.e] = done ? 0.0f : ret;
+            late->st.ret_run[P.e] = done ? 0.0f : ret;
         }
         if (done) {
-            if (a.st.ep_count) a.st.ep_count[P.e] += 1;
-            if (a.st.ep_len) a.st.ep_len[P.e] = t_new;
-            if (a.st.ep_return && a.st.ret_run) a.st.ep_return[P.e] = ret;
-            if (a.st.ep_win) a.st.ep_win[P.e] = (m0 > m1) ? 1 : 0;
-            if (a.st.ep_first_kill && want_kills) a.st.ep_first_kill[P.e] = (int8_t)kills;
+            if (late->st.ep_count) late->st.ep_count[P.e] += 1;
+            if (late->st.ep_len) late->st.ep_len[P.e] = t_new;
+            if (late->st.ep_return && late->st.ret_run) late->st.ep_return[P.e] = ret;
+            if (late->st.ep_win) late->st.ep_win[P.e] = (m0 > m1) ? 1 : 0;
+            if (late->st.ep_first_kill && want_kills) late->st.ep_first_kill[P.e] = (int8_t)kills;
         }
     }
     if (has && writer) store_state(a, P.k, U);
