@@ -430,6 +430,55 @@ def test_full_size_sampled_envs(name, steps, n_sample):
     assert torch.equal((-r[:, :1]).expand(E, N)[team], r[team])
 
 
+WHOLE = [
+    ("c2_4096env_5v5", 24),
+    ("c3_16384env_10v10", 12),
+    ("c4_65536env_5v5", 12),
+    ("c5_1024env_64v64", 4),
+]
+
+
+@pytest.mark.parametrize("name,ticks", WHOLE, ids=[c[0] for c in WHOLE])
+def test_full_size_every_env_first_ticks(name, ticks):
+    """The benchmark's launch (fused tick, full env count): the checker steps the WHOLE batch for
+    the first ticks after reset and every field of every env is compared, so that each workgroup
+    of the full-size grid (every XCD's first and last groups, the ragged last one) is checked,
+    not only the sampled envs of the full-length run above."""
+    import torch
+    from oracle.ref import RefEnv
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = I.WORKLOADS[name]
+    E, N = w.num_envs, w.num_units
+    _say(f"[gpu] full size, every env, {name}: E={E} N={N} ticks={ticks}")
+    p = I.make_params(w)
+    sc = I.make_scenario(w)
+    ref = RefEnv(p, sc)
+    gpu = TabxEnv(p, sc, want_metrics=True, want_global_state=True)
+    ref.reset()
+    gpu.reset()
+
+    def same(t, want):
+        # bit-identical on the device (the expected outcome); the tolerance comparison on the
+        # host, with its message, only if not
+        return torch.equal(t.reshape(-1), torch.from_numpy(want).to(t.device).view(t.dtype).reshape(-1))
+
+    for s in range(ticks):
+        a = I.actions_for_step(w.seed, s, E, N)
+        gpu.step_observe(torch.from_numpy(a).to("cuda:0"))
+        ref.step(a)
+        ref.observe()
+        where = f"{name} every env tick {s}: "
+        compare_state(gpu.state_numpy(), ref.st, where)
+        compare_metrics(gpu, ref, where)
+        quick = (same(gpu.obs, ref.obs) and same(gpu.rewards, ref.rewards) and
+                 same(gpu.dones, ref.dones) and same(gpu.vis, ref.vis.view(np.int64)) and
+                 same(gpu.amask, ref.amask))
+        if not quick:
+            compare_outputs(gpu, ref, where)
+        assert same(gpu.gs_live, ref.global_state()), where + "global state"
+        _say(f"[gpu]   tick {s} ok ({'bit-identical' if quick else 'within tolerance'})")
+
+
 def test_observation_tensor_beyond_two_giga_floats():
     """1.44 million 5v5 envs: the observation tensor has more than 2^31 floats (9.2 GB), so every
     row offset must be computed in 64 bits; sampled envs from both ends and from behind the 2^31
