@@ -178,3 +178,14 @@ def test_part_structs_advance_every_pointer(B):
     for first, count in ((-1, 4), (60, 5), (0, -1)):
         with pytest.raises(B.TabxError):
             B.tabx_part(p, sc, st, first, count)
+
+
+def test_plain_c_client_compiles_and_links():
+    """include/tabx.h is valid C11 and a C program links against the library with gcc alone
+    (the program itself needs a GPU: tests/test_gpu_c_client.py runs it)."""
+    import os
+    from oracle import ref
+    from tests import c_client
+    ref.build()
+    binary = c_client.build()
+    assert os.access(binary, os.X_OK)
