@@ -38,7 +38,8 @@ struct KArgs {
     int       copy_passes;         // ceil(G * R * row_pitch / 4 / lanes), <= kMaxPasses
     int       rows_per_flush;      // R: consecutive rows of an env staged before they are stored
     int       num_groups;          // workgroups that have envs to process
-    int       zdesc_offset;        // copy of the zone descriptors in dynamic LDS, floats
+    int       zdesc_offset;        // copy of the zone descriptors in dynamic LDS, floats (from the wavefront's
+                                   //    area; from the start if the workgroup keeps one copy, see the kernel)
     int       zdesc_staged;        // ... which exists for elliptical zones and for deciding units
     int       script_offset;       // scripted units deciding in the observe stage: their LDS, floats
     int       groups_per_xcd;      // ceil(num_groups / 8)

@@ -66,8 +66,11 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     // elliptical zones, deciding units: the descriptors of the workgroup's envs sit in LDS for
     // the zone lookups and the bush search
     const int zlen = 6 * a.p.max_zones;
-    float *zdesc = dyn_lds + a.zdesc_offset;
-    if (a.zdesc_staged) {
+    // (wavefronts that only write rows never look at them: then the workgroup keeps one copy,
+    // behind the wavefronts' areas, and only the first wavefront fills it)
+    constexpr bool ZSHARED = TWIN != 0 && !SCRIPT;
+    float *zdesc = (ZSHARED ? dyn_all : dyn_lds) + a.zdesc_offset;
+    if (a.zdesc_staged && (lead || !ZSHARED)) {
         const int G = a.envs_per_block;
         for (int q = P.l; q < G * zlen; q += 64 * WAVES) {
             const int g = q / zlen;
@@ -142,11 +145,11 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
                 P.row = row;
                 P.ks = (size_t)row * a.p.num_units + P.u;
                 load_spec(a, P.ks, U);
-                if (a.zdesc_staged)
+                if (a.zdesc_staged && !ZSHARED)
                     for (int q = P.u; q < zlen; q += a.p.num_units)
                         zd[q] = a.sc.zone_desc[(size_t)row * zlen + q];
             }
-            if (a.zdesc_staged) lds_barrier<1>();
+            if (a.zdesc_staged && !ZSHARED) lds_barrier<1>();
         }
         // the unit's health ratio, as the step stage leaves it (same operands, same rounding)
         C.ratio = (P.has && U.enabled) ? U.hp / U.hmax : 0.0f;
@@ -346,12 +349,17 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     // ... and by the bidding area of scripted units that decide in the observe stage
     const size_t zdesc_even = (zdesc_floats + 1) & ~(size_t)1;
     const size_t script_floats = mode == MODE_SCRIPTED_STEP_OBSERVE ? sizeof(ScriptLds<WAVES>) / 4 : 0;
-    // (wavefronts sharing an env group: one such area each)
-    a.dyn_stride = (int)((dyn_floats + zdesc_even + script_floats + 3) & ~(size_t)3);
-    const size_t dyn_bytes = (size_t)a.dyn_stride * (a.twin ? a.twin : 1) * sizeof(float);
+    // (wavefronts sharing an env group: one such area each; the zone descriptors only once, behind
+    // the areas, unless the wavefronts decide for scripted units and each look zones up: a
+    // workgroup of two wavefronts on c3 takes 25.3 KB, and six of them must fit a CU's 160 KB)
+    const int sharers = a.twin ? a.twin : 1;
+    const bool zshared = a.twin && mode != MODE_SCRIPTED_STEP_OBSERVE;   // the kernels' ZSHARED
+    a.dyn_stride = (int)((dyn_floats + (zshared ? 0 : zdesc_even) + script_floats + 3) & ~(size_t)3);
+    const size_t dyn_bytes = ((size_t)a.dyn_stride * sharers + (zshared ? zdesc_even : 0)) * sizeof(float);
     const size_t step_bytes = zdesc_floats * sizeof(float);
-    a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0 : (int)dyn_floats;
-    a.script_offset = a.zdesc_offset + (int)zdesc_even;
+    a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0
+                     : zshared ? a.dyn_stride * sharers : (int)dyn_floats;
+    a.script_offset = zshared ? (int)dyn_floats : a.zdesc_offset + (int)zdesc_even;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
@@ -508,7 +516,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         const int num_groups = (p->num_envs + G - 1) / G;
         const bool small_batch = num_groups <= 2048;             // under one residency round
         // eight or more flushes, and a short step stage
-        const bool long_chain = N >= 16 * R / 2 && p->zone_shapes == 0 && !(p->collision_alpha > 0.0f);
+        const bool long_chain = N >= 16 * R / 2 && !(p->collision_alpha > 0.0f);
         if (per < N && mode == MODE_OBSERVE) {
             a.obs_per_chunk = per;
             a.obs_chunks = (N + per - 1) / per;
