@@ -195,16 +195,24 @@ __device__ __forceinline__ int zone_at(const KArgs &a, const float *zd, int row,
 {
     if (a.p.zone_shapes == 1) {
         int code = 0;
-        for (int z = 0; z < a.p.max_zones; ++z) {
-            const float *d = zd + 6 * z;
-            const float kind = d[0];
-            const float dx = x - d[1];
-            const float dy = y - d[2];
-            const float hx2 = d[3] * d[3];
-            const float hy2 = d[4] * d[4];
-            const bool inside = (kind != 0.0f) && (((dx * dx) * hy2) + ((dy * dy) * hx2) <= hx2 * hy2);
-            code = inside ? (((int)kind & 3) | ((z + 1) << 2)) : code;
-            own_effect = inside ? d[5] : own_effect;
+        // four slots per round, their descriptors fetched together (a slot beyond the last one
+        // re-reads the last and is masked out), so that the fetch latency is paid once per round
+        const int Z = a.p.max_zones;
+        for (int z0 = 0; z0 < Z; z0 += 4) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int z = z0 + k;
+                const float *d = zd + 6 * (z < Z ? z : Z - 1);
+                const float kind = d[0];
+                const float dx = x - d[1];
+                const float dy = y - d[2];
+                const float hx2 = d[3] * d[3];
+                const float hy2 = d[4] * d[4];
+                const bool inside = (z < Z) && (kind != 0.0f) &&
+                                    (((dx * dx) * hy2) + ((dy * dy) * hx2) <= hx2 * hy2);
+                code = inside ? (((int)kind & 3) | ((z + 1) << 2)) : code;
+                own_effect = inside ? d[5] : own_effect;
+            }
         }
         return code;
     }

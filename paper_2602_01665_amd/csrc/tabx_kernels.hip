@@ -504,7 +504,7 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     //    them load the specifications meanwhile and then write their share of the rows.
     //    Measured: c3 107 -> 99.5 us, c2 15.8 -> 14.0 us, but c4 (10 observers, five flushes per
     //    wavefront, a full machine) 87 -> 102 us; with a longer step stage the wavefronts that
-    //    wait for it cost more than the shorter chains save: elliptical zones 107.3 -> 111.6 us,
+    //    wait for it cost more than the shorter chains save:
     //    body collisions 111.9 -> 114.0 us, the scripted c3 tick 117.0 -> 129.0 us; hence the
     //    conditions below.  Three or four wavefronts per group: 120 us and more on c3, but a
     //    gain from 32 units per env on (below).
