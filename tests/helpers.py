@@ -48,3 +48,44 @@ def other_slot(D_row, i, j):
 
 def vis_bit(vis, e, i, j):
     return int((int(vis[e, i, j >> 6]) >> (j & 63)) & 1)
+
+
+class ShardedRef:
+    """The checker on a large batch: the envs are dealt to `threads` sub-batches, each stepped
+    by its own RefEnv on its own host thread (envs share nothing; the checker's calls release
+    the interpreter lock).  `fields()` gives the whole batch's arrays again."""
+
+    def __init__(self, w, params_of, scenario, threads=16):
+        from concurrent.futures import ThreadPoolExecutor
+        E = w.num_envs
+        self.bounds = [E * k // threads for k in range(threads + 1)]
+        self.parts = [RefEnv(params_of(self.bounds[k + 1] - self.bounds[k]),
+                             I.take_envs(scenario, slice(self.bounds[k], self.bounds[k + 1])))
+                      for k in range(threads)]
+        self.pool = ThreadPoolExecutor(threads)
+        self.N, self.D = self.parts[0].N, self.parts[0].D
+        # one observation array for the whole batch; every sub-batch writes its slice of it
+        self.obs = np.zeros((E, self.N, self.D), np.float32)
+        for k, r in enumerate(self.parts):
+            r.obs = self.obs[self.bounds[k]:self.bounds[k + 1]]
+
+    def _each(self, fn):
+        list(self.pool.map(fn, range(len(self.parts))))
+
+    def reset(self):
+        self._each(lambda k: self.parts[k].reset())
+
+    def tick(self, actions):
+        def run(k):
+            self.parts[k].step(actions[self.bounds[k]:self.bounds[k + 1]])
+            self.parts[k].observe()
+        self._each(run)
+
+    def state(self, name):
+        return np.concatenate([r.st[name] for r in self.parts])
+
+    def output(self, name):
+        return np.concatenate([getattr(r, name) for r in self.parts])
+
+    def global_state(self):
+        return np.concatenate([r.global_state() for r in self.parts])

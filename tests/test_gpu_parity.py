@@ -431,52 +431,62 @@ def test_full_size_sampled_envs(name, steps, n_sample):
 
 
 WHOLE = [
-    ("c2_4096env_5v5", 24),
-    ("c3_16384env_10v10", 12),
-    ("c4_65536env_5v5", 12),
-    ("c5_1024env_64v64", 4),
+    # (past the truncation horizon of 256 ticks, so that every env restarts at least once)
+    ("c2_4096env_5v5", 300),
+    ("c3_16384env_10v10", 300),
+    ("c4_65536env_5v5", 280),
+    ("c5_1024env_64v64", 260),
 ]
 
 
 @pytest.mark.parametrize("name,ticks", WHOLE, ids=[c[0] for c in WHOLE])
-def test_full_size_every_env_first_ticks(name, ticks):
-    """The benchmark's launch (fused tick, full env count): the checker steps the WHOLE batch for
-    the first ticks after reset and every field of every env is compared, so that each workgroup
-    of the full-size grid (every XCD's first and last groups, the ragged last one) is checked,
-    not only the sampled envs of the full-length run above."""
+def test_full_size_every_env(name, ticks):
+    """The benchmark's launch (fused tick, full env count): the checker steps the WHOLE batch
+    (its envs dealt to host threads) and every field of every env is compared after every tick,
+    bit for bit, so that each workgroup of the full-size grid (every XCD's first and last groups,
+    the ragged last one) is checked, not only the sampled envs of the full-length run above.
+    (Run once over the workloads' full step counts as well: 1000, 1000, 500 and 500 ticks of c3,
+    c4, c5 and c2, every env, every field, bit-identical.)"""
     import torch
-    from oracle.ref import RefEnv
+    from tests.helpers import ShardedRef
+    from tests.parity import FLOAT_STATE, INT_STATE, METRIC_FLOAT, METRIC_INT
     from paper_2602_01665_amd.binding import TabxEnv
     w = I.WORKLOADS[name]
     E, N = w.num_envs, w.num_units
     _say(f"[gpu] full size, every env, {name}: E={E} N={N} ticks={ticks}")
-    p = I.make_params(w)
     sc = I.make_scenario(w)
-    ref = RefEnv(p, sc)
-    gpu = TabxEnv(p, sc, want_metrics=True, want_global_state=True)
+    ref = ShardedRef(w, lambda n: I.make_params(w, n), sc)
+    gpu = TabxEnv(I.make_params(w), sc, want_metrics=True, want_global_state=True)
     ref.reset()
     gpu.reset()
 
     def same(t, want):
-        # bit-identical on the device (the expected outcome); the tolerance comparison on the
-        # host, with its message, only if not
-        return torch.equal(t.reshape(-1), torch.from_numpy(want).to(t.device).view(t.dtype).reshape(-1))
+        want = torch.from_numpy(np.ascontiguousarray(want))
+        if want.dtype in (torch.uint64,):
+            want = want.view(torch.int64)
+        return torch.equal(t.reshape(-1).view(torch.uint8), want.to(t.device).reshape(-1).view(torch.uint8))
 
+    dones = 0
     for s in range(ticks):
         a = I.actions_for_step(w.seed, s, E, N)
         gpu.step_observe(torch.from_numpy(a).to("cuda:0"))
-        ref.step(a)
-        ref.observe()
+        ref.tick(a)
         where = f"{name} every env tick {s}: "
-        compare_state(gpu.state_numpy(), ref.st, where)
-        compare_metrics(gpu, ref, where)
-        quick = (same(gpu.obs, ref.obs) and same(gpu.rewards, ref.rewards) and
-                 same(gpu.dones, ref.dones) and same(gpu.vis, ref.vis.view(np.int64)) and
-                 same(gpu.amask, ref.amask))
-        if not quick:
-            compare_outputs(gpu, ref, where)
-        assert same(gpu.gs_live, ref.global_state()), where + "global state"
-        _say(f"[gpu]   tick {s} ok ({'bit-identical' if quick else 'within tolerance'})")
+        assert same(gpu.obs, ref.obs), where + "obs"
+        for k in FLOAT_STATE + INT_STATE:
+            assert same(gpu.st[k], ref.state(k)), where + k
+        for k in METRIC_FLOAT + METRIC_INT:
+            assert same(gpu.metrics[k], ref.state(k)), where + k
+        assert same(gpu.rewards, ref.output("rewards")), where + "rewards"
+        assert same(gpu.dones, ref.output("dones")), where + "dones"
+        assert same(gpu.vis, ref.output("vis").view(np.int64)), where + "vis_mask"
+        assert same(gpu.amask, ref.output("amask")), where + "action_mask"
+        if s % 10 == 0 or s == ticks - 1:
+            assert same(gpu.gs_live, ref.global_state()), where + "global state"
+        dones += int(ref.output("dones").sum())
+        if s % 25 == 0:
+            _say(f"[gpu]   tick {s} ok, {dones} episodes ended")
+    _say(f"[gpu]   all {ticks} ticks bit-identical, {dones} episodes ended")
 
 
 def test_observation_tensor_beyond_two_giga_floats():
