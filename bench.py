@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # copy kernel of known size); see profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/tabx_tick_<workload>.md: (WRITE_SIZE KiB x 1.0 + FETCH_SIZE KiB x 2.0) x 1024
-    "c3_16384env_10v10": int((487596.8 + 2.0 * 30633.1) * 1024),
+    "c3_16384env_10v10": int((487593.9 + 2.0 * 30643.8) * 1024),
     "c4_65536env_5v5": int((442496.7 + 2.0 * 27411.2) * 1024),
     "c5_1024env_64v64": int((1056009.0 + 2.0 * 9745.0) * 1024),
     "c2_4096env_5v5": int((27636.9 + 2.0 * 4070.6) * 1024),
