@@ -59,7 +59,10 @@ class ShardedRef:
         from concurrent.futures import ThreadPoolExecutor
         E = w.num_envs
         self.bounds = [E * k // threads for k in range(threads + 1)]
-        self.parts = [RefEnv(params_of(self.bounds[k + 1] - self.bounds[k]),
+        # (every sub-batch knows its envs' indices in the whole batch: the random draws of the
+        # heuristic policy are keyed by them)
+        self.parts = [RefEnv(dict(params_of(self.bounds[k + 1] - self.bounds[k]),
+                                  env_ids=np.arange(self.bounds[k], self.bounds[k + 1], dtype=np.int32)),
                              I.take_envs(scenario, slice(self.bounds[k], self.bounds[k + 1])))
                       for k in range(threads)]
         self.pool = ThreadPoolExecutor(threads)
@@ -80,6 +83,25 @@ class ShardedRef:
             self.parts[k].step(actions[self.bounds[k]:self.bounds[k + 1]])
             self.parts[k].observe()
         self._each(run)
+
+    def scripted_tick(self, policy, controlled, actions):
+        """Decide-then-step: the controlled units' entries of `actions` ([E, N], in place) are
+        chosen by the heuristic policy on the current state, then the tick runs.  Returns the
+        memory flags as they stand after the decisions."""
+        flags = [None] * len(self.parts)
+
+        def run(k):
+            lo, hi = self.bounds[k], self.bounds[k + 1]
+            r = self.parts[k]
+            part = np.ascontiguousarray(actions[lo:hi])
+            r.heuristic_actions(policy, controlled[lo:hi], part)
+            flags[k] = r.mem["mem_valid"].copy()
+            actions[lo:hi] = part
+            r.step(part)
+            r.mem["mem_valid"][r.dones.astype(bool)] = 0
+            r.observe()
+        self._each(run)
+        return np.concatenate(flags)
 
     def state(self, name):
         return np.concatenate([r.st[name] for r in self.parts])

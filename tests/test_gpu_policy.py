@@ -239,6 +239,57 @@ def test_full_size_scripted_tick_with_level_bank():
     assert torch.isfinite(gpu.obs).all()
 
 
+def test_full_size_scripted_tick_every_env():
+    """The launch `bench.py --policy medium` times, EVERY env of it: the checker (envs dealt to
+    host threads) decides and steps the whole batch, and the actions applied, every state field,
+    the outputs and the memory flags are compared bit for bit after every tick, past the
+    truncation horizon.  (One-off runs of the same comparison: c4 / expert 300 ticks, c5 /
+    novice 270, c3 with elliptical zones / advanced 300, all bit-identical.)"""
+    import torch
+    from paper_2602_01665_amd.binding import TabxEnv
+    from tests.helpers import ShardedRef
+    from tests.parity import FLOAT_STATE, INT_STATE
+    w = I.WORKLOADS["c3_16384env_10v10"]
+    E, N, ticks = w.num_envs, w.num_units, 280
+    _say(f"[gpu] full size scripted tick, every env: E={E} N={N} ticks={ticks}")
+    sc = I.make_scenario(w)
+    ref = ShardedRef(w, lambda n: I.make_params(w, n), sc)
+    gpu = TabxEnv(I.make_params(w), sc)
+    ref.reset()
+    gpu.reset()
+    team = np.ascontiguousarray(sc["team"], np.uint8).reshape(E, N)
+    ctl_d = torch.from_numpy(team).to("cuda:0")
+    pol = I.policy("medium", w.seed)
+    gpu.prime_scripted(pol, ctl_d)
+
+    def same(t, want):
+        want = torch.from_numpy(np.ascontiguousarray(want))
+        return torch.equal(t.reshape(-1).view(torch.uint8), want.to(t.device).reshape(-1).view(torch.uint8))
+
+    dones = 0
+    for s in range(ticks):
+        where = f"full size scripted, every env, tick {s}: "
+        a = I.actions_for_step(w.seed, s, E, N).copy()
+        ad = torch.from_numpy(a.copy()).to("cuda:0")
+        waiting_flags = gpu.mem["mem_valid"].clone()       # after the decisions for this tick
+        flags = ref.scripted_tick(pol, team, a)
+        gpu.scripted_step_observe(pol, ctl_d, ad)
+        assert same(waiting_flags, flags), where + "memory flags"
+        assert same(ad, a), where + "actions applied"
+        assert same(gpu.obs, ref.obs), where + "obs"
+        for k in FLOAT_STATE + INT_STATE:
+            assert same(gpu.st[k], ref.state(k)), where + k
+        assert same(gpu.rewards, ref.output("rewards")), where + "rewards"
+        assert same(gpu.dones, ref.output("dones")), where + "dones"
+        assert same(gpu.vis, ref.output("vis").view(np.int64)), where + "vis_mask"
+        assert same(gpu.amask, ref.output("amask")), where + "action_mask"
+        dones += int(ref.output("dones").sum())
+        if s % 50 == 0:
+            _say(f"[gpu]   tick {s} ok")
+    _say(f"[gpu]   all {ticks} ticks bit-identical, {dones} episodes ended")
+    assert dones >= E
+
+
 def _scripted_rollout(w, E, steps, tier, who, scenario=None, seed=5, **override):
     """tabx_scripted_step_observe (decisions taken inside the observe stage, applied by the next
     call) against the checker's decide-then-step sequence: actions, states, observations,
