@@ -271,9 +271,12 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
      * All pairs are evaluated on the positions after the kinematic update and each unit
      * adds its corrections in ascending partner index (Jacobi style), then is clipped to
      * the arena again.  Dead bodies collide like live ones; disabled placeholders do not
-     * exist.  The impulse part of the paper's response changes velocities only, and the
-     * action stage rewrites every velocity later in the same tick, so it has no effect
-     * under this kinematic reading and is not modelled. */
+     * exist.  A kinematic body (same passage: exempt from the response) is one whose mass is
+     * +infinity: it gives way to nobody, a body of finite mass gives way to it for the whole
+     * corrected depth, and two kinematic bodies leave each other alone.  The impulse part of
+     * the paper's response changes velocities only, and the action stage rewrites every
+     * velocity later in the same tick, so it has no effect under this kinematic reading and
+     * is not modelled. */
     if (P.collision_alpha > 0.0f) {
         std::vector<float> px(N), py(N), ax(N, 0.0f), ay(N, 0.0f);
         for (int u = 0; u < N; ++u) {
@@ -297,7 +300,12 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
                     nx = (i < j) ? 1.0f : -1.0f;
                     ny = 0.0f;
                 }
-                float share = S.mass[j] / (S.mass[i] + S.mass[j]);
+                const bool kinematic_i = std::isinf(S.mass[i]);
+                const bool kinematic_j = std::isinf(S.mass[j]);
+                float share;
+                if (kinematic_i) share = 0.0f;
+                else if (kinematic_j) share = 1.0f;
+                else share = S.mass[j] / (S.mass[i] + S.mass[j]);
                 float c = ((pen - P.collision_slop) * P.collision_alpha) * share;
                 ax[i] = ax[i] - (c * nx);
                 ay[i] = ay[i] - (c * ny);

@@ -527,6 +527,33 @@ def test_collision_is_mass_aware_and_ignores_liveness_and_teams():
     assert env.st["x"][0, 0] == 0.0 and env.st["hp"][0, 0] == 70.0
 
 
+def test_kinematic_bodies_are_exempt_from_the_correction():
+    """App. A "Collision detection and resolution": units with kinematic bodies are exempt
+    (encoded as infinite mass); their partners give way for the whole corrected depth."""
+    inf = float("inf")
+    sh = G["collision_kinematic_partner_shift"][0]
+    env = make_ref([unit("assassin", 0, 10.0, 10.0, mass=inf), unit("assassin", 1, 11.5, 10.0)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    assert env.st["x"][0, 0] == 10.0
+    assert env.st["x"][0, 1] == pytest.approx(11.5 + sh, abs=1e-6)
+    # the other way round
+    env = make_ref([unit("assassin", 0, 10.0, 10.0), unit("assassin", 1, 11.5, 10.0, mass=inf)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP))
+    assert env.st["x"][0, 1] == 11.5
+    assert env.st["x"][0, 0] == pytest.approx(10.0 - sh, abs=1e-6)
+    # two kinematic bodies leave each other alone; a third, ordinary one gives way to both
+    env = make_ref([unit("assassin", 0, 10.0, 10.0, mass=inf), unit("assassin", 1, 11.5, 10.0, mass=inf),
+                    unit("assassin", 1, 10.75, 11.0)], **COLL)
+    env.step(acts(A.ACT_NOOP, A.ACT_NOOP, A.ACT_NOOP))
+    assert list(env.st["x"][0, :2]) == [10.0, 11.5] and list(env.st["y"][0, :2]) == [10.0, 10.0]
+    assert np.isfinite(env.st["x"]).all() and np.isfinite(env.st["y"]).all()
+    # pushed straight up by symmetry: depth 2 - 1.25, each partner contributes its y-share
+    d = math.hypot(0.75, 1.0)
+    up = 2 * ((2.0 - d) - 0.01) * 0.8 * (1.0 / d)
+    assert env.st["x"][0, 2] == pytest.approx(10.75, abs=1e-6)
+    assert env.st["y"][0, 2] == pytest.approx(11.0 + up, abs=1e-5)
+
+
 def test_collision_keeps_the_centre_of_mass_and_matches_float64():
     """Random crowded env: with no clipping the mass-weighted mean position is unchanged, and
     every displacement agrees with a float64 evaluation of the same pair sum."""
