@@ -80,7 +80,9 @@ typedef struct TabxParams {
     /* Body collisions (App. A "Collision detection and resolution"): after the kinematic
      * update overlapping body circles are pushed apart: of the penetration depth beyond
      * collision_slop the fraction collision_alpha is corrected per tick, split by inverse
-     * mass (needs mass > 0), every unit summing its corrections over its partners in
+     * mass (needs mass > 0; mass = +infinity marks a kinematic body, which is exempt: it gives
+     * way to nobody and a finite partner gives way for the whole corrected depth), every unit
+     * summing its corrections over its partners in
      * ascending index on the pre-correction positions, then clipped to the arena.  Dead
      * bodies collide, disabled placeholders do not.  collision_alpha = 0 switches it off. */
     float   collision_alpha;

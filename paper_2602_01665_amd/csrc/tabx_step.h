@@ -98,7 +98,10 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             // coincident centres separate along x, the lower index to the left
             const float nx = apart ? dx / dist : (P.u < jj ? 1.0f : -1.0f);
             const float ny = apart ? dy / dist : 0.0f;
-            const float share = J.w / (U.mass + J.w);
+            // a kinematic body (infinite mass) gives way to nobody; a body of finite mass
+            // gives way to it for the whole corrected depth
+            const float inf = __builtin_inff();
+            const float share = U.mass == inf ? 0.0f : (J.w == inf ? 1.0f : J.w / (U.mass + J.w));
             const float c = ((pen - a.p.collision_slop) * a.p.collision_alpha) * share;
             const bool push = (pen > a.p.collision_slop) && (jj != P.u) && (J.w >= 0.0f);
             // subtracting a zero product leaves the finite sum unchanged

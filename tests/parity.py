@@ -11,7 +11,9 @@ def _cmp_float(name, got, want, where=""):
     got = np.asarray(got)
     want = np.asarray(want)
     assert got.shape == want.shape, (name, got.shape, want.shape)
-    bad = ~(np.abs(got.astype(np.float64) - want.astype(np.float64)) <= FLOAT_TOL)
+    # (equal values are equal, infinities included: a kinematic body's mass is +inf)
+    with np.errstate(invalid="ignore"):
+        bad = ~((got == want) | (np.abs(got.astype(np.float64) - want.astype(np.float64)) <= FLOAT_TOL))
     if bad.any():
         idx = np.argwhere(bad)[0]
         raise AssertionError(f"{where}{name}: {int(bad.sum())} floats differ by more than "

@@ -240,7 +240,8 @@ def test_rollout_with_elliptical_zones(team_size, zones, E, fused):
     assert dones > 0
 
 
-def test_collisions_in_a_crowd_of_mixed_bodies():
+@pytest.mark.parametrize("kinematic", [False, True], ids=["finite", "kinematic"])
+def test_collisions_in_a_crowd_of_mixed_bodies(kinematic):
     names = list(I.ROSTER)
     rng = np.random.default_rng(9)
     units = [dict(unit=names[k % 9], team=k % 2, x=float(rng.uniform(10, 22)),
@@ -254,8 +255,14 @@ def test_collisions_in_a_crowd_of_mixed_bodies():
     sc["init_y"] = (sc["init_y"] + rng.uniform(-3, 3, sc["init_y"].shape)).astype(np.float32)
     sc["init_x"][:, 3] = sc["init_x"][:, 2]          # coincident centres
     sc["init_y"][:, 3] = sc["init_y"][:, 2]
+    if kinematic:
+        # every fifth body is kinematic (infinite mass: exempt from the correction), among them
+        # one of the coincident pair and, in half of the envs, both
+        sc["mass"][:, ::5] = np.inf
+        sc["mass"][:, 2] = np.inf
+        sc["mass"][::2, 3] = np.inf
     w = I.Workload("crowd", E, 15, 32.0, 0, "none", 1.0, "iid", steps=80, seed=77)
-    _say("[gpu] collisions in a crowd of 30 mixed bodies")
+    _say(f"[gpu] collisions in a crowd of 30 mixed bodies, kinematic={kinematic}")
     inexact, dones = _rollout(w, E, 80, True, scenario=sc, max_steps=30, collision_alpha=0.5,
                               collision_slop=0.05)
     assert dones > 0
