@@ -314,6 +314,26 @@ int tabx_part(const TabxParams *params, const TabxScenario *scenario, const Tabx
               int32_t first_env, int32_t count, TabxParams *part_params,
               TabxScenario *part_scenario, TabxState *part_state);
 
+/* Host-only: how the library would lay a call out on the machine, without enqueuing anything
+ * (for occupancy checks and tuning: on gfx950 a CU keeps as many workgroups resident as its
+ * 160 KB of LDS and its registers allow, and the launches are sized against that).  `call` names
+ * the entry point; the policy calls count as deciding.  dynamic_lds_bytes is what the launch
+ * requests on top of the kernel's static LDS.  TABX_ERR_SHAPE for an unknown call. */
+enum TabxCall {
+    TABX_CALL_RESET = 0, TABX_CALL_STEP = 1, TABX_CALL_OBSERVE = 2, TABX_CALL_STEP_OBSERVE = 3,
+    TABX_CALL_HEURISTIC_ACTIONS = 4, TABX_CALL_POLICY_STEP_OBSERVE = 5,
+    TABX_CALL_SCRIPTED_STEP_OBSERVE = 6
+};
+typedef struct TabxLaunchInfo {
+    int32_t workgroups;              /* grid size                                             */
+    int32_t threads_per_workgroup;
+    int32_t envs_per_workgroup;      /* envs packed into a workgroup                          */
+    int32_t wavefronts_per_env_group;/* wavefronts that share those envs (1, 2 or 4)          */
+    int32_t rows_per_flush;          /* observation rows of an env staged before a flush      */
+    int32_t dynamic_lds_bytes;
+} TabxLaunchInfo;
+int tabx_launch_info(const TabxParams *params, int call, TabxLaunchInfo *info);
+
 const char *tabx_strerror(int code);
 
 #ifdef __cplusplus

@@ -25,7 +25,8 @@ STATE_FLOAT = ("x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed")
 
 EXPORTS = ("tabx_obs_dim", "tabx_num_actions", "tabx_reset", "tabx_step", "tabx_observe",
            "tabx_step_observe", "tabx_global_state", "tabx_heuristic_actions",
-           "tabx_policy_step_observe", "tabx_scripted_step_observe", "tabx_part", "tabx_strerror")
+           "tabx_policy_step_observe", "tabx_scripted_step_observe", "tabx_part", "tabx_launch_info",
+           "tabx_strerror")
 
 _I8 = C.POINTER(C.c_int8)
 _I32 = C.POINTER(C.c_int32)
@@ -135,6 +136,23 @@ def tabx_part(params: TabxParams, scenario: TabxScenario, state: TabxState, firs
     _check(_lib.tabx_part(C.byref(params), C.byref(scenario), C.byref(state), int(first_env),
                           int(count), C.byref(pp), C.byref(psc), C.byref(pst)), "tabx_part")
     return pp, psc, pst
+
+
+class TabxLaunchInfo(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("workgroups", "threads_per_workgroup", "envs_per_workgroup",
+                                          "wavefronts_per_env_group", "rows_per_flush",
+                                          "dynamic_lds_bytes")]
+
+
+CALLS = {"reset": 0, "step": 1, "observe": 2, "step_observe": 3, "heuristic_actions": 4,
+         "policy_step_observe": 5, "scripted_step_observe": 6}
+
+
+def tabx_launch_info(params: TabxParams, call: str) -> dict:
+    """How the library would lay the call out (host only, nothing is enqueued)."""
+    info = TabxLaunchInfo()
+    _check(_lib.tabx_launch_info(C.byref(params), CALLS[call], C.byref(info)), "tabx_launch_info")
+    return {n: getattr(info, n) for n, _ in TabxLaunchInfo._fields_}
 
 
 def tabx_num_actions() -> int:

@@ -328,11 +328,11 @@ static int check_state(const TabxParams *p, const TabxState *s)
     return TABX_OK;
 }
 
+// Dynamic LDS of a launch and where its parts lie (fills the offsets in `a`).
+struct LdsPlan { size_t dyn_bytes, step_bytes; };
 template <int WAVES>
-static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
+static LdsPlan plan_lds(Mode mode, KArgs &a)
 {
-    const dim3 grid((unsigned)(8 * a.groups_per_xcd * a.obs_chunks));
-    const dim3 block(64 * WAVES * (a.twin ? a.twin : 1));
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
     // buffers for a two-wave workgroup)
     const size_t rows_staged = WAVES == 1 ? (size_t)a.envs_per_block * a.rows_per_flush : 2;
@@ -360,6 +360,16 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     a.zdesc_offset = (mode == MODE_STEP || mode == MODE_POLICY) ? 0
                      : zshared ? a.dyn_stride * sharers : (int)dyn_floats;
     a.script_offset = zshared ? (int)dyn_floats : a.zdesc_offset + (int)zdesc_even;
+    return {dyn_bytes, step_bytes};
+}
+
+template <int WAVES>
+static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
+{
+    const dim3 grid((unsigned)(8 * a.groups_per_xcd * a.obs_chunks));
+    const dim3 block(64 * WAVES * (a.twin ? a.twin : 1));
+    const LdsPlan lds = plan_lds<WAVES>(mode, a);
+    const size_t dyn_bytes = lds.dyn_bytes, step_bytes = lds.step_bytes;
     switch (mode) {
     case MODE_RESET:
         hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
@@ -402,65 +412,11 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     }
 }
 
-static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const TabxState *st,
-               const uint8_t *actions, const uint8_t *env_mask, float *rewards,
-               uint8_t *dones, float *obs, uint64_t *vis_mask, uint8_t *action_mask,
-               void *stream, const TabxPolicy *policy = nullptr,
-               const TabxPolicyMemory *memory = nullptr, const uint8_t *controlled = nullptr,
-               uint8_t *actions_out = nullptr)
+// How a call is laid out on the machine: envs per workgroup, rows per flush, wavefronts per env
+// group, store passes (all written into `a`; needs a.obs_dim and a.p).  Returns the wavefronts
+// an env takes (1 or 2).
+static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
 {
-    int rc = check_params(p);
-    if (rc) return rc;
-    if (p->num_envs == 0) return TABX_OK;          // empty batch: nothing to validate or do
-    if ((rc = check_scenario(p, sc))) return rc;
-    if ((rc = check_state(p, st))) return rc;
-    const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE ||
-                          mode == MODE_SCRIPTED_STEP_OBSERVE;
-    const bool stepping = mode == MODE_STEP || mode == MODE_STEP_OBSERVE ||
-                          mode == MODE_POLICY_STEP_OBSERVE || mode == MODE_SCRIPTED_STEP_OBSERVE;
-    const bool observing = mode == MODE_OBSERVE || mode == MODE_STEP_OBSERVE ||
-                           mode == MODE_POLICY_STEP_OBSERVE || mode == MODE_SCRIPTED_STEP_OBSERVE;
-    if (deciding) {
-        if (!policy || !memory || !actions_out) return TABX_ERR_NULL;
-        if (!memory->mem_x || !memory->mem_y || !memory->mem_valid) return TABX_ERR_NULL;
-        if (!aligned(memory->mem_x, 4) || !aligned(memory->mem_y, 4)) return TABX_ERR_ALIGN;
-        if (mode == MODE_SCRIPTED_STEP_OBSERVE && !memory->next_action) return TABX_ERR_NULL;
-        const float fin[] = {policy->epsilon, policy->xi, policy->assassin_speed, policy->ranger_range};
-        for (float v : fin)
-            if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
-    }
-    if (stepping) {
-        if (!actions || !rewards || !dones) return TABX_ERR_NULL;
-        if (!aligned(rewards, 4)) return TABX_ERR_ALIGN;
-    }
-    if (observing) {
-        if (!obs) return TABX_ERR_NULL;
-        if (!aligned(obs, 16) || (vis_mask && !aligned(vis_mask, 16))) return TABX_ERR_ALIGN;
-    }
-    KArgs a;
-    a.p = *p;
-    a.sc = *sc;
-    a.st = *st;
-    a.actions = actions;
-    a.env_mask = env_mask;
-    a.rewards = rewards;
-    a.dones = dones;
-    a.obs = obs;
-    a.vis_mask = vis_mask;
-    a.action_mask = action_mask;
-    a.obs_dim = 16 * p->num_units + 6 * p->max_zones;
-    a.pa = {};
-    a.zdesc_staged = (p->zone_shapes == 1 || (deciding && p->max_zones > 0)) ? 1 : 0;
-    if (deciding) {
-        a.pa.pol = *policy;
-        a.pa.mem = *memory;
-        a.pa.controlled = controlled;
-        a.pa.actions_out = actions_out;
-        a.pa.next_action = memory->next_action;
-    }
-
-    hipStream_t s = (hipStream_t)stream;
-    (void)hipGetLastError();
     // N <= 64: one wavefront per workgroup with G whole envs packed into it; G is floor(64 / N)
     // unless the staged rows of G envs would need more than kMaxPasses store passes or more
     // zone chunks than lanes.  64 < N <= 128: two wavefronts per env.
@@ -538,6 +494,69 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
         }
     }
     a.copy_passes = waves == 1 ? (G * R * cpr + 63) / 64 : ((cpr + 1) / 2 + 63) / 64;
+    return waves;
+}
+
+static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const TabxState *st,
+               const uint8_t *actions, const uint8_t *env_mask, float *rewards,
+               uint8_t *dones, float *obs, uint64_t *vis_mask, uint8_t *action_mask,
+               void *stream, const TabxPolicy *policy = nullptr,
+               const TabxPolicyMemory *memory = nullptr, const uint8_t *controlled = nullptr,
+               uint8_t *actions_out = nullptr)
+{
+    int rc = check_params(p);
+    if (rc) return rc;
+    if (p->num_envs == 0) return TABX_OK;          // empty batch: nothing to validate or do
+    if ((rc = check_scenario(p, sc))) return rc;
+    if ((rc = check_state(p, st))) return rc;
+    const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE ||
+                          mode == MODE_SCRIPTED_STEP_OBSERVE;
+    const bool stepping = mode == MODE_STEP || mode == MODE_STEP_OBSERVE ||
+                          mode == MODE_POLICY_STEP_OBSERVE || mode == MODE_SCRIPTED_STEP_OBSERVE;
+    const bool observing = mode == MODE_OBSERVE || mode == MODE_STEP_OBSERVE ||
+                           mode == MODE_POLICY_STEP_OBSERVE || mode == MODE_SCRIPTED_STEP_OBSERVE;
+    if (deciding) {
+        if (!policy || !memory || !actions_out) return TABX_ERR_NULL;
+        if (!memory->mem_x || !memory->mem_y || !memory->mem_valid) return TABX_ERR_NULL;
+        if (!aligned(memory->mem_x, 4) || !aligned(memory->mem_y, 4)) return TABX_ERR_ALIGN;
+        if (mode == MODE_SCRIPTED_STEP_OBSERVE && !memory->next_action) return TABX_ERR_NULL;
+        const float fin[] = {policy->epsilon, policy->xi, policy->assassin_speed, policy->ranger_range};
+        for (float v : fin)
+            if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
+    }
+    if (stepping) {
+        if (!actions || !rewards || !dones) return TABX_ERR_NULL;
+        if (!aligned(rewards, 4)) return TABX_ERR_ALIGN;
+    }
+    if (observing) {
+        if (!obs) return TABX_ERR_NULL;
+        if (!aligned(obs, 16) || (vis_mask && !aligned(vis_mask, 16))) return TABX_ERR_ALIGN;
+    }
+    KArgs a;
+    a.p = *p;
+    a.sc = *sc;
+    a.st = *st;
+    a.actions = actions;
+    a.env_mask = env_mask;
+    a.rewards = rewards;
+    a.dones = dones;
+    a.obs = obs;
+    a.vis_mask = vis_mask;
+    a.action_mask = action_mask;
+    a.obs_dim = 16 * p->num_units + 6 * p->max_zones;
+    a.pa = {};
+    a.zdesc_staged = (p->zone_shapes == 1 || (deciding && p->max_zones > 0)) ? 1 : 0;
+    if (deciding) {
+        a.pa.pol = *policy;
+        a.pa.mem = *memory;
+        a.pa.controlled = controlled;
+        a.pa.actions_out = actions_out;
+        a.pa.next_action = memory->next_action;
+    }
+
+    hipStream_t s = (hipStream_t)stream;
+    (void)hipGetLastError();
+    const int waves = plan_shape(mode, p, a);
     if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
     if (waves == 1) launch_mode<1>(mode, a, s);
     else launch_mode<2>(mode, a, s);
@@ -689,6 +708,35 @@ int tabx_part(const TabxParams *p, const TabxScenario *sc, const TabxState *st, 
     if (pst->level_draws) pst->level_draws += e0;
     if (pst->global_state)
         pst->global_state += e0 * (16 * N + 6 * (size_t)p->max_zones);
+    return TABX_OK;
+}
+
+int tabx_launch_info(const TabxParams *p, int call, TabxLaunchInfo *info)
+{
+    using namespace tabx;
+    const int rc = check_params(p);
+    if (rc) return rc;
+    if (!info) return TABX_ERR_NULL;
+    if (call < TABX_CALL_RESET || call > TABX_CALL_SCRIPTED_STEP_OBSERVE) return TABX_ERR_SHAPE;
+    static const Mode modes[] = {MODE_RESET, MODE_STEP, MODE_OBSERVE, MODE_STEP_OBSERVE, MODE_POLICY,
+                                 MODE_POLICY_STEP_OBSERVE, MODE_SCRIPTED_STEP_OBSERVE};
+    const Mode mode = modes[call];
+    const bool deciding = mode == MODE_POLICY || mode == MODE_POLICY_STEP_OBSERVE ||
+                          mode == MODE_SCRIPTED_STEP_OBSERVE;
+    KArgs a = {};
+    a.p = *p;
+    a.obs_dim = 16 * p->num_units + 6 * p->max_zones;
+    a.zdesc_staged = (p->zone_shapes == 1 || (deciding && p->max_zones > 0)) ? 1 : 0;
+    const int waves = plan_shape(mode, p, a);
+    if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
+    const LdsPlan lds = waves == 1 ? plan_lds<1>(mode, a) : plan_lds<2>(mode, a);
+    const bool staged = mode != MODE_RESET && mode != MODE_STEP && mode != MODE_POLICY;
+    info->workgroups = 8 * a.groups_per_xcd * a.obs_chunks;
+    info->threads_per_workgroup = 64 * waves * (a.twin ? a.twin : 1);
+    info->envs_per_workgroup = a.envs_per_block;
+    info->wavefronts_per_env_group = waves * (a.twin ? a.twin : 1);
+    info->rows_per_flush = a.rows_per_flush;
+    info->dynamic_lds_bytes = mode == MODE_RESET ? 0 : (int32_t)(staged ? lds.dyn_bytes : lds.step_bytes);
     return TABX_OK;
 }
 

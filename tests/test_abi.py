@@ -189,3 +189,30 @@ def test_plain_c_client_compiles_and_links():
     ref.build()
     binary = c_client.build()
     assert os.access(binary, os.X_OK)
+
+
+def test_launch_info_reports_the_layout_without_a_gpu(B):
+    """tabx_launch_info is host-only: the shapes of the five workloads' fused ticks, and its errors."""
+    from paper_2602_01665_amd import inputs as I
+    want = {"c1_16env_3v3": (10, 2, 128), "c2_4096env_5v5": (6, 2, 128),
+            "c3_16384env_10v10": (3, 2, 128), "c4_65536env_5v5": (6, 1, 64),
+            "c5_1024env_64v64": (1, 2, 128)}
+    for name, (envs, waves, threads) in want.items():
+        w = I.WORKLOADS[name]
+        p = B.make_params(I.make_params(w))
+        info = B.tabx_launch_info(p, "step_observe")
+        assert (info["envs_per_workgroup"], info["wavefronts_per_env_group"],
+                info["threads_per_workgroup"]) == (envs, waves, threads), (name, info)
+        groups = -(-w.num_envs // envs)
+        assert groups <= info["workgroups"] < groups + 8          # rounded up to the eight XCDs
+        assert 0 < info["dynamic_lds_bytes"] <= 64 * 1024
+        assert B.tabx_launch_info(p, "reset")["dynamic_lds_bytes"] == 0
+        # a stand-alone observe splits an env group's observers over two workgroups (one-wave envs)
+        split = 2 if w.num_units <= 64 else 1
+        assert B.tabx_launch_info(p, "observe")["workgroups"] == split * info["workgroups"]
+    p = B.make_params(I.make_params(I.WORKLOADS["c1_16env_3v3"]))
+    info = B.TabxLaunchInfo()
+    import ctypes as C
+    assert B._lib.tabx_launch_info(C.byref(p), 7, C.byref(info)) == -2       # unknown call
+    assert B._lib.tabx_launch_info(C.byref(p), 3, None) == -1                # NULL
+    assert B._lib.tabx_launch_info(None, 3, C.byref(info)) == -1
