@@ -157,12 +157,12 @@ struct Shared {
                                   // (policy stage: alive | team<<1 | concealable<<2 | bush key<<8)
     uint64_t rowbits[WAVES == 1 ? 1 : L][WAVES];   // two-wave workgroups: ballots of "observer i sees lane"
     uint64_t ballots[WAVES][4];
-    int      rows[WAVES == 1 ? 64 : 1];   // level bank: the row an env slot has just switched to, or -1
 };
 
 // Several wavefronts of one workgroup may share an env group (fused tick): the first one runs
 // the step stage and alone touches the state; the others take the stepped units over through
-// LDS and each writes the rows of its share of the observers.  What they all see sits here.
+// LDS and each writes the rows of its share of the observers.  What they all see sits here
+// (one per workgroup, whether or not its wavefronts share a group).
 struct TwinShared {
     int rows[64];      // level bank: the row an env slot has just switched to, or -1
 };

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     const int half = TWIN ? (int)(threadIdx.x >> 6) : 0;
     Shared<WAVES> &sh = sh_all[half];
     float *dyn_lds = dyn_all + half * a.dyn_stride;
-    int *rows = TWIN ? twin.rows : sh.rows;     // TWIN: 0, or how many wavefronts share an env group
+    int *rows = twin.rows;                      // TWIN: 0, or how many wavefronts share an env group
     Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
@@ -171,11 +171,12 @@ template <int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
 {
     __shared__ Shared<WAVES> sh;
+    __shared__ int level_rows[64];      // level bank: the row an env slot has just switched to
     Place P = locate<WAVES>(a);
     const int N = a.p.num_units;
     const bool go = P.has && !(a.env_mask && a.env_mask[P.e] == 0);
     if (a.p.num_levels > 0) {
-        const int row = advance_level<WAVES>(a, sh, P, go, sh.rows);
+        const int row = advance_level<WAVES>(a, sh, P, go, level_rows);
         if (row >= 0) {
             P.row = row;
             P.ks = (size_t)row * N + P.u;
