@@ -132,7 +132,8 @@ typedef struct TabxScenario {
     const float *sight_cos_half;                   /* cos(sight_angle / 2)           */
     const float *sight_range;                      /* cone radius                    */
     const float *hurt_halfwidth;                   /* lateral half-width of hurtbox  */
-    const uint8_t *team;                           /* 0 = allies, 1 = adversaries    */
+    const uint8_t *team;                           /* 0 = allies, 1 = adversaries (must be 0 or 1:
+                                                      any other non-zero byte is read as 1) */
     const uint8_t *enabled;                        /* 0 = padding placeholder        */
     const int8_t  *terrain;    /* [E][grid_h][grid_w] cell codes, NULL iff no grid   */
     const float   *zone_desc;  /* [E][max_zones][6] = type, cx, cy, hx, hy, effect;

@@ -12,6 +12,13 @@
 namespace tabx {
 
 constexpr int kMaxPasses = 10;     // store passes that stream one set of staged rows
+#ifndef TABX_PAD_SHIFT
+#define TABX_PAD_SHIFT 4
+#endif
+#ifndef TABX_ROTATE
+#define TABX_ROTATE 0
+#endif
+constexpr int kPadShift = TABX_PAD_SHIFT;   // staged rows: one spare 16-byte chunk after every 2^kPadShift
 
 struct PolicyArgs {
     TabxPolicy       pol;
@@ -266,7 +273,7 @@ __device__ __forceinline__ void load_spec(const KArgs &a, size_t k, Unit &U)
     U.cos_half = at32(a.sc.sight_cos_half, k);
     U.sight_range = at32(a.sc.sight_range, k);
     U.hurt_hw = at32(a.sc.hurt_halfwidth, k);
-    U.team = at32(a.sc.team, k);
+    U.team = at32(a.sc.team, k) != 0;    // any non-zero byte means the adversaries
     U.enabled = at32(a.sc.enabled, k);
 }
 

@@ -138,6 +138,11 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         C.restarted = (flags & 2) != 0;
         restarted = __ballot(C.restarted) != 0ull;
         lds_barrier<1>();          // the records are read: the staging area may take rows now
+        if (SCRIPT && P.has && C.restarted) {
+            // a new episode remembers nothing: the wavefront that decides for a unit clears its flag
+            const int first = P.chunk * a.obs_per_chunk;
+            if (P.u >= first && P.u < first + a.obs_per_chunk) a.pa.mem.mem_valid[P.k] = 0;
+        }
         if (a.p.num_levels > 0 && restarted) {
             // envs that moved to another level: their specifications and elliptical zones
             const int row = (P.has && C.restarted) ? rows[P.g] : -1;
@@ -344,7 +349,7 @@ static LdsPlan plan_lds(Mode mode, KArgs &a)
     // (wavefronts that take over another one's step receive three 16-byte records per lane here)
     if (a.twin && dyn_floats < 3 * 64 * 4) dyn_floats = 3 * 64 * 4;
     // ... with one spare 16-byte chunk after every 16 (see staged_chunk)
-    dyn_floats = 4 * ((dyn_floats + 3) / 4 + (dyn_floats + 3) / 64 + 1);
+    dyn_floats = 4 * ((dyn_floats + 3) / 4 + (((dyn_floats + 3) / 4) >> kPadShift) + 1);
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
     const size_t zdesc_floats = a.zdesc_staged ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
     // ... and by the bidding area of scripted units that decide in the observe stage
@@ -364,8 +369,18 @@ static LdsPlan plan_lds(Mode mode, KArgs &a)
     return {dyn_bytes, step_bytes};
 }
 
+// Enqueues one kernel and returns the status of THIS launch (the runtime's sticky "last error"
+// is neither read nor cleared: an error the caller's own earlier work left pending stays theirs).
+template <class Kernel, class Arg0>
+static hipError_t enqueue(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                          Arg0 &a0)
+{
+    void *args[] = {(void *)&a0};
+    return hipLaunchKernel((const void *)kernel, grid, block, args, lds_bytes, stream);
+}
+
 template <int WAVES>
-static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
+static hipError_t launch_mode(Mode mode, KArgs a, hipStream_t stream)
 {
     const dim3 grid((unsigned)(8 * a.groups_per_xcd * a.obs_chunks));
     const dim3 block(64 * WAVES * (a.twin ? a.twin : 1));
@@ -373,44 +388,31 @@ static void launch_mode(Mode mode, KArgs a, hipStream_t stream)
     const size_t dyn_bytes = lds.dyn_bytes, step_bytes = lds.step_bytes;
     switch (mode) {
     case MODE_RESET:
-        hipLaunchKernelGGL((tabx_reset_kernel<WAVES>), grid, block, 0, stream, a);
-        break;
+        return enqueue(tabx_reset_kernel<WAVES>, grid, block, 0, stream, a);
     case MODE_STEP:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, false>), grid, block, step_bytes,
-                           stream, a);
-        break;
+        return enqueue(tabx_tick_kernel<WAVES, false, true, false>, grid, block, step_bytes, stream, a);
     case MODE_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, false, true>), grid, block, dyn_bytes,
-                           stream, a);
-        break;
+        return enqueue(tabx_tick_kernel<WAVES, false, false, true>, grid, block, dyn_bytes, stream, a);
     case MODE_STEP_OBSERVE:
         if (WAVES == 1 && a.twin > 2)
-            hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, false, 4>), grid, block,
-                               dyn_bytes, stream, a);
-        else if (WAVES == 1 && a.twin)
-            hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, false, 2>), grid, block,
-                               dyn_bytes, stream, a);
-        else
-            hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true>), grid, block, dyn_bytes,
-                               stream, a);
-        break;
+            return enqueue(tabx_tick_kernel<1, false, true, true, false, 4>, grid, block, dyn_bytes,
+                           stream, a);
+        if (WAVES == 1 && a.twin)
+            return enqueue(tabx_tick_kernel<1, false, true, true, false, 2>, grid, block, dyn_bytes,
+                           stream, a);
+        return enqueue(tabx_tick_kernel<WAVES, false, true, true>, grid, block, dyn_bytes, stream, a);
     case MODE_POLICY:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, false, false>), grid, block, step_bytes,
-                           stream, a);
-        break;
+        return enqueue(tabx_tick_kernel<WAVES, true, false, false>, grid, block, step_bytes, stream, a);
     case MODE_POLICY_STEP_OBSERVE:
-        hipLaunchKernelGGL((tabx_tick_kernel<WAVES, true, true, true>), grid, block, dyn_bytes,
-                           stream, a);
-        break;
+        return enqueue(tabx_tick_kernel<WAVES, true, true, true>, grid, block, dyn_bytes, stream, a);
     case MODE_SCRIPTED_STEP_OBSERVE:
         if (WAVES == 1 && a.twin)
-            hipLaunchKernelGGL((tabx_tick_kernel<1, false, true, true, true, 2>), grid, block,
-                               dyn_bytes, stream, a);
-        else
-            hipLaunchKernelGGL((tabx_tick_kernel<WAVES, false, true, true, true>), grid, block,
-                               dyn_bytes, stream, a);
-        break;
+            return enqueue(tabx_tick_kernel<1, false, true, true, true, 2>, grid, block, dyn_bytes,
+                           stream, a);
+        return enqueue(tabx_tick_kernel<WAVES, false, true, true, true>, grid, block, dyn_bytes,
+                       stream, a);
     }
+    return hipErrorInvalidValue;
 }
 
 // How a call is laid out on the machine: envs per workgroup, rows per flush, wavefronts per env
@@ -485,7 +487,7 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
             // 91.7 us at 0.45 GB of rows per tick; fewer than four flushes each costs more than
             // it saves: N = 16 with four, 92 -> 124 us)
             // (as long as four staging areas fit the 64 KB of LDS a workgroup may take)
-            const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) * 17 / 16 + 64;
+            const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) * ((1 << kPadShift) + 1) / (1 << kPadShift) + 64;
             const size_t lds4 = 4 * (staged + sizeof(Shared<1>)) + sizeof(TwinShared);
             if (mode == MODE_STEP_OBSERVE && N >= 16 * R && p->zone_shapes == 0 &&
                 lds4 <= 60 * 1024) {
@@ -556,12 +558,10 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
     }
 
     hipStream_t s = (hipStream_t)stream;
-    (void)hipGetLastError();
     const int waves = plan_shape(mode, p, a);
     if (a.copy_passes > kMaxPasses) return TABX_ERR_SHAPE;
-    if (waves == 1) launch_mode<1>(mode, a, s);
-    else launch_mode<2>(mode, a, s);
-    return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
+    const hipError_t err = waves == 1 ? launch_mode<1>(mode, a, s) : launch_mode<2>(mode, a, s);
+    return err == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
 }
 
 } // namespace tabx
@@ -629,10 +629,11 @@ int tabx_global_state(const TabxParams *p, const TabxScenario *sc, const TabxSta
     const size_t units = (size_t)p->num_envs * p->num_units;
     const size_t zones = (size_t)p->num_envs * 6 * p->max_zones;
     const size_t threads = units > zones ? units : zones;
-    (void)hipGetLastError();
-    hipLaunchKernelGGL(tabx::tabx_global_state_kernel, dim3((unsigned)((threads + 255) / 256)),
-                       dim3(256), 0, (hipStream_t)stream, a, out);
-    return hipGetLastError() == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
+    void *args[] = {(void *)&a, (void *)&out};
+    const hipError_t err = hipLaunchKernel((const void *)tabx::tabx_global_state_kernel,
+                                           dim3((unsigned)((threads + 255) / 256)), dim3(256), args,
+                                           0, (hipStream_t)stream);
+    return err == hipSuccess ? TABX_OK : TABX_ERR_LAUNCH;
 }
 
 int tabx_heuristic_actions(const TabxParams *p, const TabxScenario *sc, const TabxState *st,

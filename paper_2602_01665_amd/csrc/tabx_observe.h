@@ -64,7 +64,7 @@ __device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &
 }
 
 // Where 16-byte chunk c of the staged row images lives in LDS.
-__device__ __forceinline__ int staged_chunk(int c) { return c + (c >> 4); }
+__device__ __forceinline__ int staged_chunk(int c) { return c + (c >> kPadShift); }
 
 // LDS of the scripted units that decide their next action inside the observe stage: per
 // deciding unit the smallest bids for "target" and "nearest enemy" and the "something to
@@ -235,14 +235,18 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     // of an env group are spread over several short-lived workgroups
     const int i_begin = P.chunk * a.obs_per_chunk;
     const int i_end = (i_begin + a.obs_per_chunk < N) ? i_begin + a.obs_per_chunk : N;
-    for (int i0 = i_begin; i0 < i_end; i0 += R) {
+    const int flushes = (i_end - i_begin + R - 1) / R;
+    const bool rotate = TABX_ROTATE == 2 || (TABX_ROTATE == 1 && WAVES == 2);
+    const int rot = (rotate && flushes > 0) ? (int)(((unsigned)P.grp * 37u) % (unsigned)flushes) : 0;
+    for (int fl = 0; fl < flushes; ++fl) {
+    const int i0 = i_begin + R * (fl + rot < flushes ? fl + rot : fl + rot - flushes);
     for (int rr = 0; rr < R; ++rr) {
         const int i = i0 + rr;
         const int oi = P.base + i;
         const float4 A = sh.ob.pose[oi];
         const float4 B = sh.ob.reach[oi];
         const int fi = sh.seer[oi];
-        const int buf = (WAVES == 1) ? rr * Dp : (i & 1) * Dp;
+        const int buf = (WAVES == 1) ? rr * Dp : (fl & 1) * Dp;
         // offset of this unit from the observer; `dot` is its component along the heading
         const float dx = U.x - A.x;
         const float dy = U.y - A.y;
@@ -362,12 +366,12 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         lds_barrier<WAVES>();
 
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
-        const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
+        const int buf = (WAVES == 1) ? 0 : (fl & 1) * Dp;
         float *row = out + i0 * D;
         // the lane's chunk of pass p is 64 p chunks after its first one; staged_chunk() of a
         // multiple of 16 is linear, so the passes are a constant stride apart in LDS
         const float4 *src = stage + staged_chunk((buf >> 2) + first_chunk);
-        constexpr int PASS_STRIDE = 64 + 64 / 16;     // 64 chunks further, with their spare chunks
+        constexpr int PASS_STRIDE = 64 + (64 >> kPadShift);     // 64 chunks further, with their spare chunks
         if (D == Dp) {
             // every chunk is whole: fetch all passes from LDS first, then issue the stores
             float4 v[kMaxPasses];

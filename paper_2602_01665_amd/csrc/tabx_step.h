@@ -332,8 +332,11 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             if (a.zdesc_staged) lds_barrier<WAVES>();
         }
         if (done) {
+            // a new episode remembers nothing.  Where several wavefronts share the env group, the
+            // wavefront that later decides for the unit clears its flag itself (it may set it again
+            // at once, and two wavefronts' stores to one byte have no order between them)
             uint8_t *const mem_valid = late->pa.mem.mem_valid;
-            if (mem_valid && writer) mem_valid[P.k] = 0;   // a new episode remembers nothing
+            if (mem_valid && writer && (a.twin == 0 || P.u < a.obs_per_chunk)) mem_valid[P.k] = 0;
             code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
