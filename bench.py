@@ -20,15 +20,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
-# copy kernel of known size); see profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/tabx_tick_<workload>.md: (WRITE_SIZE KiB x 1.0 + FETCH_SIZE KiB x 2.0) x 1024
-    "c3_16384env_10v10": int((487593.9 + 2.0 * 30643.8) * 1024),
-    "c4_65536env_5v5": int((442496.7 + 2.0 * 27411.2) * 1024),
-    "c5_1024env_64v64": int((1056009.0 + 2.0 * 9745.0) * 1024),
-    "c2_4096env_5v5": int((27636.9 + 2.0 * 4070.6) * 1024),
-}
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the fused tick as the committed rocprofv3 summary of that workload
+    states them (`profiles/tabx_tick_<workload>.md`, line `traffic_bytes_per_launch: N (commit C)`:
+    FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy).  They
+    are measurements of the commit named there, not of this run: None if there is no summary."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"tabx_tick_{workload}.md")
+    try:
+        m = re.search(r"traffic_bytes_per_launch:\s*(\d+)\s*\(commit\s+(\w+)\)", open(path).read())
+    except OSError:
+        return None, None
+    if not m:
+        return None, None
+    return int(m.group(1)), {"file": os.path.relpath(path, ROOT), "commit": m.group(2)}
 
 
 def algorithmic_bytes_per_env(N: int, D: int, Z: int) -> int:
@@ -65,16 +70,53 @@ def cpu_baseline(w, I, scenario: dict, sample_envs: int, ticks: int) -> dict:
     single_ticks = max(1, ticks // 4)
     dt1 = run(0, E, single_ticks)
     single = E * N * single_ticks / dt1
-    cores = max(1, min(16, os.cpu_count() or 1, E))
+    # one thread per core of this job's CPU share: the GPU machines export it as OMP_NUM_THREADS (a
+    # one-GPU job may use 16 of the host's cores, whatever os.cpu_count() shows); else every core
+    host_cores = os.cpu_count() or 1
+    share = int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or host_cores
+    cores = max(1, min(share, host_cores, E))
     bounds = [E * k // cores for k in range(cores + 1)]
     t0 = time.perf_counter()
     with ThreadPoolExecutor(cores) as pool:     # the checker's calls release the interpreter lock
         list(pool.map(lambda k: run(bounds[k], bounds[k + 1], ticks), range(cores)))
     dt = time.perf_counter() - t0
     return {"value": E * N * ticks / dt, "unit": "agent-steps/s", "cores": cores,
-            "kind": "oracle", "single_thread_value": single,
+            "host_cores": host_cores, "kind": "oracle", "single_thread_value": single,
             "sample": f"first {E} envs of the workload: {ticks} ticks of step+observe on "
                       f"{cores} threads ({dt:.1f} s), {single_ticks} ticks on one ({dt1:.1f} s)"}
+
+
+def time_workload(I, TabxEnv, torch, name: str, ticks: int, warmup: int) -> dict:
+    """The fused tick of one more workload, timed with HIP events on the launch stream: `ticks`
+    ticks after `warmup`, a fresh pre-generated action batch per tick."""
+    w = I.WORKLOADS[name]
+    E, N = w.num_envs, w.num_units
+    p = I.make_params(w)
+    env = TabxEnv(p, I.make_scenario(w))
+    env.reset()
+    n_act = max(1, min(ticks + warmup, (1 << 28) // (E * N)))
+    acts = [torch.from_numpy(I.actions_for_step(w.seed, s, E, N)).to("cuda:0") for s in range(n_act)]
+    stream = torch.cuda.current_stream()
+    for s in range(warmup):
+        env.step_observe(acts[s % n_act], stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for s in range(ticks):
+        env.step_observe(acts[(warmup + s) % n_act], stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert torch.isfinite(env.obs).all()
+    ms = ev0.elapsed_time(ev1) / ticks
+    B = algorithmic_bytes_per_env(N, env.D, p["max_zones"]) * E
+    gbs = B / (ms * 1e-3) / 1e9
+    return {"num_envs": E, "units_per_env": N, "obs_dim": env.D, "ticks": ticks, "warmup": warmup,
+            "ms_per_step": wall * 1e3 / ticks, "kernel_ms": ms,
+            "agent_steps_per_s": E * N * ticks / wall,
+            "algorithmic_bytes_per_launch": B, "algorithmic_GBs": gbs,
+            "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
 
 
 def main() -> int:
@@ -113,6 +155,9 @@ def main() -> int:
                          "launched on a stream of its own (reported as `pipelined`; 0 or 1: skip)")
     ap.add_argument("--policy-scan", action="store_true",
                     help="with --policy: the policy as a stage of its own in front of the step")
+    ap.add_argument("--other-workloads", type=int, default=None, metavar="TICKS",
+                    help="timed ticks for each of the other workloads (c1, c2, c4, c5) reported in "
+                         "`workloads` (default: 300 when the headline runs in its plain form; 0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (environments are independent; more GPUs "
@@ -169,10 +214,34 @@ def main() -> int:
 
     if policy and not args.separate and not args.policy_scan:
         env.prime_scripted(policy, scripted, stream)
+    # What a store stream can reach on this very box: a plain device fill of an obs-sized buffer
+    # (always measured, before the ticks; the copy, used to scale the profiler's byte counters,
+    # with --calibrate)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dst = torch.empty_like(env.obs)
+    nbytes = dst.numel() * 4
+    cal = {"bytes": nbytes}
+    jobs = [("fill", lambda: dst.fill_(1.0), nbytes)]
+    if args.calibrate:
+        src = torch.empty_like(env.obs)
+        jobs.append(("copy", lambda: dst.copy_(src), 2 * nbytes))
+    for label, fn, moved in jobs:
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for _ in range(20):
+            fn()
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / 20
+        cal[label + "_ms"] = ms
+        cal[label + "_GBs"] = moved / (ms * 1e-3) / 1e9
+    del dst
+
     for s in range(args.warmup):
         tick(s)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
     for s in range(args.steps):
@@ -229,7 +298,7 @@ def main() -> int:
 
     achieved = B_env * E / (kernel_ms * 1e-3) / 1e9
     plain = not (args.collisions or args.separate or args.policy or args.global_state)
-    traffic = MEASURED_TRAFFIC_BYTES.get(name) if plain else None     # measured for the fused tick
+    traffic, traffic_source = measured_traffic(name) if plain else (None, None)
     out = {
         "metric": "agent-steps/sec (step+observe) at 16384 envs 10v10; HBM GB/s vs peak",
         "value": E * N * args.steps / wall,
@@ -247,6 +316,7 @@ def main() -> int:
                               + ("" if n_act >= args.steps + args.warmup else ", cycled")},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": B_env * E,
                      "kernel_ms": kernel_ms,
                      "kernel_ms_median": float(np.median(rep_ms)), "kernel_ms_min": min(rep_ms),
@@ -254,30 +324,15 @@ def main() -> int:
     }
     if pipelined:
         out["pipelined"] = pipelined
-    # What a store stream can reach on this very box: a plain device fill of an obs-sized buffer
-    # (always measured; the copy, used to scale the profiler's byte counters, with --calibrate)
-    dst = torch.empty_like(env.obs)
-    nbytes = dst.numel() * 4
-    cal = {"bytes": nbytes}
-    jobs = [("fill", lambda: dst.fill_(1.0), nbytes)]
-    if args.calibrate:
-        src = torch.empty_like(env.obs)
-        jobs.append(("copy", lambda: dst.copy_(src), 2 * nbytes))
-    for label, fn, moved in jobs:
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        ev0.record(stream)
-        for _ in range(20):
-            fn()
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        ms = ev0.elapsed_time(ev1) / 20
-        cal[label + "_ms"] = ms
-        cal[label + "_GBs"] = moved / (ms * 1e-3) / 1e9
     out["calibration"] = cal
     out["roofline"]["device_fill_GBs"] = cal["fill_GBs"]
     out["roofline"]["frac_of_device_fill"] = achieved / cal["fill_GBs"]
+    # the other workloads, each as its own fused tick (hipEvent-timed; the headline stays `value`)
+    others = args.other_workloads if args.other_workloads is not None else (300 if plain and not args.workload else 0)
+    if others > 0:
+        out["workloads"] = {n: time_workload(I, TabxEnv, torch, n, min(others, I.WORKLOADS[n].steps), 50)
+                            for n in ("c1_16env_3v3", "c2_4096env_5v5", "c4_65536env_5v5",
+                                      "c5_1024env_64v64") if n != name}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, I, scenario, 1024 if N <= 32 else 32,
                                            1200 if N <= 32 else 300)

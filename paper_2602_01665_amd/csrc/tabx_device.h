@@ -12,13 +12,7 @@
 namespace tabx {
 
 constexpr int kMaxPasses = 10;     // store passes that stream one set of staged rows
-#ifndef TABX_PAD_SHIFT
-#define TABX_PAD_SHIFT 4
-#endif
-#ifndef TABX_ROTATE
-#define TABX_ROTATE 0
-#endif
-constexpr int kPadShift = TABX_PAD_SHIFT;   // staged rows: one spare 16-byte chunk after every 2^kPadShift
+constexpr int kPadShift = 4;       // staged rows: one spare 16-byte chunk after every 2^kPadShift
 
 struct PolicyArgs {
     TabxPolicy       pol;
@@ -59,6 +53,21 @@ struct KArgs {
     int       cell_pow2;
     PolicyArgs pa;
 };
+
+// Per-wavefront time stamps of an instrumented build (-DTABX_TRACE; compiled out of the product):
+// slot 0 kernel entry, 6 before the step stage, 1 after it (or after the hand-over), 2 / 3 / 4
+// observer loop start / first rows stored / loop end, 5 kernel end, 7 hardware ids.
+#ifdef TABX_TRACE
+__device__ unsigned long long g_trace[1 << 21];
+#define TABX_STAMP(slot)                                                                          \
+    do {                                                                                          \
+        if ((threadIdx.x & 63) == 0)                                                              \
+            g_trace[(((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)) & ((1 << 21) - 1)] = \
+                wall_clock64();                                                                   \
+    } while (0)
+#else
+#define TABX_STAMP(slot) do { } while (0)
+#endif
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));   // 16-byte store, 4-byte aligned
 
@@ -393,7 +402,20 @@ __device__ __forceinline__ void team_means(const Shared<WAVES> &sh, const Place 
                                            int c0, int c1, float &m0, float &m1)
 {
     float s0 = 0.0f, s1 = 0.0f;
-    for (int jj = 0; jj < N; ++jj) {
+    int jj = 0;
+    // eight terms are fetched together and then added one by one, in index order: the LDS
+    // latency is paid once per eight instead of once per term
+    for (; jj + 8 <= N; jj += 8) {
+        float2 q[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) q[k] = sh.st.share[P.base + jj + k];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            s0 = s0 + q[k].x;
+            s1 = s1 + q[k].y;
+        }
+    }
+    for (; jj < N; ++jj) {
         const float2 q = sh.st.share[P.base + jj];
         s0 = s0 + q.x;
         s1 = s1 + q.y;

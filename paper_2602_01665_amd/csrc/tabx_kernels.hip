@@ -51,6 +51,16 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     Shared<WAVES> &sh = sh_all[half];
     float *dyn_lds = dyn_all + half * a.dyn_stride;
     int *rows = twin.rows;                      // TWIN: 0, or how many wavefronts share an env group
+    TABX_STAMP(0);
+#ifdef TABX_TRACE
+    if ((threadIdx.x & 63) == 0) {
+        unsigned hw = 0, xcc = 0;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        g_trace[(((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + 7) & ((1 << 21) - 1)] =
+            ((unsigned long long)xcc << 32) | hw;
+    }
+#endif
     Place P = locate<WAVES>(a);
     Unit U = {};
     int code_u = 0;
@@ -109,6 +119,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         forced = policy_env<WAVES>(a, sh, P, U, code_u, cu, su, zd);
     }
     bool restarted = false;
+    TABX_STAMP(6);
     if (DO_STEP && lead) {
         restarted = step_env<WAVES>(a, sh, zd, rows, P, U, code_u, C, forced);
         if (TWIN) {
@@ -166,10 +177,12 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
         const int row = Zr.lane ? rows[Zr.zg] : -1;
         if (row >= 0) Zr = load_zone_regs<WAVES>(a, P, row);
     }
+    TABX_STAMP(1);
     if (SCRIPT && !DO_STEP && P.has) C.tick = a.st.t[P.e];
     ScriptLds<WAVES> *script = reinterpret_cast<ScriptLds<WAVES> *>(dyn_lds + a.script_offset);
     if (DO_OBS) observe_env<WAVES, DO_STEP, SCRIPT>(a, sh, dyn_lds, P, U, code_u, C, Zr, script, zd);
     if (DO_STEP) asm volatile("" ::"v"(C.warm));    // keeps the cache-warming load of step_env
+    TABX_STAMP(5);
 }
 
 template <int WAVES>
@@ -565,6 +578,21 @@ static int run(Mode mode, const TabxParams *p, const TabxScenario *sc, const Tab
 }
 
 } // namespace tabx
+
+#ifdef TABX_TRACE
+// Instrumented builds only: copies the first n time stamps to the host / clears them.
+extern "C" int tabx_dbg_read(void *dst, int n)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    return hipMemcpyFromSymbol(dst, HIP_SYMBOL(tabx::g_trace), (size_t)n * 8) == hipSuccess ? 0 : -1;
+}
+extern "C" int tabx_dbg_clear(void)
+{
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(tabx::g_trace)) != hipSuccess) return -1;
+    return hipMemset(p, 0, sizeof(tabx::g_trace)) == hipSuccess ? 0 : -1;
+}
+#endif
 
 extern "C" {
 

@@ -235,11 +235,10 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     // of an env group are spread over several short-lived workgroups
     const int i_begin = P.chunk * a.obs_per_chunk;
     const int i_end = (i_begin + a.obs_per_chunk < N) ? i_begin + a.obs_per_chunk : N;
+    TABX_STAMP(2);
     const int flushes = (i_end - i_begin + R - 1) / R;
-    const bool rotate = TABX_ROTATE == 2 || (TABX_ROTATE == 1 && WAVES == 2);
-    const int rot = (rotate && flushes > 0) ? (int)(((unsigned)P.grp * 37u) % (unsigned)flushes) : 0;
     for (int fl = 0; fl < flushes; ++fl) {
-    const int i0 = i_begin + R * (fl + rot < flushes ? fl + rot : fl + rot - flushes);
+    const int i0 = i_begin + R * fl;
     for (int rr = 0; rr < R; ++rr) {
         const int i = i0 + rr;
         const int oi = P.base + i;
@@ -417,7 +416,9 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             }
         }
         if (WAVES == 1) lds_barrier<WAVES>();    // two waves alternate between two staging buffers
+        if (fl == 0) TABX_STAMP(3);
     }
+    TABX_STAMP(4);
 
     if (want_vis) {
         uint64_t *const vis_mask = late_args()->vis_mask;
