@@ -33,7 +33,8 @@ class RefParams(C.Structure):
                 ("map_w", "map_h", "cell_size", "dt", "turn_rate", "lava_dps", "swamp_mult",
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
                [("zone_shapes", C.c_int), ("num_levels", C.c_int), ("level_seed", C.c_uint),
-                ("hurtbox_cone", C.c_int), ("hit_all", C.c_int), ("env_ids", _I32)]
+                ("hurtbox_cone", C.c_int), ("hit_all", C.c_int), ("dynamics", C.c_int),
+                ("move_gain", C.c_float), ("restitution", C.c_float), ("env_ids", _I32)]
 
 
 _SC_FLOAT = ("init_x", "init_y", "init_theta", "hmax", "radius", "mass", "speed", "dmg",
@@ -60,7 +61,7 @@ class RefState(C.Structure):
     _fields_ = [(n, _F) for n in _ST_FLOAT] + [("alive", _B), ("t", C.POINTER(C.c_int)),
                                                 ("phi_prev", _F)] + \
                [(n, t) for n, t, _ in _METRICS] + \
-               [(n, _I32) for n in _LEVELS]
+               [(n, _I32) for n in _LEVELS] + [("ax", _F), ("ay", _F)]
 
 
 class RefPolicy(C.Structure):
@@ -181,6 +182,9 @@ class RefEnv:
             self.st["level"] = np.zeros(E, np.int32)
             self.st["next_level"] = (np.arange(E) % L).astype(np.int32)   # first episodes
             self.st["level_draws"] = np.zeros(E, np.int32)
+        if self.p.get("dynamics", 0) == 1:            # persistent velocities: the acceleration is state
+            self.st["ax"] = np.zeros((E, N), np.float32)
+            self.st["ay"] = np.zeros((E, N), np.float32)
         self._bind_state()
         self.gstate = np.zeros((E, 16 * N + 6 * self.p["max_zones"]), np.float32)
         self.rewards = np.zeros((E, N), np.float32)
@@ -199,7 +203,9 @@ class RefEnv:
                             **({n: _ptr(self.st[n], t) for n, t, _ in _METRICS}
                                if self.metrics else {}),
                             **({n: _ptr(self.st[n], _I32) for n in _LEVELS}
-                               if "level" in self.st else {}))
+                               if "level" in self.st else {}),
+                            **({n: _ptr(self.st[n], _F) for n in ("ax", "ay")}
+                               if "ax" in self.st else {}))
 
     def set_state(self, **arrays):
         """Overwrites state fields in place (hand-worked cases)."""

@@ -184,6 +184,10 @@ void reset_env(const RefParams &P, const RefScenario &S, RefState &st, int e)
         st.theta[k] = S.init_theta[u];
         st.vx[k] = 0.0f;
         st.vy[k] = 0.0f;
+        if (P.dynamics == 1) {
+            st.ax[k] = 0.0f;
+            st.ay[k] = 0.0f;
+        }
         st.hp[k] = S.enabled[u] ? S.hmax[u] : 0.0f;
         st.cd[k] = 0.0f;
         st.reveal[k] = 0.0f;
@@ -233,6 +237,28 @@ inline bool role_allows(float dmg_i, int team_i, int team_j)
     return dmg_i < 0.0f ? (team_i == team_j) : (team_i != team_j);
 }
 
+/* Contact of two circular bodies (App. A "Collision detection and resolution", circle to
+ * circle): penetration depth pen = r_i + r_j - |p_j - p_i| and the normal from i to j;
+ * coincident centres separate along x, the lower index to the left. */
+struct Contact { float nx, ny, pen; };
+Contact body_contact(const RefScenario &S, const std::vector<float> &px, const std::vector<float> &py,
+                     int i, int j)
+{
+    Contact c;
+    float dx = px[j] - px[i];
+    float dy = py[j] - py[i];
+    float dist = std::sqrt((dx * dx) + (dy * dy));
+    c.pen = (S.radius[i] + S.radius[j]) - dist;
+    if (dist > 0.0f) {
+        c.nx = dx / dist;
+        c.ny = dy / dist;
+    } else {               /* coincident centres: separate along x by index */
+        c.nx = (i < j) ? 1.0f : -1.0f;
+        c.ny = 0.0f;
+    }
+    return c;
+}
+
 void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
               const unsigned char *act, float *rewards, unsigned char *dones,
               double *min_margin)
@@ -256,6 +282,12 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
         v = st.reveal[k] - P.dt;
         st.reveal[k] = v > 0.0f ? v : 0.0f;
         if (!alive0[u]) continue;
+        if (P.dynamics == 1) {
+            /* explicit Euler, in the passage's order: the velocity from the current
+             * acceleration first, then the position from that velocity */
+            st.vx[k] = st.vx[k] + st.ax[k] * P.dt;
+            st.vy[k] = st.vy[k] + st.ay[k] * P.dt;
+        }
         float x = st.x[k] + st.vx[k] * P.dt;
         float y = st.y[k] + st.vy[k] * P.dt;
         bool oob = (x < 0.0f) || (x > P.map_w) || (y < 0.0f) || (y > P.map_h);
@@ -274,32 +306,62 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
      * exist.  A kinematic body (same passage: exempt from the response) is one whose mass is
      * +infinity: it gives way to nobody, a body of finite mass gives way to it for the whole
      * corrected depth, and two kinematic bodies leave each other alone.  The impulse part of
-     * the paper's response changes velocities only, and the action stage rewrites every
-     * velocity later in the same tick, so it has no effect under this kinematic reading and
-     * is not modelled. */
+     * the paper's response changes velocities only; in the kinematic mode the action stage
+     * rewrites every velocity later in the same tick, so it is evaluated only with persistent
+     * velocities (dynamics = 1, below). */
     if (P.collision_alpha > 0.0f) {
         std::vector<float> px(N), py(N), ax(N, 0.0f), ay(N, 0.0f);
         for (int u = 0; u < N; ++u) {
             px[u] = st.x[b + u];
             py[u] = st.y[b + u];
         }
+        /* Impulse response (same passage; only with persistent velocities, dynamics = 1): for
+         * every pair that interpenetrates (depth > 0, the slop applies to the position
+         * correction only) the relative velocity v_j - v_i is projected onto the normal n
+         * (from i to j).  A pair that is already separating (projection > 0) gets no impulse.
+         * Otherwise the impulse magnitude is (1 + e) * (-v_rel.n) / (1/m_i + 1/m_j) and unit i's
+         * velocity changes by it times 1/m_i, away from j.  A kinematic body (infinite mass,
+         * inverse mass 0) is exempt; its partner bounces off it as off a wall.  Jacobi style
+         * like the correction: all pairs on the velocities after the kinematic update, unit i
+         * adding its changes in ascending partner index. */
+        if (P.dynamics == 1) {
+            std::vector<float> pvx(N), pvy(N), dvx(N, 0.0f), dvy(N, 0.0f);
+            for (int u = 0; u < N; ++u) {
+                pvx[u] = st.vx[b + u];
+                pvy[u] = st.vy[b + u];
+            }
+            for (int i = 0; i < N; ++i) {
+                if (!S.enabled[i]) continue;
+                const float inv_i = 1.0f / S.mass[i];          /* 0 for a kinematic body */
+                if (inv_i == 0.0f) continue;
+                for (int j = 0; j < N; ++j) {
+                    if (j == i || !S.enabled[j]) continue;
+                    const Contact ct = body_contact(S, px, py, i, j);
+                    if (!(ct.pen > 0.0f)) continue;
+                    const float nx = ct.nx, ny = ct.ny;
+                    float rvx = pvx[j] - pvx[i];
+                    float rvy = pvy[j] - pvy[i];
+                    float vn = (rvx * nx) + (rvy * ny);
+                    if (vn > 0.0f) continue;                   /* separating: correction only */
+                    const float inv_j = 1.0f / S.mass[j];
+                    float jimp = ((1.0f + P.restitution) * (0.0f - vn)) / (inv_i + inv_j);
+                    dvx[i] = dvx[i] - ((jimp * inv_i) * nx);
+                    dvy[i] = dvy[i] - ((jimp * inv_i) * ny);
+                }
+            }
+            for (int u = 0; u < N; ++u) {
+                if (!S.enabled[u]) continue;
+                st.vx[b + u] = pvx[u] + dvx[u];
+                st.vy[b + u] = pvy[u] + dvy[u];
+            }
+        }
         for (int i = 0; i < N; ++i) {
             if (!S.enabled[i]) continue;
             for (int j = 0; j < N; ++j) {
                 if (j == i || !S.enabled[j]) continue;
-                float dx = px[j] - px[i];
-                float dy = py[j] - py[i];
-                float dist = std::sqrt((dx * dx) + (dy * dy));
-                float pen = (S.radius[i] + S.radius[j]) - dist;
+                const Contact ct = body_contact(S, px, py, i, j);
+                const float pen = ct.pen, nx = ct.nx, ny = ct.ny;
                 if (!(pen > P.collision_slop)) continue;
-                float nx, ny;
-                if (dist > 0.0f) {
-                    nx = dx / dist;
-                    ny = dy / dist;
-                } else {               /* coincident centres: separate along x by index */
-                    nx = (i < j) ? 1.0f : -1.0f;
-                    ny = 0.0f;
-                }
                 const bool kinematic_i = std::isinf(S.mass[i]);
                 const bool kinematic_j = std::isinf(S.mass[j]);
                 float share;
@@ -322,16 +384,35 @@ void step_env(const RefParams &P, const RefScenario &bank, RefState &st, int e,
     const float dtheta = P.turn_rate * P.dt;
     for (int u = 0; u < N; ++u) {
         const int k = b + u;
-        st.vx[k] = 0.0f;
-        st.vy[k] = 0.0f;
+        /* the velocity the unit wants: its current speed along a move action, else none */
+        float wx = 0.0f, wy = 0.0f;
         if (alive0[u]) {
             const int a = act[k];
             const float sp = st.cur_speed[k];
-            if (a == ACT_XP) st.vx[k] = sp;
-            else if (a == ACT_YP) st.vy[k] = sp;
-            else if (a == ACT_XM) st.vx[k] = -sp;
-            else if (a == ACT_YM) st.vy[k] = -sp;
-            else if (a == ACT_ROT_L) {
+            if (a == ACT_XP) wx = sp;
+            else if (a == ACT_YP) wy = sp;
+            else if (a == ACT_XM) wx = -sp;
+            else if (a == ACT_YM) wy = -sp;
+        }
+        if (P.dynamics == 1) {
+            /* persistent velocity: the action sets the acceleration the next physics stage
+             * integrates; what is not alive neither moves nor accelerates */
+            if (alive0[u]) {
+                st.ax[k] = (wx - st.vx[k]) * P.move_gain;
+                st.ay[k] = (wy - st.vy[k]) * P.move_gain;
+            } else {
+                st.vx[k] = 0.0f;
+                st.vy[k] = 0.0f;
+                st.ax[k] = 0.0f;
+                st.ay[k] = 0.0f;
+            }
+        } else {
+            st.vx[k] = wx;
+            st.vy[k] = wy;
+        }
+        if (alive0[u]) {
+            const int a = act[k];
+            if (a == ACT_ROT_L) {
                 float th = st.theta[k] + dtheta;
                 if (th >= TWO_PI_F) th = th - TWO_PI_F;
                 st.theta[k] = th;

@@ -59,6 +59,13 @@ typedef struct RefParams {
                                    the sight cone's angle (any distance)                         */
     int   hit_all;              /* 0: a strike lands on the closest valid body in the hurtbox;
                                    1: on every valid body in it                                  */
+    int   dynamics;             /* 0: kinematic (a move sets the velocity outright, everything else
+                                   zeroes it).  1: persistent velocity: the action stage sets an
+                                   acceleration (move_gain * (wanted velocity - velocity)), the physics
+                                   stage integrates it (velocity first, then position), and colliding
+                                   bodies exchange an impulse with restitution                    */
+    float move_gain;            /* dynamics = 1: how fast the velocity follows the wanted one, per time unit */
+    float restitution;          /* dynamics = 1: coefficient of restitution e of the collision impulse       */
     const int *env_ids;         /* NULL, or [E]: the index each env has in the batch it was taken
                                    from; the random draws (level draws, heuristic policy) are
                                    keyed by it, so a sample of a large batch replays exactly     */
@@ -92,6 +99,8 @@ typedef struct RefState {
      * episode will take (refilled with a uniform draw when it is taken; the caller may
      * overwrite it), and how many draws the env has made */
     int   *level, *next_level, *level_draws;
+    /* dynamics = 1: the acceleration the last action stage set, [E][N] (NULL otherwise) */
+    float *ax, *ay;
 } RefState;
 
 int  tabx_ref_obs_dim(const RefParams *p);

@@ -282,7 +282,7 @@ __device__ __forceinline__ void load_spec(const KArgs &a, size_t k, Unit &U)
     U.cos_half = at32(a.sc.sight_cos_half, k);
     U.sight_range = at32(a.sc.sight_range, k);
     U.hurt_hw = at32(a.sc.hurt_halfwidth, k);
-    U.team = at32(a.sc.team, k) != 0;    // any non-zero byte means the adversaries
+    U.team = ((int)at32(a.sc.team, k) + 255) >> 8;    // 0 or 1: any non-zero byte means the adversaries
     U.enabled = at32(a.sc.enabled, k);
 }
 
@@ -402,20 +402,7 @@ __device__ __forceinline__ void team_means(const Shared<WAVES> &sh, const Place 
                                            int c0, int c1, float &m0, float &m1)
 {
     float s0 = 0.0f, s1 = 0.0f;
-    int jj = 0;
-    // eight terms are fetched together and then added one by one, in index order: the LDS
-    // latency is paid once per eight instead of once per term
-    for (; jj + 8 <= N; jj += 8) {
-        float2 q[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) q[k] = sh.st.share[P.base + jj + k];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            s0 = s0 + q[k].x;
-            s1 = s1 + q[k].y;
-        }
-    }
-    for (; jj < N; ++jj) {
+    for (int jj = 0; jj < N; ++jj) {
         const float2 q = sh.st.share[P.base + jj];
         s0 = s0 + q.x;
         s1 = s1 + q.y;

@@ -121,7 +121,7 @@ __global__ __launch_bounds__(64 * WAVES * (TWIN ? TWIN : 1)) void tabx_tick_kern
     bool restarted = false;
     TABX_STAMP(6);
     if (DO_STEP && lead) {
-        restarted = step_env<WAVES>(a, sh, zd, rows, P, U, code_u, C, forced);
+        restarted = step_env<WAVES, TWIN != 0>(a, sh, zd, rows, P, U, code_u, C, forced);
         if (TWIN) {
             // hand the stepped units to the other wavefronts: three 16-byte records per lane in
             // each one's row staging area, which it does not use before it has read them

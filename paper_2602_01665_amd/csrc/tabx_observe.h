@@ -236,16 +236,14 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int i_begin = P.chunk * a.obs_per_chunk;
     const int i_end = (i_begin + a.obs_per_chunk < N) ? i_begin + a.obs_per_chunk : N;
     TABX_STAMP(2);
-    const int flushes = (i_end - i_begin + R - 1) / R;
-    for (int fl = 0; fl < flushes; ++fl) {
-    const int i0 = i_begin + R * fl;
+    for (int i0 = i_begin; i0 < i_end; i0 += R) {
     for (int rr = 0; rr < R; ++rr) {
         const int i = i0 + rr;
         const int oi = P.base + i;
         const float4 A = sh.ob.pose[oi];
         const float4 B = sh.ob.reach[oi];
         const int fi = sh.seer[oi];
-        const int buf = (WAVES == 1) ? rr * Dp : (fl & 1) * Dp;
+        const int buf = (WAVES == 1) ? rr * Dp : (i & 1) * Dp;
         // offset of this unit from the observer; `dot` is its component along the heading
         const float dx = U.x - A.x;
         const float dy = U.y - A.y;
@@ -365,7 +363,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         lds_barrier<WAVES>();
 
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
-        const int buf = (WAVES == 1) ? 0 : (fl & 1) * Dp;
+        const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
         float *row = out + i0 * D;
         // the lane's chunk of pass p is 64 p chunks after its first one; staged_chunk() of a
         // multiple of 16 is linear, so the passes are a constant stride apart in LDS
@@ -416,7 +414,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
             }
         }
         if (WAVES == 1) lds_barrier<WAVES>();    // two waves alternate between two staging buffers
-        if (fl == 0) TABX_STAMP(3);
+        if (i0 == i_begin) TABX_STAMP(3);
     }
     TABX_STAMP(4);
 

@@ -39,7 +39,8 @@ __device__ __forceinline__ int advance_level(const KArgs &a, Shared<WAVES> &sh, 
 // `forced` >= 0 replaces the unit's entry of the action array (the policy stage chose it).
 // `zd`: the env's zone descriptors in LDS (elliptical zones), rewritten when the env changes
 // level.  Returns whether any env of the workgroup restarted.
-template <int WAVES>
+// SHARED: further wavefronts of the workgroup take the stepped units over and decide for some of them.
+template <int WAVES, bool SHARED = false>
 __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, float *zd,
                                          int *rows, Place &P, Unit &U, int &code_u, Carry &C,
                                          int forced)
@@ -336,7 +337,7 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             // wavefront that later decides for the unit clears its flag itself (it may set it again
             // at once, and two wavefronts' stores to one byte have no order between them)
             uint8_t *const mem_valid = late->pa.mem.mem_valid;
-            if (mem_valid && writer && (a.twin == 0 || P.u < a.obs_per_chunk)) mem_valid[P.k] = 0;
+            if (mem_valid && writer && (!SHARED || P.u < a.obs_per_chunk)) mem_valid[P.k] = 0;
             code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);

@@ -15,7 +15,8 @@ SRC = os.path.join(ROOT, "oracle", "tabx_ref.cpp")
 # the pin tests, quickest killers first
 PINS = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_edges.py",
         "tests/test_oracle_policy.py", "tests/test_oracle_levels.py",
-        "tests/test_oracle_hurtbox_variants.py", "tests/test_oracle_rollouts.py"]
+        "tests/test_oracle_hurtbox_variants.py", "tests/test_oracle_dynamics.py",
+        "tests/test_oracle_rollouts.py"]
 
 
 def test_every_planted_mistake_occurs_exactly_once_in_the_checker():
