@@ -155,6 +155,10 @@ def main() -> int:
                          "launched on a stream of its own (reported as `pipelined`; 0 or 1: skip)")
     ap.add_argument("--policy-scan", action="store_true",
                     help="with --policy: the policy as a stage of its own in front of the step")
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="keep the device busy with the calibration fill for this long before the "
+                         "ticks (the clocks of an idle GPU take tens of ms to settle; untimed, and "
+                         "no tick runs in it)")
     ap.add_argument("--other-workloads", type=int, default=None, metavar="TICKS",
                     help="timed ticks for each of the other workloads (c1, c2, c4, c5) reported in "
                          "`workloads` (default: 300 when the headline runs in its plain form; 0: skip)")
@@ -226,9 +230,13 @@ def main() -> int:
         src = torch.empty_like(env.obs)
         jobs.append(("copy", lambda: dst.copy_(src), 2 * nbytes))
     for label, fn, moved in jobs:
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
+        t_busy = time.perf_counter()
+        while True:                     # at least three, and until the device has settled
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            if label != "fill" or (time.perf_counter() - t_busy) * 1e3 >= args.settle_ms:
+                break
         ev0.record(stream)
         for _ in range(20):
             fn()

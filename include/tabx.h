@@ -120,6 +120,23 @@ typedef struct TabxParams {
      * the random draws (level bank, heuristic policy), so the parts draw what the whole batch
      * would.  Nothing else depends on it. */
     int32_t  env_id_offset;
+    /* Physics mode (App. A "Movement and kinematic update": explicit Euler, the velocity from
+     * the current acceleration, then the position; "Collision detection and resolution": impulse
+     * response).  0 (default): kinematic: a move action sets the velocity outright, any other
+     * action zeroes it, and a collision only corrects positions.  1: persistent velocity: the
+     * action stage sets the acceleration move_gain * (wanted velocity - velocity), where the
+     * wanted velocity is the unit's current speed along a move action and zero otherwise; the
+     * next tick's physics stage integrates it (v += a * dt, then p += v * dt); with body
+     * collisions on, every interpenetrating pair (depth > 0, whatever the slop) whose relative
+     * velocity along the normal n (from i to j) is not separating (v_rel.n <= 0) exchanges the
+     * impulse (1 + restitution) * (-v_rel.n) / (1/m_i + 1/m_j) along n, unit i's velocity
+     * changing by it times 1/m_i; a kinematic body (mass = +infinity) takes none.  All pairs are
+     * resolved on the velocities after the kinematic update, each unit adding its changes in
+     * ascending partner index.  Units that are not alive hold no velocity or acceleration.
+     * Needs TabxState.ax / ay. */
+    int32_t  dynamics;
+    float    move_gain;           /* per time unit; move_gain * dt in (0, 1] is sensible       */
+    float    restitution;         /* coefficient of restitution e, normally in [0, 1]          */
 } TabxParams;
 
 /* The scenario: unit specifications and zones (the unit and zone axes of the
@@ -170,6 +187,9 @@ typedef struct TabxState {
      * ticks) also writes the global state of tabx_global_state here, for centralised critics
      * that want it every tick; it costs its bytes and no second launch. */
     float   *global_state;
+    /* Required iff params->dynamics == 1, [E * N] f32: the acceleration the last action stage set
+     * (TabxParams.dynamics); tabx_reset clears it. */
+    float   *ax, *ay;
 } TabxState;
 
 /* Floats per agent observation: 16 * N + 6 * max_zones.

@@ -47,7 +47,8 @@ class TabxParams(C.Structure):
                  "reveal_time", "boundary_frac", "collision_alpha", "collision_slop")] + \
                [("zone_shapes", C.c_int32), ("num_levels", C.c_int32), ("level_seed", C.c_uint32),
                 ("hurtbox_cone", C.c_int32), ("hit_all", C.c_int32),
-                ("env_id_offset", C.c_int32)]
+                ("env_id_offset", C.c_int32), ("dynamics", C.c_int32),
+                ("move_gain", C.c_float), ("restitution", C.c_float)]
 
 
 class TabxScenario(C.Structure):
@@ -60,7 +61,7 @@ class TabxState(C.Structure):
     _fields_ = [(n, _F) for n in STATE_FLOAT] + \
                [("alive", _U8), ("t", C.POINTER(C.c_int32)), ("phi_prev", _F)] + \
                [(n, t) for n, t, _ in METRICS] + \
-               [(n, _I32) for n in LEVELS] + [("global_state", _F)]
+               [(n, _I32) for n in LEVELS] + [("global_state", _F), ("ax", _F), ("ay", _F)]
 
 
 class TabxError(RuntimeError):
@@ -264,6 +265,9 @@ class TabxEnv:
             self.st["level"] = torch.zeros(E, dtype=torch.int32, device=dev)
             self.st["next_level"] = (torch.arange(E, device=dev) % L).to(torch.int32)
             self.st["level_draws"] = torch.zeros(E, dtype=torch.int32, device=dev)
+        if self.p.get("dynamics", 0) == 1:     # persistent velocities: the acceleration is state
+            self.st["ax"] = torch.zeros(E * N, dtype=torch.float32, device=dev)
+            self.st["ay"] = torch.zeros(E * N, dtype=torch.float32, device=dev)
         # global state written by every observing call (else only by global_state())
         self.gs_live = (torch.zeros(E, self.D, dtype=torch.float32, device=dev)
                         if want_global_state else None)
@@ -287,6 +291,7 @@ class TabxEnv:
                          phi_prev=_cast(st["phi_prev"], _F),
                          **{n: _cast(metrics[n], t) for n, t, _ in METRICS if n in metrics},
                          **{n: _cast(st[n], _I32) for n in LEVELS if n in st},
+                         **{n: _cast(st[n], _F) for n in ("ax", "ay") if n in st},
                          global_state=_cast(global_state, _F))
 
     def parts(self, k: int):

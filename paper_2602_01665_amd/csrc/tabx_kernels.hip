@@ -208,6 +208,10 @@ __global__ __launch_bounds__(64 * WAVES) void tabx_reset_kernel(const KArgs a)
         spawn_unit(a, a.sc.zone_desc + (size_t)P.row * 6 * a.p.max_zones, P.row, P.ks, U, zeff);
         ratio = U.enabled ? U.hp / U.hmax : 0.0f;
         store_state(a, P.k, U);
+        if (a.p.dynamics == 1) {
+            a.st.ax[P.k] = 0.0f;
+            a.st.ay[P.k] = 0.0f;
+        }
     }
     const bool en = go && U.enabled;
     sh.st.share[P.l] = make_float2((en && U.team == 0) ? ratio : 0.0f,
@@ -291,7 +295,7 @@ static int check_params(const TabxParams *p)
     if (p->zone_shapes != 0 && p->zone_shapes != 1) return TABX_ERR_SHAPE;
     if (p->zone_shapes == 1 && (p->grid_w != 0 || p->max_zones < 1)) return TABX_ERR_SHAPE;
     if (p->num_levels < 0) return TABX_ERR_SHAPE;
-    if ((p->hurtbox_cone | p->hit_all) & ~1) return TABX_ERR_SHAPE;
+    if ((p->hurtbox_cone | p->hit_all | p->dynamics) & ~1) return TABX_ERR_SHAPE;
     if (p->env_id_offset < 0 || (int64_t)p->env_id_offset + p->num_envs > INT32_MAX)
         return TABX_ERR_SHAPE;
     if ((int64_t)p->num_levels * p->num_units > (int64_t)1 << 30) return TABX_ERR_SHAPE;
@@ -300,7 +304,8 @@ static int check_params(const TabxParams *p)
     for (float v : pos)
         if (!(v > 0.0f) || !(v < 3.0e38f)) return TABX_ERR_PARAM;
     const float fin[] = {p->turn_rate, p->lava_dps, p->swamp_mult, p->reveal_time,
-                         p->boundary_frac, p->collision_alpha, p->collision_slop};
+                         p->boundary_frac, p->collision_alpha, p->collision_slop,
+                         p->move_gain, p->restitution};
     for (float v : fin)
         if (!(v > -3.0e38f && v < 3.0e38f)) return TABX_ERR_PARAM;
     return TABX_OK;
@@ -341,7 +346,9 @@ static int check_state(const TabxParams *p, const TabxState *s)
     }
     if (!s->alive || !s->t) return TABX_ERR_NULL;
     if (!aligned(s->t, 4)) return TABX_ERR_ALIGN;
-    const void *m4[] = {s->ret_run, s->ep_count, s->ep_len, s->ep_return, s->global_state};
+    if (p->dynamics == 1 && (!s->ax || !s->ay)) return TABX_ERR_NULL;
+    const void *m4[] = {s->ret_run, s->ep_count, s->ep_len, s->ep_return, s->global_state,
+                        s->ax, s->ay};
     for (const void *q : m4)
         if (q && !aligned(q, 4)) return TABX_ERR_ALIGN;
     return TABX_OK;
@@ -738,6 +745,8 @@ int tabx_part(const TabxParams *p, const TabxScenario *sc, const TabxState *st, 
     if (pst->level_draws) pst->level_draws += e0;
     if (pst->global_state)
         pst->global_state += e0 * (16 * N + 6 * (size_t)p->max_zones);
+    if (pst->ax) pst->ax += u0;
+    if (pst->ay) pst->ay += u0;
     return TABX_OK;
 }
 

@@ -64,6 +64,13 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     const float ret_run = (ret_run_p && has) ? at32(ret_run_p, (size_t)P.e) : 0.0f;
     float bdmg = 0.0f;
     const bool writer = P.chunk == 0;      // (always: only a group's first wavefront steps)
+    // persistent velocities: the acceleration the last action stage set is part of the state
+    const bool dynamic = late->p.dynamics == 1;
+    float acx = 0.0f, acy = 0.0f;
+    if (dynamic && has) {
+        acx = at32(late->st.ax, P.k);
+        acy = at32(late->st.ay, P.k);
+    }
 
     // stage 1: cooldown / reveal timers, explicit Euler move, arena penalty + clip
     if (has && U.enabled) {
@@ -72,6 +79,10 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         v = U.reveal - dt;
         U.reveal = v > 0.0f ? v : 0.0f;
         if (alive0) {
+            if (dynamic) {             // the velocity from the acceleration first, then the position
+                U.vx = U.vx + acx * dt;
+                U.vy = U.vy + acy * dt;
+            }
             const float nx = U.x + U.vx * dt;
             const float ny = U.y + U.vy * dt;
             const bool oob = (nx < 0.0f) || (nx > a.p.map_w) || (ny < 0.0f) || (ny > a.p.map_h);
@@ -87,8 +98,14 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     if (a.p.collision_alpha > 0.0f) {
         // partner record: x, y, radius, mass (negative mass: not a body)
         sh.st.pj[P.l] = make_float4(U.x, U.y, U.radius, (has && U.enabled) ? U.mass : -1.0f);
+        // (with persistent velocities the partners' velocities travel in the next array, which
+        // the combat stage rewrites only after the barrier that ends this stage)
+        if (dynamic) sh.st.aim1[P.l] = make_float4(U.vx, U.vy, 0.0f, 0.0f);
         lds_barrier<WAVES>();
         float ax = 0.0f, ay = 0.0f;
+        float dvx = 0.0f, dvy = 0.0f;
+        const float inv_i = 1.0f / U.mass;             // 0 for a kinematic body, which takes no impulse
+        const bool bounces = dynamic && has && U.enabled && inv_i != 0.0f;
         for (int jj = 0; jj < N; ++jj) {
             const float4 J = sh.st.pj[P.base + jj];
             const float dx = J.x - U.x;
@@ -99,6 +116,21 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             // coincident centres separate along x, the lower index to the left
             const float nx = apart ? dx / dist : (P.u < jj ? 1.0f : -1.0f);
             const float ny = apart ? dy / dist : 0.0f;
+            if (dynamic) {
+                // impulse along the normal from the relative velocity, unless the pair is
+                // already separating; split by inverse mass (the slop gates the correction only)
+                const float4 V = sh.st.aim1[P.base + jj];
+                const float rvx = V.x - U.vx;
+                const float rvy = V.y - U.vy;
+                const float vn = (rvx * nx) + (rvy * ny);
+                const float inv_j = 1.0f / J.w;
+                const float jimp = ((1.0f + late->p.restitution) * (0.0f - vn)) / (inv_i + inv_j);
+                const bool hit = bounces && (pen > 0.0f) && (jj != P.u) && (J.w >= 0.0f) && !(vn > 0.0f);
+                // (subtracting a zero product leaves the finite sum unchanged)
+                const float je = hit ? jimp * inv_i : 0.0f;
+                dvx = dvx - (je * nx);
+                dvy = dvy - (je * ny);
+            }
             // a kinematic body (infinite mass) gives way to nobody; a body of finite mass
             // gives way to it for the whole corrected depth
             const float inf = __builtin_inff();
@@ -113,6 +145,10 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         if (has && U.enabled) {
             U.x = clamp_between(U.x + ax, 0.0f, a.p.map_w);
             U.y = clamp_between(U.y + ay, 0.0f, a.p.map_h);
+            if (dynamic) {
+                U.vx = U.vx + dvx;
+                U.vy = U.vy + dvy;
+            }
         }
         lds_barrier<WAVES>();          // the partner records are rewritten for the combat stage
     }
@@ -137,15 +173,27 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
     // stage 2a: movement sets next tick's velocity, rotation turns the heading now
     float cu = 1.0f, su = 0.0f;
     if (has) {
-        U.vx = 0.0f;
-        U.vy = 0.0f;
+        // the velocity the unit wants: its current speed along a move action, else none
+        float wx = 0.0f, wy = 0.0f;
         if (alive0) {
             const float sp = U.cur_speed;
-            if (act == TABX_ACT_MOVE_XP) U.vx = sp;
-            else if (act == TABX_ACT_MOVE_YP) U.vy = sp;
-            else if (act == TABX_ACT_MOVE_XM) U.vx = -sp;
-            else if (act == TABX_ACT_MOVE_YM) U.vy = -sp;
-            else if (act == TABX_ACT_ROT_LEFT) {
+            if (act == TABX_ACT_MOVE_XP) wx = sp;
+            else if (act == TABX_ACT_MOVE_YP) wy = sp;
+            else if (act == TABX_ACT_MOVE_XM) wx = -sp;
+            else if (act == TABX_ACT_MOVE_YM) wy = -sp;
+        }
+        if (dynamic) {
+            // the acceleration for the next tick's physics stage; what is not alive holds neither
+            acx = alive0 ? (wx - U.vx) * late->p.move_gain : 0.0f;
+            acy = alive0 ? (wy - U.vy) * late->p.move_gain : 0.0f;
+            U.vx = alive0 ? U.vx : 0.0f;
+            U.vy = alive0 ? U.vy : 0.0f;
+        } else {
+            U.vx = wx;
+            U.vy = wy;
+        }
+        if (alive0) {
+            if (act == TABX_ACT_ROT_LEFT) {
                 float th = U.theta + (a.p.turn_rate * dt);
                 if (th >= kTwoPi) th = th - kTwoPi;
                 U.theta = th;
@@ -339,6 +387,8 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
             uint8_t *const mem_valid = late->pa.mem.mem_valid;
             if (mem_valid && writer && (!SHARED || P.u < a.obs_per_chunk)) mem_valid[P.k] = 0;
             code_u = spawn_unit(a, zd, P.row, P.ks, U, zeff);
+            acx = 0.0f;
+            acy = 0.0f;
             ratio = U.enabled ? U.hp / U.hmax : 0.0f;
             heading_sincos(U.theta, su, cu);
         }
@@ -383,6 +433,10 @@ __device__ __forceinline__ bool step_env(const KArgs &a, Shared<WAVES> &sh, floa
         }
     }
     if (has && writer) store_state(a, P.k, U);
+    if (dynamic && has && writer) {
+        late->st.ax[P.k] = acx;
+        late->st.ay[P.k] = acy;
+    }
     C.cu = cu;
     C.su = su;
     C.ratio = ratio;

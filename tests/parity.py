@@ -36,7 +36,7 @@ def compare_state(gpu_state: dict, ref_state: dict, where="", rows=None):
     """gpu_state: numpy dict from TabxEnv.state_numpy(); rows: env indices of the GPU batch
     that correspond to the checker's envs (None = all)."""
     inexact = 0
-    for k in FLOAT_STATE:
+    for k in FLOAT_STATE + tuple(k for k in ("ax", "ay") if k in ref_state):
         g = gpu_state[k] if rows is None else gpu_state[k][rows]
         inexact += _cmp_float(k, g, ref_state[k], where)
     for k in INT_STATE + tuple(k for k in LEVEL_STATE if k in ref_state):

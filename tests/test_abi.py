@@ -160,7 +160,7 @@ def test_part_structs_advance_every_pointer(B):
             assert addr(psc, name) - addr(sc, name) == 12 * step, name
         else:
             assert addr(psc, name) - addr(sc, name) == 12 * N * (step // N if step >= N else step), name
-    unit4 = {"x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed"}
+    unit4 = {"x", "y", "vx", "vy", "theta", "hp", "cd", "reveal", "cur_speed", "ax", "ay"}
     size = {"alive": N, "t": 4, "phi_prev": 4, "ret_run": 4, "ep_count": 4, "ep_len": 4,
             "ep_return": 4, "ep_win": 1, "ep_first_kill": 1, "level": 4, "next_level": 4,
             "level_draws": 4, "global_state": 4 * (16 * N + 6 * Z)}

@@ -229,6 +229,20 @@ def test_rollout_with_body_collisions(name, E, steps, fused):
     assert dones > 0
 
 
+@pytest.mark.parametrize("name,E,steps", [("c1_16env_3v3", 16, 100), ("c3_16384env_10v10", 48, 120),
+                                          ("c5_1024env_64v64", 2, 40)])
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+@pytest.mark.parametrize("alpha,e", [(0.8, 0.5), (0.0, 1.0)], ids=["colliding", "passing"])
+def test_rollout_with_persistent_velocities(name, E, steps, fused, alpha, e):
+    """The optional physics mode in which the action sets an acceleration and colliding bodies
+    exchange an impulse (velocities and accelerations are compared as state)."""
+    _say(f"[gpu] persistent velocities: {name} E={E} fused={fused} alpha={alpha} e={e}")
+    inexact, dones = _rollout(I.WORKLOADS[name], E, steps, fused, max_steps=40, dynamics=1,
+                              move_gain=2.0, restitution=e, collision_alpha=alpha,
+                              collision_slop=0.01)
+    assert dones > 0
+
+
 @pytest.mark.parametrize("team_size,zones,E", [(3, 4, 37), (10, 8, 40), (10, 16, 9), (40, 6, 3)])
 @pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
 def test_rollout_with_elliptical_zones(team_size, zones, E, fused):
@@ -241,7 +255,8 @@ def test_rollout_with_elliptical_zones(team_size, zones, E, fused):
 
 
 @pytest.mark.parametrize("kinematic", [False, True], ids=["finite", "kinematic"])
-def test_collisions_in_a_crowd_of_mixed_bodies(kinematic):
+@pytest.mark.parametrize("dynamics", [0, 1], ids=["kinematic_mode", "persistent_velocity"])
+def test_collisions_in_a_crowd_of_mixed_bodies(kinematic, dynamics):
     names = list(I.ROSTER)
     rng = np.random.default_rng(9)
     units = [dict(unit=names[k % 9], team=k % 2, x=float(rng.uniform(10, 22)),
@@ -262,9 +277,9 @@ def test_collisions_in_a_crowd_of_mixed_bodies(kinematic):
         sc["mass"][:, 2] = np.inf
         sc["mass"][::2, 3] = np.inf
     w = I.Workload("crowd", E, 15, 32.0, 0, "none", 1.0, "iid", steps=80, seed=77)
-    _say(f"[gpu] collisions in a crowd of 30 mixed bodies, kinematic={kinematic}")
+    _say(f"[gpu] collisions in a crowd of 30 mixed bodies, kinematic={kinematic} dynamics={dynamics}")
     inexact, dones = _rollout(w, E, 80, True, scenario=sc, max_steps=30, collision_alpha=0.5,
-                              collision_slop=0.05)
+                              collision_slop=0.05, dynamics=dynamics, move_gain=3.0, restitution=0.8)
     assert dones > 0
 
 

@@ -33,6 +33,13 @@ def _draw_config(seed):
     over = dict(max_steps=int(rng.choice([9, 17, 30])),
                 hit_all=int(rng.random() < 0.3), hurtbox_cone=int(rng.random() < 0.3),
                 collision_alpha=float(rng.choice([0.0, 0.0, 0.8])))
+    # (a stream of its own, so that the configurations drawn above stay what they were)
+    rng2 = np.random.default_rng([4712, seed])
+    if rng2.random() < 0.35:           # persistent velocities, with whatever collision setting was drawn
+        over.update(dynamics=1, move_gain=float(rng2.choice([1.0, 2.0, 4.0])),
+                    restitution=float(rng2.choice([0.0, 0.5, 1.0])))
+        if rng2.random() < 0.5:
+            over["collision_alpha"] = 0.8
     levels = int(rng.choice([0, 0, 3, 7]))
     form = str(rng.choice(["fused", "separate", "scripted"]))
     return w, E, over, levels, form
