@@ -140,6 +140,29 @@ def test_every_roster_unit_and_role_mix():
         assert hist[5] > 0
 
 
+def test_units_that_hold_several_roles():
+    """Fast Rangers (Ranger and Assassin), fast Healers (Healer, Ranger and Assassin), fast plain
+    units, and a Healer just below the Ranger threshold, on both teams."""
+    E = 48
+    w = I.Workload("multi_role_policy", E, 8, 40.0, 20, "iid", 0.6, "iid", steps=120, seed=4242)
+    sc = I.make_scenario(w, E)
+    rows = [("archer", dict(speed=1.6)), ("healer", dict(speed=1.6)), ("farmer", dict(speed=1.6)),
+            ("healer", dict(range=9.9)), ("archer", {}), ("assassin", dict(range=10.0)),
+            ("deadeye", dict(speed=1.4)), ("farmer", {})]
+    for u in range(w.num_units):
+        name, over = rows[u % len(rows)]
+        vals = dict(zip(("hmax", "radius", "mass", "speed", "dmg", "range", "cooldown"), I.ROSTER[name]))
+        vals.update(over)
+        for k, v in vals.items():
+            sc[k][:, u] = np.float32(v)
+        sc["hurt_halfwidth"][:, u] = np.float32(vals["radius"])
+    for tier, fused in (("expert", False), ("advanced", True)):
+        _say(f"[gpu] policy with multi-role units, tier {tier}")
+        hist, dones = _policy_rollout(w, E, 120, tier, "both", scenario=sc, fused=fused, max_steps=90)
+        _say(f"[gpu]   action histogram {hist.tolist()} episodes ended {dones}")
+        assert hist[5] > 0 and hist[1:5].sum() > 0
+
+
 def test_ragged_and_padded_units():
     for team_size, disabled in [(1, 0), (7, 2), (33, 4), (50, 9)]:
         w = I.Workload(f"ragged_policy_{team_size}", 5, team_size, 40.0, 20, "iid", 0.6, "iid",

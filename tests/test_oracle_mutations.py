@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "tabx_ref.cpp")
 # the pin tests, quickest killers first
 PINS = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_edges.py",
-        "tests/test_oracle_policy.py", "tests/test_oracle_levels.py",
+        "tests/test_oracle_policy.py", "tests/test_oracle_policy_roles.py", "tests/test_oracle_levels.py",
         "tests/test_oracle_hurtbox_variants.py", "tests/test_oracle_dynamics.py",
         "tests/test_oracle_rollouts.py"]
 
