@@ -352,6 +352,11 @@ typedef struct TabxLaunchInfo {
     int32_t wavefronts_per_env_group;/* wavefronts that share those envs (1, 2 or 4)          */
     int32_t rows_per_flush;          /* observation rows of an env staged before a flush      */
     int32_t dynamic_lds_bytes;
+    /* the machine the launch shapes are tuned for: compare with the device's own properties */
+    int32_t assumed_compute_units;            /* 256                                         */
+    int32_t assumed_lds_per_cu_bytes;         /* 160 KB                                      */
+    int32_t assumed_lds_per_workgroup_bytes;  /* 64 KB: the most a launch takes per workgroup */
+    int32_t assumed_wavefront_lanes;          /* 64                                          */
 } TabxLaunchInfo;
 int tabx_launch_info(const TabxParams *params, int call, TabxLaunchInfo *info);
 

@@ -142,7 +142,10 @@ def tabx_part(params: TabxParams, scenario: TabxScenario, state: TabxState, firs
 class TabxLaunchInfo(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("workgroups", "threads_per_workgroup", "envs_per_workgroup",
                                           "wavefronts_per_env_group", "rows_per_flush",
-                                          "dynamic_lds_bytes")]
+                                          "dynamic_lds_bytes", "assumed_compute_units",
+                                          "assumed_lds_per_cu_bytes",
+                                          "assumed_lds_per_workgroup_bytes",
+                                          "assumed_wavefront_lanes")]
 
 
 CALLS = {"reset": 0, "step": 1, "observe": 2, "step_observe": 3, "heuristic_actions": 4,

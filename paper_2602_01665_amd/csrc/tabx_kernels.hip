@@ -279,6 +279,14 @@ __global__ __launch_bounds__(256) void tabx_global_state_kernel(const KArgs a, f
 
 // ------------------------------------------------------------------ host side
 
+// The machine the launch shapes below are tuned for (MI355X, gfx950).  tabx_launch_info reports
+// them, so that a caller, or a test that runs on the device, can hold them against the
+// properties the device itself reports.
+constexpr int kComputeUnits = 256;
+constexpr int kLdsPerCuBytes = 160 * 1024;          // a CU's LDS, shared by its resident workgroups
+constexpr int kLdsPerWorkgroupBytes = 64 * 1024;    // the most one workgroup may take
+constexpr int kWavefrontLanes = 64;
+
 enum Mode { MODE_RESET, MODE_STEP, MODE_OBSERVE, MODE_STEP_OBSERVE, MODE_POLICY,
             MODE_POLICY_STEP_OBSERVE, MODE_SCRIPTED_STEP_OBSERVE };
 
@@ -493,7 +501,8 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
     if (waves == 1 && N >= 4) {
         const int per = ((N + 1) / 2 + R - 1) / R * R;
         const int num_groups = (p->num_envs + G - 1) / G;
-        const bool small_batch = num_groups <= 2048;             // under one residency round
+        // under one residency round (eight single-wavefront workgroups per CU)
+        const bool small_batch = num_groups <= 8 * kComputeUnits;
         // eight or more flushes, and a short step stage
         const bool long_chain = N >= 16 * R / 2 && !(p->collision_alpha > 0.0f);
         if (per < N && mode == MODE_OBSERVE) {
@@ -510,7 +519,7 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
             const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) * ((1 << kPadShift) + 1) / (1 << kPadShift) + 64;
             const size_t lds4 = 4 * (staged + sizeof(Shared<1>)) + sizeof(TwinShared);
             if (mode == MODE_STEP_OBSERVE && N >= 16 * R && p->zone_shapes == 0 &&
-                lds4 <= 60 * 1024) {
+                lds4 <= kLdsPerWorkgroupBytes - 4 * 1024) {
                 a.twin = 4;
                 a.obs_per_chunk = ((N + 3) / 4 + R - 1) / R * R;
             }
@@ -776,6 +785,10 @@ int tabx_launch_info(const TabxParams *p, int call, TabxLaunchInfo *info)
     info->wavefronts_per_env_group = waves * (a.twin ? a.twin : 1);
     info->rows_per_flush = a.rows_per_flush;
     info->dynamic_lds_bytes = mode == MODE_RESET ? 0 : (int32_t)(staged ? lds.dyn_bytes : lds.step_bytes);
+    info->assumed_compute_units = kComputeUnits;
+    info->assumed_lds_per_cu_bytes = kLdsPerCuBytes;
+    info->assumed_lds_per_workgroup_bytes = kLdsPerWorkgroupBytes;
+    info->assumed_wavefront_lanes = kWavefrontLanes;
     return TABX_OK;
 }
 

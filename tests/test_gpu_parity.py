@@ -594,3 +594,20 @@ def test_calls_can_be_captured_into_a_graph():
         # unrelated eager work between the replays
         _ = (eager.obs * 2).sum().item()
     assert int(eager.metrics["ep_count"].sum()) > 0
+
+
+def test_launch_shapes_assume_the_device_that_is_there():
+    """The launch-shape heuristics are tuned for a machine of 256 CUs with 160 KB of LDS each,
+    64 KB per workgroup at most, 64-lane wavefronts: the device must be that machine."""
+    import torch
+    from paper_2602_01665_amd import binding as B
+    info = B.tabx_launch_info(B.make_params(I.make_params(I.WORKLOADS[I.HEADLINE])), "step_observe")
+    props = torch.cuda.get_device_properties(0)
+    assert props.multi_processor_count == info["assumed_compute_units"]
+    assert props.warp_size == info["assumed_wavefront_lanes"]
+    # (the most the planner lets one workgroup take: the device must allow at least that)
+    assert props.shared_memory_per_block >= info["assumed_lds_per_workgroup_bytes"]
+    if hasattr(props, "shared_memory_per_multiprocessor"):
+        assert props.shared_memory_per_multiprocessor == info["assumed_lds_per_cu_bytes"]
+    _say(f"[gpu] device: {props.multi_processor_count} CUs, {props.shared_memory_per_block} B LDS per workgroup, "
+         f"{getattr(props, 'shared_memory_per_multiprocessor', None)} B per CU, {props.warp_size} lanes")
