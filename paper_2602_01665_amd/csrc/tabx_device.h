@@ -12,7 +12,6 @@
 namespace tabx {
 
 constexpr int kMaxPasses = 10;     // store passes that stream one set of staged rows
-constexpr int kPadShift = 4;       // staged rows: one spare 16-byte chunk after every 2^kPadShift
 
 struct PolicyArgs {
     TabxPolicy       pol;

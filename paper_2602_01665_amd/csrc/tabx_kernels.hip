@@ -370,14 +370,16 @@ static LdsPlan plan_lds(Mode mode, KArgs &a)
     // dynamic LDS: the staged rows (G rows for a single wavefront, two alternating one-row
     // buffers for a two-wave workgroup)
     const size_t rows_staged = WAVES == 1 ? (size_t)a.envs_per_block * a.rows_per_flush : 2;
+    // (the two alternating buffers of a two-wave workgroup are whole 64-byte groups apart)
+    const size_t pitch = WAVES == 1 ? (size_t)a.row_pitch : (size_t)((a.row_pitch + 15) / 16 * 16);
     // ... rounded up to whole store passes, which read their 16 bytes per lane unconditionally
-    size_t dyn_floats = rows_staged * a.row_pitch;
-    const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? a.row_pitch : 0);
+    size_t dyn_floats = rows_staged * pitch;
+    const size_t pass_floats = (size_t)a.copy_passes * 64 * WAVES * 4 + (WAVES == 2 ? pitch : 0);
     if (dyn_floats < pass_floats) dyn_floats = pass_floats;
     // (wavefronts that take over another one's step receive three 16-byte records per lane here)
     if (a.twin && dyn_floats < 3 * 64 * 4) dyn_floats = 3 * 64 * 4;
-    // ... with one spare 16-byte chunk after every 16 (see staged_chunk)
-    dyn_floats = 4 * ((dyn_floats + 3) / 4 + (((dyn_floats + 3) / 4) >> kPadShift) + 1);
+    // ... in whole 64-byte groups (staged_chunk permutes the chunks of a group among themselves)
+    dyn_floats = (dyn_floats + 15) / 16 * 16;
     // ... followed, for elliptical zones, by the zone descriptors of the workgroup's envs
     const size_t zdesc_floats = a.zdesc_staged ? (size_t)a.envs_per_block * 6 * a.p.max_zones : 0;
     // ... and by the bidding area of scripted units that decide in the observe stage
@@ -516,7 +518,7 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
             // 91.7 us at 0.45 GB of rows per tick; fewer than four flushes each costs more than
             // it saves: N = 16 with four, 92 -> 124 us)
             // (as long as four staging areas fit the 64 KB of LDS a workgroup may take)
-            const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) * ((1 << kPadShift) + 1) / (1 << kPadShift) + 64;
+            const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) + 64;
             const size_t lds4 = 4 * (staged + sizeof(Shared<1>)) + sizeof(TwinShared);
             if (mode == MODE_STEP_OBSERVE && N >= 16 * R && p->zone_shapes == 0 &&
                 lds4 <= kLdsPerWorkgroupBytes - 4 * 1024) {
@@ -525,7 +527,9 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
             }
         }
     }
-    a.copy_passes = waves == 1 ? (G * R * cpr + 63) / 64 : ((cpr + 1) / 2 + 63) / 64;
+    // (two-wave envs: each wavefront streams one half of a row, both halves whole 64-byte groups)
+    const int half = ((cpr / 2) + 3) & ~3, rest = ((cpr + 3) & ~3) - half;
+    a.copy_passes = waves == 1 ? (G * R * cpr + 63) / 64 : ((half > rest ? half : rest) + 63) / 64;
     return waves;
 }
 

@@ -63,8 +63,20 @@ __device__ __forceinline__ ZoneRegs load_zone_regs(const KArgs &a, const Place &
     return Z;
 }
 
-// Where 16-byte chunk c of the staged row images lives in LDS.
-__device__ __forceinline__ int staged_chunk(int c) { return c + (c >> kPadShift); }
+// Where 16-byte chunk c of a set of staged row images lives in LDS (c counts from the start of
+// the set): the four chunks of every aligned 64-byte group are permuted by the group's index
+// (XOR with bits 3..4 of c).  Measured on gfx950 (SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE of
+// one-pattern kernels): a 16-byte write of 64 lanes takes 8 cycles when every 8 consecutive lanes
+// hit 8 different 16-byte slots modulo 128 bytes; the unit blocks that neighbouring lanes write
+// are 64 bytes apart, which unpermuted puts every other lane on the same slot (32 cycles; 16
+// with one spare chunk per 16; 8 with this permutation).  A 16-byte read takes 4 cycles only
+// if lane t reads chunk base + t, 8 as soon as a spare chunk interrupts the run and 12 if the
+// lanes of a group read it in permuted order.  So the store passes read the physical chunks in
+// lane order and undo the permutation on the way out: lane t's chunk goes to the place of
+// logical chunk staged_chunk(t) in HBM, which is in the same 64-byte group, so every store
+// instruction still writes whole lines.  The map is its own inverse, and staged_chunk(c + 32 k)
+// = staged_chunk(c) + 32 k.
+__device__ __forceinline__ int staged_chunk(int c) { return c ^ ((c >> 3) & 3); }
 
 // LDS of the scripted units that decide their next action inside the observe stage: per
 // deciding unit the smallest bids for "target" and "nearest enemy" and the "something to
@@ -105,10 +117,8 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     const int envs_left = P.grp < a.num_groups ? a.p.num_envs - P.grp * G : 0;
     const int envs_here = envs_left < G ? envs_left : G;
 
-    // Blocks of 16 floats written by neighbouring lanes are 64 bytes apart, which would put every
-    // fourth lane on the same LDS banks; one spare 16-byte chunk after every 16 spreads them.
     float4 *stage = reinterpret_cast<float4 *>(stg);
-    const bool blocks_aligned = (Dp & 15) == 0;  // every block then lies within one group of 16 chunks
+    const bool blocks_aligned = (Dp & 15) == 0;  // every block is then one aligned 64-byte group
 
     lds_barrier<WAVES>();                        // the step stage is done with the LDS union
 
@@ -169,25 +179,30 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
     int valid[kMaxPasses];
     // two-wave workgroups (one env, one row per flush): each wavefront streams one contiguous half
     // of the row, 64 chunks per pass
-    const int half_row = (CPR + 1) >> 1;
+    // (both halves are whole 64-byte groups, so that the permutation stays within a half)
+    const int half_row = ((CPR >> 1) + 3) & ~3;
+    const int row_chunks = (CPR + 3) & ~3;         // pitch of the two alternating row buffers
+    // the PHYSICAL chunk the lane reads in pass 0; it holds logical chunk staged_chunk(first_chunk)
     const int first_chunk = WAVES == 2 ? wv * half_row + lane : P.l;
     if (WAVES == 2) {
         const bool whole = (D & 3) == 0;
-        const int end = wv == 0 ? half_row : CPR;
-        int q = first_chunk;
+        const int end = wv == 0 ? half_row : row_chunks;
+        int phys = first_chunk;
+        int q = staged_chunk(first_chunk);
 #pragma unroll
         for (int p = 0; p < kMaxPasses; ++p) {
             const int left = D - 4 * q;
             const int vm = (whole || left >= 4) ? 15 : ((1 << (left > 0 ? left : 0)) - 1);
-            valid[p] = (q < end && envs_here > 0) ? vm : 0;
+            valid[p] = (phys < end && q < CPR && envs_here > 0) ? vm : 0;
             dst_off[p] = (unsigned)(4 * q);
             q += 64;
+            phys += 64;
         }
     } else {
         const int RC = R * CPR;                    // chunks per env slot and flush
         const bool whole = (D & 3) == 0;           // no row ends inside a chunk (always so if R > 1)
         int tg = 0;                                // env slot of chunk t
-        int q = P.l;                               // chunk within the env's R staged rows
+        int q = staged_chunk(P.l);                 // chunk within the env's R staged rows
         while (q >= RC) {                          // (RC >= 64 for all but tiny rows)
             q -= RC;
             tg += 1;
@@ -243,7 +258,9 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         const float4 A = sh.ob.pose[oi];
         const float4 B = sh.ob.reach[oi];
         const int fi = sh.seer[oi];
-        const int buf = (WAVES == 1) ? rr * Dp : (i & 1) * Dp;
+        // two-wave workgroups alternate between two row buffers; a single wavefront stages R rows
+        const int base = (WAVES == 1) ? 0 : (i & 1) * row_chunks;
+        const int buf = (WAVES == 1) ? rr * Dp : 0;
         // offset of this unit from the observer; `dot` is its component along the heading
         const float dx = U.x - A.x;
         const float dy = U.y - A.y;
@@ -320,17 +337,25 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 gs[3] = f4u{q3.x, q3.y, q3.z, q3.w};
             }
             const int cb = (buf + blk_row0 + 16 * blk) >> 2;       // first 16-byte chunk of the block
+            // (written as 128-bit vector values: as four-member structs the last chunk has been
+            // seen to go out as four separate dwords, each a many-way bank conflict)
+            typedef float v4 __attribute__((ext_vector_type(4)));
+            v4 *vstage = reinterpret_cast<v4 *>(stg);
+            const v4 w0 = {q0.x, q0.y, q0.z, q0.w}, w1 = {q1.x, q1.y, q1.z, q1.w};
+            const v4 w2 = {q2.x, q2.y, q2.z, q2.w}, w3 = {q3.x, q3.y, q3.z, q3.w};
             if (blocks_aligned) {
-                float4 *d = stage + staged_chunk(cb);
-                d[0] = q0;
-                d[1] = q1;
-                d[2] = q2;
-                d[3] = q3;
+                // (cb is a multiple of 4: the block's chunks are permuted among themselves)
+                v4 *d = vstage + base + cb;
+                const int sw = (cb >> 3) & 3;
+                d[sw] = w0;
+                d[1 ^ sw] = w1;
+                d[2 ^ sw] = w2;
+                d[3 ^ sw] = w3;
             } else {
-                stage[staged_chunk(cb)] = q0;
-                stage[staged_chunk(cb + 1)] = q1;
-                stage[staged_chunk(cb + 2)] = q2;
-                stage[staged_chunk(cb + 3)] = q3;
+                vstage[base + staged_chunk(cb)] = w0;
+                vstage[base + staged_chunk(cb + 1)] = w1;
+                vstage[base + staged_chunk(cb + 2)] = w2;
+                vstage[base + staged_chunk(cb + 3)] = w3;
             }
         }
         if (zone_lane) {
@@ -343,7 +368,7 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
                 const float shift = __int_as_float((xb & zsx[k]) | (yb & zsy[k]));
                 zo[k] = __int_as_float(__float_as_int(zval[k] - shift) & en);
             }
-            stage[staged_chunk((buf + zone_dst0) >> 2)] = make_float4(zo[0], zo[1], zo[2], zo[3]);
+            stage[base + staged_chunk((buf + zone_dst0) >> 2)] = make_float4(zo[0], zo[1], zo[2], zo[3]);
             if (want_gs && i == 0) {
                 // ... and the zone slots with absolute centres are its tail
                 float *gz = late_args()->st.global_state + (size_t)(P.grp * G + zg) * D + 16 * N + 4 * zc;
@@ -363,12 +388,10 @@ __device__ __forceinline__ void observe_env(const KArgs &a, Shared<WAVES> &sh, f
         lds_barrier<WAVES>();
 
         // stream the finished rows: LDS chunk -> one 16-byte store, row order, 1 KB per instruction
-        const int buf = (WAVES == 1) ? 0 : (i0 & 1) * Dp;
         float *row = out + i0 * D;
-        // the lane's chunk of pass p is 64 p chunks after its first one; staged_chunk() of a
-        // multiple of 16 is linear, so the passes are a constant stride apart in LDS
-        const float4 *src = stage + staged_chunk((buf >> 2) + first_chunk);
-        constexpr int PASS_STRIDE = 64 + (64 >> kPadShift);     // 64 chunks further, with their spare chunks
+        // the lane reads physical chunk first_chunk + 64 p in pass p: whole runs, in lane order
+        const float4 *src = stage + ((WAVES == 1) ? 0 : (i0 & 1) * row_chunks) + first_chunk;
+        constexpr int PASS_STRIDE = 64;
         if (D == Dp) {
             // every chunk is whole: fetch all passes from LDS first, then issue the stores
             float4 v[kMaxPasses];
