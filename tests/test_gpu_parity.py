@@ -511,6 +511,73 @@ def test_full_size_every_env(name, ticks):
     _say(f"[gpu]   all {ticks} ticks bit-identical, {dones} episodes ended")
 
 
+def test_full_size_headline_shape_with_dense_combat():
+    """The headline launch shape (16384 envs, 10v10, rectangle terrain, 8 zone slots) with a
+    fragile, fast-firing roster on an arena of 16 x 16 (health and cooldowns at a twentieth), where
+    uniformly random actions kill: episodes end by elimination, so the kill, first-kill, win and
+    restart paths run all over the full-size grid (with the benchmark's own roster every episode
+    of random play ends by truncation).  Every env, every field, every tick against the checker,
+    bit for bit."""
+    import dataclasses
+    import torch
+    from tests.helpers import ShardedRef
+    from tests.parity import FLOAT_STATE, INT_STATE, METRIC_FLOAT, METRIC_INT
+    from paper_2602_01665_amd.binding import TabxEnv
+    w = dataclasses.replace(I.WORKLOADS["c3_16384env_10v10"], name="c3_dense_combat", map_size=16.0)
+    E, N = w.num_envs, w.num_units
+    ticks = 140
+    _say(f"[gpu] full size, every env, dense combat: E={E} N={N} ticks={ticks}")
+    sc = I.make_scenario(w)
+    sc["hmax"] = (sc["hmax"] * np.float32(0.05)).astype(np.float32)
+    sc["cooldown"] = (sc["cooldown"] * np.float32(0.05)).astype(np.float32)
+    ref = ShardedRef(w, lambda n: I.make_params(w, n), sc)
+    gpu = TabxEnv(I.make_params(w), sc, want_metrics=True)
+    assert B_launch_is_headline(gpu)
+    ref.reset()
+    gpu.reset()
+
+    def same(t, want):
+        want = torch.from_numpy(np.ascontiguousarray(want))
+        if want.dtype in (torch.uint64,):
+            want = want.view(torch.int64)
+        return torch.equal(t.reshape(-1).view(torch.uint8), want.to(t.device).reshape(-1).view(torch.uint8))
+
+    for s in range(ticks):
+        a = I.actions_for_step(w.seed, s, E, N)
+        gpu.step_observe(torch.from_numpy(a).to("cuda:0"))
+        ref.tick(a)
+        where = f"dense combat every env tick {s}: "
+        assert same(gpu.obs, ref.obs), where + "obs"
+        for k in FLOAT_STATE + INT_STATE:
+            assert same(gpu.st[k], ref.state(k)), where + k
+        for k in METRIC_FLOAT + METRIC_INT:
+            assert same(gpu.metrics[k], ref.state(k)), where + k
+        assert same(gpu.rewards, ref.output("rewards")), where + "rewards"
+        assert same(gpu.dones, ref.output("dones")), where + "dones"
+        assert same(gpu.vis, ref.output("vis").view(np.int64)), where + "vis_mask"
+    count = gpu.metrics["ep_count"].cpu().numpy()
+    length = gpu.metrics["ep_len"].cpu().numpy()
+    win = gpu.metrics["ep_win"].cpu().numpy()
+    first = gpu.metrics["ep_first_kill"].cpu().numpy()
+    ended = count > 0
+    _say(f"[gpu]   envs with a finished episode {int(ended.sum())}, ended early "
+         f"{int((length[ended] < 256).sum())}, allied wins {int(win[ended].sum())}, first kills "
+         f"{np.bincount(first[ended].astype(np.int64), minlength=4).tolist()}")
+    # eliminations, not truncations; both outcomes; each kind of first kill
+    assert ended.sum() > E // 8 and (length[ended] < 256).all()
+    assert 0 < win[ended].sum() < ended.sum()
+    assert (np.bincount(first[ended].astype(np.int64), minlength=4)[1:3] > 0).all()
+
+
+def B_launch_is_headline(gpu):
+    """The dense-combat batch is launched like the headline workload (two wavefronts per group of
+    three envs, two rows per flush)."""
+    from paper_2602_01665_amd import binding as B
+    head = B.tabx_launch_info(B.make_params(I.make_params(I.WORKLOADS[I.HEADLINE])), "step_observe")
+    mine = B.tabx_launch_info(gpu.params, "step_observe")
+    return head == mine
+
+
 def test_observation_tensor_beyond_two_giga_floats():
     """1.44 million 5v5 envs: the observation tensor has more than 2^31 floats (9.2 GB), so every
     row offset must be computed in 64 bits; sampled envs from both ends and from behind the 2^31
