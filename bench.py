@@ -134,6 +134,9 @@ def main() -> int:
     ap.add_argument("--collisions", action="store_true",
                     help="switch the optional body-collision correction on (alpha 0.8, slop 0.01); "
                          "not part of the headline tick")
+    ap.add_argument("--dynamics", action="store_true",
+                    help="persistent velocities with the collision impulse (TabxParams.dynamics = 1, "
+                         "move_gain 2, restitution 0.5; implies --collisions); not the headline tick")
     ap.add_argument("--separate", action="store_true",
                     help="time tabx_step + tabx_observe as two launches instead of the fused one")
     ap.add_argument("--reps", type=int, default=5,
@@ -182,7 +185,12 @@ def main() -> int:
     name = args.workload or I.HEADLINE
     w = I.WORKLOADS[name]
     E, N = w.num_envs, w.num_units
-    p = I.make_params(w, **(dict(collision_alpha=0.8) if args.collisions else {}))
+    over = {}
+    if args.collisions or args.dynamics:
+        over.update(collision_alpha=0.8)
+    if args.dynamics:
+        over.update(dynamics=1, move_gain=2.0, restitution=0.5)
+    p = I.make_params(w, **over)
     scenario = I.make_scenario(w)
     env = TabxEnv(p, scenario, want_global_state=args.global_state)
     env.reset()
@@ -305,7 +313,7 @@ def main() -> int:
                      "frac_of_hbm_peak": B_env * E * args.steps / best / 1e9 / HBM_PEAK_GBS}
 
     achieved = B_env * E / (kernel_ms * 1e-3) / 1e9
-    plain = not (args.collisions or args.separate or args.policy or args.global_state)
+    plain = not (args.collisions or args.dynamics or args.separate or args.policy or args.global_state)
     traffic, traffic_source = measured_traffic(name) if plain else (None, None)
     out = {
         "metric": "agent-steps/sec (step+observe) at 16384 envs 10v10; HBM GB/s vs peak",
@@ -317,7 +325,8 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": name, "num_envs": E, "units_per_env": N, "obs_dim": env.D,
                    "launch": "separate step+observe" if args.separate else "fused step_observe",
-                   "body_collisions": bool(args.collisions),
+                   "body_collisions": bool(args.collisions or args.dynamics),
+                   "persistent_velocities": bool(args.dynamics),
                    "scripted_adversaries": args.policy,
                    "global_state_every_tick": bool(args.global_state),
                    "actions": f"{n_act} pre-generated seeded uniform action batches on the device"

@@ -122,6 +122,15 @@ WORKLOADS = {
 WORKLOADS["c3e_16384env_10v10_ellipses"] = Workload(
     "c3e_16384env_10v10_ellipses", 16384, 10, 64.0, 0, "ellipses", 1.0, "ratio",
     role_counts=(4, 3, 3), max_zones=8, steps=1000, seed=20260213)
+# shapes that launch four wavefronts per env group (32 and more units per env, one-wavefront
+# envs): the headline's terrain and zones with larger teams, sized to about the same 0.45 GB of
+# observation rows per tick; not benchmark configurations either
+WORKLOADS["n32_6144env_16v16"] = Workload(
+    "n32_6144env_16v16", 6144, 16, 64.0, 64, "rects", 1.0, "ratio", role_counts=(6, 5, 5),
+    max_zones=8, steps=500, seed=20260216)
+WORKLOADS["n64_1536env_32v32"] = Workload(
+    "n64_1536env_32v32", 1536, 32, 64.0, 64, "rects", 1.0, "ratio", role_counts=(12, 10, 10),
+    max_zones=8, steps=500, seed=20260232)
 HEADLINE = "c3_16384env_10v10"
 
 
