@@ -484,9 +484,9 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
     // Long-lived wavefronts make a long tail at the end of the launch, and a wavefront's chain
     // of flushes is the latency floor of a small batch.  Where that matters the observers of an
     // env group are split between several wavefronts:
-    //  - a stand-alone observe uses two workgroups per group (each loads the group's units and
-    //    writes half of its rows): measured -3 ... -9 % on the packed-env kernels, +5 % with
-    //    two-wave envs, which therefore do not split;
+    //  - a stand-alone observe uses several workgroups per group (each loads the group's units
+    //    and writes its share of the rows): up to -14 % on the packed-env kernels (below), +5 %
+    //    with two-wave envs, which therefore do not split;
     //  - a launch that also steps cannot (the second workgroup would need the state after the
     //    first one's step), but the wavefronts of ONE workgroup can: the first one runs the step
     //    stage and hands the stepped units to the others through LDS (see the kernel); all of
@@ -508,8 +508,17 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
         // eight or more flushes, and a short step stage
         const bool long_chain = N >= 16 * R / 2 && !(p->collision_alpha > 0.0f);
         if (per < N && mode == MODE_OBSERVE) {
-            a.obs_per_chunk = per;
-            a.obs_chunks = (N + per - 1) / per;
+            // about four flushes per workgroup, one workgroup more for short chains (c3: ten
+            // flushes over 3 workgroups 91.7 us, over 2: 95.3, 5: 100.3, one: 106.4; c4: five
+            // flushes over 3: 73.6 us, 2: 76.8, one: 84.4; 16v16: sixteen over 4: 85 us, 2: 92.7,
+            // 8: 89.4; 32v32: thirty-two over 8: 80.7 us, 4: 88, 2: 92.8); at most two with zone
+            // descriptors to stage per workgroup (elliptical zones: 95.2 us with 2, 96.9 with 3)
+            const int flushes = (N + R - 1) / R;
+            int share = (flushes + 3) / 4 + (flushes < 8 ? 1 : 0);
+            if (share > 8) share = 8;
+            if (share > 2 && p->zone_shapes == 1) share = 2;
+            a.obs_per_chunk = ((N + share - 1) / share + R - 1) / R * R;
+            a.obs_chunks = (N + a.obs_per_chunk - 1) / a.obs_per_chunk;
         } else if (per < N && ((mode == MODE_STEP_OBSERVE && (small_batch || long_chain)) ||
                                (mode == MODE_SCRIPTED_STEP_OBSERVE && small_batch))) {
             a.obs_per_chunk = per;
