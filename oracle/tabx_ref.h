@@ -21,7 +21,12 @@
  * the heuristic policy branch by branch on hand-placed units, its tier table
  * against the paper's; the level bank's queue semantics and an identity bank
  * against the plain scenario; the hurtbox variants by hand and by a float64
- * brute force of one tick's health; tests/test_oracle_mutations.py plants 196
+ * brute force of one tick's health; the collision correction and, with
+ * persistent velocities, the relaxation towards the wanted velocity and the
+ * restitution impulse against closed forms (equal masses head-on, 50 : 1
+ * masses, a kinematic partner, a separating pair) and conserved momentum; the
+ * policy again from its passage with units that hold several roles at once;
+ * tests/test_oracle_mutations.py plants 196
  * one-line mistakes in copies of this checker and requires the pins to fail on
  * each.  The heuristic's numbers the paper does
  * not give (half-range standoff, arrival radius, the hash behind its random

@@ -387,7 +387,7 @@ static LdsPlan plan_lds(Mode mode, KArgs &a)
     const size_t script_floats = mode == MODE_SCRIPTED_STEP_OBSERVE ? sizeof(ScriptLds<WAVES>) / 4 : 0;
     // (wavefronts sharing an env group: one such area each; the zone descriptors only once, behind
     // the areas, unless the wavefronts decide for scripted units and each look zones up: a
-    // workgroup of two wavefronts on c3 takes 25.3 KB, and six of them must fit a CU's 160 KB)
+    // workgroup of two wavefronts on c3 takes 23.8 KB, and six of them must fit a CU's 160 KB)
     const int sharers = a.twin ? a.twin : 1;
     const bool zshared = a.twin && mode != MODE_SCRIPTED_STEP_OBSERVE;   // the kernels' ZSHARED
     a.dyn_stride = (int)((dyn_floats + (zshared ? 0 : zdesc_even) + script_floats + 3) & ~(size_t)3);
