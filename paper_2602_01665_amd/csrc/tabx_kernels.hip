@@ -529,7 +529,12 @@ static int plan_shape(Mode mode, const TabxParams *p, KArgs &a)
             // (as long as four staging areas fit the 64 KB of LDS a workgroup may take)
             const size_t staged = (size_t)G * R * a.row_pitch * sizeof(float) + 64;
             const size_t lds4 = 4 * (staged + sizeof(Shared<1>)) + sizeof(TwinShared);
-            if (mode == MODE_STEP_OBSERVE && N >= 16 * R && p->zone_shapes == 0 &&
+            // ... or a batch of at most three env groups per CU, whose launch is one wavefront's
+            // chain from the first load to the last store (3v3 x 16 envs 9.8 -> 8.8 us, 5v5 x
+            // 4096 13.0 -> 12.2 us, 10v10 x 1024 18.8 -> 15.4 us; from five groups per CU on it
+            // costs: 5v5 x 8192 18.5 -> 21.9 us, 10v10 x 4096 33.4 -> 35.8 us)
+            const bool tiny_batch = num_groups <= 3 * kComputeUnits && N > 2 * R;
+            if (mode == MODE_STEP_OBSERVE && (N >= 16 * R || tiny_batch) && p->zone_shapes == 0 &&
                 lds4 <= kLdsPerWorkgroupBytes - 4 * 1024) {
                 a.twin = 4;
                 a.obs_per_chunk = ((N + 3) / 4 + R - 1) / R * R;

@@ -194,7 +194,7 @@ def test_plain_c_client_compiles_and_links():
 def test_launch_info_reports_the_layout_without_a_gpu(B):
     """tabx_launch_info is host-only: the shapes of the five workloads' fused ticks, and its errors."""
     from paper_2602_01665_amd import inputs as I
-    want = {"c1_16env_3v3": (10, 2, 128), "c2_4096env_5v5": (6, 2, 128),
+    want = {"c1_16env_3v3": (10, 4, 256), "c2_4096env_5v5": (6, 4, 256),
             "c3_16384env_10v10": (3, 2, 128), "c4_65536env_5v5": (6, 1, 64),
             "c5_1024env_64v64": (1, 2, 128)}
     for name, (envs, waves, threads) in want.items():

@@ -94,6 +94,33 @@ def test_rollout_matches_checker(name, E, steps, over, fused):
     assert dones > 0              # auto-reset was exercised
 
 
+FORMS = [
+    # (workload, envs, wavefronts sharing an env group in the fused tick, overrides)
+    ("c3_16384env_10v10", 700, 4, {}),                       # at most three env groups per CU
+    ("c3_16384env_10v10", 2400, 2, {}),                      # under one residency round
+    ("c3_16384env_10v10", 2400, 2, dict(collision_alpha=0.8)),
+    ("c2_4096env_5v5", 5400, 2, {}),
+    ("c4_65536env_5v5", 13000, 1, {}),                       # a full machine, five flushes
+    ("n32_6144env_16v16", 1700, 4, {}),                      # sixteen flushes
+    ("c3e_16384env_10v10_ellipses", 700, 2, {}),             # elliptical zones never take four
+]
+
+
+@pytest.mark.parametrize("name,E,sharing,over", FORMS,
+                         ids=[f"{c[0]}-{c[1]}-{c[2]}" + ("-collisions" if c[3] else "") for c in FORMS])
+def test_every_form_of_the_fused_launch(name, E, sharing, over):
+    """How many wavefronts share an env group in the fused tick depends on the batch size, the
+    number of observers and the options; each form runs here at a batch size that selects it
+    (checked against what the library says it would launch), every env against the checker."""
+    from paper_2602_01665_amd import binding as B
+    w = I.WORKLOADS[name]
+    info = B.tabx_launch_info(B.make_params(I.make_params(w, E, max_steps=20, **over)), "step_observe")
+    assert info["wavefronts_per_env_group"] == sharing, info
+    _say(f"[gpu] fused launch form: {name} E={E}, {sharing} wavefront(s) per env group {over}")
+    inexact, dones = _rollout(w, E, 45, True, max_steps=20, **over)
+    assert dones > 0
+
+
 @pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
 def test_combat_heavy_rollout(fused):
     _say(f"[gpu] dense 4v4 combat rollout fused={fused}")
