@@ -104,6 +104,9 @@ def _rollout(w, E, L, steps, fused, policy=None, curriculum=False, **override):
     ("c3_16384env_10v10", 40, 6, 120, dict(max_steps=16)),
     ("c3e_16384env_10v10_ellipses", 40, 6, 120, dict(max_steps=16)),
     ("c5_1024env_64v64", 3, 4, 60, dict(max_steps=9)),
+    # batch sizes at which the fused tick runs two wavefronts per env group, and one
+    ("c3_16384env_10v10", 2400, 6, 50, dict(max_steps=16)),
+    ("c4_65536env_5v5", 13000, 9, 50, dict(max_steps=16)),
 ], ids=lambda v: v if isinstance(v, str) else None)
 def test_level_bank_rollouts(name, E, L, steps, over, fused):
     _say(f"[gpu] level bank {name} E={E} L={L} fused={fused}")

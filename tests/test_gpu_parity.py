@@ -99,6 +99,7 @@ FORMS = [
     ("c3_16384env_10v10", 700, 4, {}),                       # at most three env groups per CU
     ("c3_16384env_10v10", 2400, 2, {}),                      # under one residency round
     ("c3_16384env_10v10", 2400, 2, dict(collision_alpha=0.8)),
+    ("c3_16384env_10v10", 2400, 2, dict(collision_alpha=0.8, dynamics=1, move_gain=2.0, restitution=0.5)),
     ("c2_4096env_5v5", 5400, 2, {}),
     ("c4_65536env_5v5", 13000, 1, {}),                       # a full machine, five flushes
     ("n32_6144env_16v16", 1700, 4, {}),                      # sixteen flushes
@@ -107,7 +108,8 @@ FORMS = [
 
 
 @pytest.mark.parametrize("name,E,sharing,over", FORMS,
-                         ids=[f"{c[0]}-{c[1]}-{c[2]}" + ("-collisions" if c[3] else "") for c in FORMS])
+                         ids=[f"{c[0]}-{c[1]}-{c[2]}" + ("-dynamics" if "dynamics" in c[3] else "-collisions" if c[3] else "")
+                              for c in FORMS])
 def test_every_form_of_the_fused_launch(name, E, sharing, over):
     """How many wavefronts share an env group in the fused tick depends on the batch size, the
     number of observers and the options; each form runs here at a batch size that selects it
